@@ -1,0 +1,195 @@
+/* lrboost -- C ABI of the low-rank bottleneck decoder-block hot path for one MI355X (gfx950).
+ *
+ * A linear map W[d_out, d_in] is replaced by  y = W_up . sigma(W_down . x)  with a rank-r
+ * bottleneck (paper Sec. 2, "Low-Rank Matrix Factorization" / "Low-Rank Activation via
+ * Auto-Encoder"; sigma = identity is the SVD variant of App. "Low-rank Training Algorithm").
+ *
+ * Conventions common to every entry point
+ *  - Every pointer is a DEVICE pointer owned by the caller unless a comment says "host".  The
+ *    library never allocates, frees or synchronises: each call validates its arguments on the
+ *    host, enqueues kernels on `stream` (a hipStream_t passed as void*, NULL = default
+ *    stream) and returns.  Scratch memory comes from the caller through (ws, ws_bytes); the
+ *    matching *_workspace_bytes() call gives the size needed.
+ *  - Matrices are row-major, activations token-major: x[T, d] with leading dimension ld (in
+ *    elements).  Weights use the [out, in] layout: W_down[r, d_in], W_up[d_out, r], dense.
+ *  - dt selects the storage type of activations, weights and gradients (LR_F32 or LR_BF16);
+ *    accumulation is always fp32.  Per-token statistics are fp32 in either case.
+ *  - LR_BF16 requires d_in, r, d_out and every leading dimension to be multiples of 8 and
+ *    every pointer 16-byte aligned (LR_EALIGN otherwise).  T is arbitrary.
+ *  - Return value: LR_OK or a negative lr_status.  Argument errors are detected before any
+ *    launch, so a failed call has enqueued nothing.  Faults inside kernels surface at the
+ *    caller's next synchronisation.  Outputs must not alias inputs.
+ *  - Weight and gamma gradients are written in grad_dt: LR_F32 (fp32 main-gradient buffers, the
+ *    usual companion of bf16 weights; always the case when dt == LR_F32) or LR_BF16 (pure bf16,
+ *    App. "Low-rank Training Algorithm", costs one more rounding).  accumulate != 0 adds them
+ *    into the given buffers instead of overwriting.  Activation gradients (dx) use dt.
+ */
+#ifndef LRBOOST_H
+#define LRBOOST_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  LR_OK = 0,
+  LR_EINVAL = -1,       /* null pointer, non-positive size, unknown enum value            */
+  LR_EUNSUPPORTED = -2, /* valid request the library cannot run (e.g. fp32 block)         */
+  LR_EWORKSPACE = -3,   /* ws is NULL or ws_bytes is smaller than *_workspace_bytes()     */
+  LR_EALIGN = -4,       /* pointer / leading-dimension / size alignment rule violated     */
+  LR_ELAUNCH = -5       /* a kernel launch was rejected by the runtime                    */
+} lr_status;
+
+typedef enum { LR_F32 = 0, LR_BF16 = 1 } lr_dtype;
+typedef enum { LR_ACT_IDENTITY = 0, LR_ACT_SILU = 1 } lr_act;
+/* LR_NORM_ONLINE: RMSNorm folded into the down-projection GEMM (sum of squares gathered
+ * inside a GEMM, 1/rms applied as a per-row scale in the epilogue; single-GPU form of the
+ * paper's Alg. 1).  LR_NORM_TWO_PASS: the unfused twin (statistic pass, normalise pass,
+ * plain GEMM), i.e. what Alg. 1 falls back to (Sec. 4.5 "Configuration").               */
+typedef enum { LR_NORM_NONE = 0, LR_NORM_TWO_PASS = 1, LR_NORM_ONLINE = 2 } lr_norm;
+
+int lr_version(void);
+/* Human-readable name of a status code; static storage, never freed. */
+const char* lr_status_string(int status);
+
+/* ---- one bottleneck layer (Sec. 2: B sigma(A x)) ------------------------------------- */
+/* y[T, d_out] = W_up . act(W_down . x);  z[T, r] (dense) receives the rank-r pre-activation,
+ * the only tensor the backward needs besides x (Sec. 4.4).                                */
+size_t lr_linear_workspace_bytes(int64_t T, int64_t d_in, int64_t r, int64_t d_out, int dt,
+                                 int backward);
+int lr_linear_fwd(const void* x, int64_t ldx, const void* w_down, const void* w_up, void* z,
+                  void* y, int64_t ldy, int64_t T, int64_t d_in, int64_t r, int64_t d_out,
+                  int act, int dt, void* ws, size_t ws_bytes, void* stream);
+/* From x, z and dy[T, d_out]: dx[T, d_in], dw_down[r, d_in], dw_up[d_out, r].              */
+int lr_linear_bwd(const void* x, int64_t ldx, const void* w_down, const void* w_up,
+                  const void* z, const void* dy, int64_t lddy, void* dx, int64_t lddx,
+                  void* dw_down, void* dw_up, int64_t T, int64_t d_in, int64_t r,
+                  int64_t d_out, int act, int dt, int grad_dt, int accumulate, void* ws,
+                  size_t ws_bytes, void* stream);
+
+/* ---- G projections sharing one input (Sec. 4.3 and App. "Linear Grouping Details") ---- */
+/* w_down_cat[G*r, d_in]: the G down-projection weights concatenated along the rank axis (one
+ * GEMM); w_up_stack[G, d_out, r]: stacked up-projection weights (one batched GEMM over the
+ * (input, weight) pairs).  Optional RMSNorm of x (Eq. 4; gamma[d_in], eps inside the root):
+ *   z_cat[T, G*r] = RMSNorm(x) . w_down_cat^T     (dense, the rank-r checkpoint)
+ *   y_g[T, d_out] = act(z_g) . w_up_g^T           at y_stack + g*y_batch_stride, ld = ldy
+ *   stat[T] (fp32) = sum_j x[t,j]^2               (written when norm != LR_NORM_NONE)
+ * gamma and stat may be NULL when norm == LR_NORM_NONE.                                     */
+size_t lr_group_workspace_bytes(int G, int64_t T, int64_t d_in, int64_t r, int64_t d_out,
+                                int dt, int backward);
+int lr_group_fwd(const void* x, int64_t ldx, const void* gamma, float eps, int norm,
+                 const void* w_down_cat, const void* w_up_stack, void* z_cat, float* stat,
+                 void* y_stack, int64_t ldy, int64_t y_batch_stride, int G, int64_t T,
+                 int64_t d_in, int64_t r, int64_t d_out, int act, int dt, void* ws,
+                 size_t ws_bytes, void* stream);
+/* dx[T, d_in] is the gradient w.r.t. the un-normalised x; dgamma[d_in] (grad_dt; ignored when
+ * norm == LR_NORM_NONE).  stat is the forward's output.                                     */
+int lr_group_bwd(const void* x, int64_t ldx, const void* gamma, float eps, int norm,
+                 const void* w_down_cat, const void* w_up_stack, const void* z_cat,
+                 const float* stat, const void* dy_stack, int64_t lddy,
+                 int64_t dy_batch_stride, void* dx, int64_t lddx, void* dgamma,
+                 void* dw_down_cat, void* dw_up_stack, int G, int64_t T, int64_t d_in,
+                 int64_t r, int64_t d_out, int act, int dt, int grad_dt, int accumulate,
+                 void* ws, size_t ws_bytes, void* stream);
+
+/* ---- the decoder block ------------------------------------------------------------------
+ * RMSNorm -> grouped low-rank Q/K/V -> causal attention -> low-rank O + residual -> RMSNorm
+ * -> grouped low-rank gate/up -> SiLU(g)*u -> low-rank down + residual.  Seven factored
+ * projections (App. "Communication volume analysis": 11dr + 3 d_ff r parameters).  Only the
+ * rank-r pre-activations are kept for the backward, which re-forwards everything wider from
+ * them and from x (Sec. 4.4).                                                              */
+typedef struct {
+  int64_t batch, seq, d_model, n_heads, head_dim;
+  int64_t ffn;     /* logical MLP width                                                    */
+  int64_t ffn_ld;  /* padded MLP width, multiple of 8, >= ffn; the pad rows/columns of the
+                      ffn-sized weights must be zero (then their gradients stay zero)      */
+  int64_t rank;
+  float eps;
+  int act;         /* lr_act at rank r                                                     */
+  int norm;        /* LR_NORM_ONLINE or LR_NORM_TWO_PASS                                   */
+  int dt;          /* LR_BF16                                                              */
+  int grad_dt;     /* dtype of the weight / gamma gradient buffers: LR_F32 or LR_BF16      */
+  int causal;      /* 1                                                                    */
+} lr_block_desc;
+
+typedef struct {
+  void* gamma1;    /* [d]                                                                  */
+  void* w_dn_qkv;  /* [3r, d]   q, k, v concatenated along the rank axis                   */
+  void* w_up_qkv;  /* [3, d, r]                                                            */
+  void* w_dn_o;    /* [r, d]                                                               */
+  void* w_up_o;    /* [d, r]                                                               */
+  void* gamma2;    /* [d]                                                                  */
+  void* w_dn_gu;   /* [2r, d]   gate, up concatenated                                      */
+  void* w_up_gu;   /* [2, ffn_ld, r]                                                       */
+  void* w_dn_d;    /* [r, ffn_ld]                                                          */
+  void* w_up_d;    /* [d, r]                                                               */
+} lr_block_params;  /* the same struct, pointing at grad_dt buffers, receives the grads    */
+
+typedef struct {
+  void* z_qkv;     /* [T, 3r]                                                              */
+  void* z_o;       /* [T, r]                                                               */
+  void* z_gu;      /* [T, 2r]                                                              */
+  void* z_d;       /* [T, r]                                                               */
+  float* s1;       /* [T] sum of squares of x                                              */
+  float* s2;       /* [T] sum of squares of h1 = x + attention branch                      */
+} lr_block_ckpt;    /* rank-r checkpoints, written by fwd, read by bwd; caller-allocated    */
+
+/* 0 when the descriptor is invalid or unsupported. */
+size_t lr_block_workspace_bytes(const lr_block_desc* desc, int backward);
+/* Bytes of all six checkpoint buffers together (information only; the caller allocates
+ * each buffer of lr_block_ckpt separately, with the shapes given above).                  */
+size_t lr_block_ckpt_bytes(const lr_block_desc* desc);
+/* desc, params, ckpt are HOST structs holding device pointers.  x, y: [T, d], dense.      */
+int lr_block_fwd(const lr_block_desc* desc, const lr_block_params* params, const void* x,
+                 void* y, const lr_block_ckpt* ckpt, void* ws, size_t ws_bytes, void* stream);
+/* x must be unchanged since the forward.  dy, dx: [T, d] dense.                           */
+int lr_block_bwd(const lr_block_desc* desc, const lr_block_params* params, const void* x,
+                 const void* dy, const lr_block_ckpt* ckpt, void* dx,
+                 const lr_block_params* grads, int accumulate, void* ws, size_t ws_bytes,
+                 void* stream);
+
+/* ---- causal multi-head attention (the sharded-safe op between the chunks, Sec. 4.2) ---- */
+/* q, k, v, o: [B*S, H*hd] token-major, head h in columns h*hd..; lse[B, H, S] fp32.
+ * bf16 only, hd = 128.                                                                    */
+int lr_attention_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
+                     int64_t ld, int64_t B, int64_t S, int64_t H, int64_t hd, int causal,
+                     int dt, void* stream);
+size_t lr_attention_bwd_workspace_bytes(int64_t B, int64_t S, int64_t H, int64_t hd);
+int lr_attention_bwd(const void* q, const void* k, const void* v, const void* o,
+                     const void* dout, const float* lse, void* dq, void* dk, void* dv,
+                     int64_t ld, int64_t B, int64_t S, int64_t H, int64_t hd, int causal,
+                     int dt, void* ws, size_t ws_bytes, void* stream);
+
+/* ---- standalone memory-bound kernels: the unfused twins of the fused epilogues ---------- */
+/* stat[t] = sum_j x[t,j]^2  (Alg. 1 line 1).                                               */
+int lr_rms_stat(const void* x, int64_t ldx, float* stat, int64_t T, int64_t d, int dt,
+                void* stream);
+/* xhat = x * gamma / sqrt(stat/d + eps)  (Eq. 4).                                          */
+int lr_rmsnorm_apply(const void* x, int64_t ldx, const void* gamma, const float* stat,
+                     float eps, void* xhat, int64_t ldo, int64_t T, int64_t d, int dt,
+                     void* stream);
+/* Reverse mode of Eq. 4: dx = (dn - n*c)/rms [+ dres], dn = dxhat*gamma, n = x/rms,
+ * c = mean_j(dn*n); dgamma_part[nparts, d] fp32 partial column sums of dxhat*n, where
+ * nparts = lr_rmsnorm_bwd_parts(T) (the caller, or lr_colsum, adds them up).  dres may be
+ * NULL.                                                                                    */
+int64_t lr_rmsnorm_bwd_parts(int64_t T);
+int lr_rmsnorm_bwd(const void* x, int64_t ldx, const void* gamma, const float* stat, float eps,
+                   const void* dxhat, int64_t lddxh, const void* dres, int64_t lddres,
+                   void* dx, int64_t lddx, float* dgamma_part, int64_t T, int64_t d, int dt,
+                   void* stream);
+/* a = act(z) elementwise on a [T, n] tensor.                                               */
+int lr_act_fwd(const void* z, int64_t ldz, void* a, int64_t lda, int64_t T, int64_t n,
+               int act, int dt, void* stream);
+/* m = SiLU(g) * u    and its reverse  dg = dm*u*SiLU'(g), du = dm*SiLU(g).                 */
+int lr_swiglu_fwd(const void* g, const void* u, void* m, int64_t ld, int64_t T, int64_t f,
+                  int dt, void* stream);
+int lr_swiglu_bwd(const void* g, const void* u, const void* dm, void* dg, void* du, int64_t ld,
+                  int64_t T, int64_t f, int dt, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LRBOOST_H */

@@ -1,0 +1,343 @@
+"""ctypes binding of liblrboost.so: argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU, passes their device pointers,
+sizes and leading dimensions through the C ABI of include/lrboost.h and returns the output
+tensors.  PyTorch is used for device memory and the current stream, nothing else: every step of
+the computation runs in the library's kernels.  There is no CPU or PyTorch fallback: if the
+library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+LR_F32, LR_BF16 = 0, 1
+LR_ACT_IDENTITY, LR_ACT_SILU = 0, 1
+LR_NORM_NONE, LR_NORM_TWO_PASS, LR_NORM_ONLINE = 0, 1, 2
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblrboost.so")
+_lib = None
+
+_vp, _i64, _int, _f32, _sz = C.c_void_p, C.c_int64, C.c_int, C.c_float, C.c_size_t
+
+
+class LrError(RuntimeError):
+    pass
+
+
+class BlockDesc(C.Structure):
+    _fields_ = [("batch", _i64), ("seq", _i64), ("d_model", _i64), ("n_heads", _i64), ("head_dim", _i64),
+                ("ffn", _i64), ("ffn_ld", _i64), ("rank", _i64), ("eps", _f32), ("act", _int), ("norm", _int),
+                ("dt", _int), ("grad_dt", _int), ("causal", _int)]
+
+
+class BlockParams(C.Structure):
+    _fields_ = [(n, _vp) for n in ("gamma1", "w_dn_qkv", "w_up_qkv", "w_dn_o", "w_up_o", "gamma2", "w_dn_gu",
+                                   "w_up_gu", "w_dn_d", "w_up_d")]
+
+
+class BlockCkpt(C.Structure):
+    _fields_ = [(n, _vp) for n in ("z_qkv", "z_o", "z_gu", "z_d", "s1", "s2")]
+
+
+PARAM_NAMES = tuple(n for n, _ in BlockParams._fields_)
+
+_SIGS = {
+    "lr_version": (_int, []),
+    "lr_status_string": (C.c_char_p, [_int]),
+    "lr_linear_workspace_bytes": (_sz, [_i64, _i64, _i64, _i64, _int, _int]),
+    "lr_linear_fwd": (_int, [_vp, _i64, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _int, _int, _vp, _sz, _vp]),
+    "lr_linear_bwd": (_int, [_vp, _i64, _vp, _vp, _vp, _vp, _i64, _vp, _i64, _vp, _vp, _i64, _i64, _i64, _i64, _int,
+                             _int, _int, _int, _vp, _sz, _vp]),
+    "lr_group_workspace_bytes": (_sz, [_int, _i64, _i64, _i64, _i64, _int, _int]),
+    "lr_group_fwd": (_int, [_vp, _i64, _vp, _f32, _int, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _int, _i64, _i64, _i64,
+                            _i64, _int, _int, _vp, _sz, _vp]),
+    "lr_group_bwd": (_int, [_vp, _i64, _vp, _f32, _int, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _vp, _i64, _vp, _vp, _vp,
+                            _int, _i64, _i64, _i64, _i64, _int, _int, _int, _int, _vp, _sz, _vp]),
+    "lr_block_workspace_bytes": (_sz, [C.POINTER(BlockDesc), _int]),
+    "lr_block_ckpt_bytes": (_sz, [C.POINTER(BlockDesc)]),
+    "lr_block_fwd": (_int, [C.POINTER(BlockDesc), C.POINTER(BlockParams), _vp, _vp, C.POINTER(BlockCkpt), _vp, _sz,
+                            _vp]),
+    "lr_block_bwd": (_int, [C.POINTER(BlockDesc), C.POINTER(BlockParams), _vp, _vp, C.POINTER(BlockCkpt), _vp,
+                            C.POINTER(BlockParams), _int, _vp, _sz, _vp]),
+    "lr_attention_fwd": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _int, _int, _vp]),
+    "lr_attention_bwd_workspace_bytes": (_sz, [_i64, _i64, _i64, _i64]),
+    "lr_attention_bwd": (_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _int, _int,
+                                _vp, _sz, _vp]),
+    "lr_rms_stat": (_int, [_vp, _i64, _vp, _i64, _i64, _int, _vp]),
+    "lr_rmsnorm_apply": (_int, [_vp, _i64, _vp, _vp, _f32, _vp, _i64, _i64, _i64, _int, _vp]),
+    "lr_rmsnorm_bwd_parts": (_i64, [_i64]),
+    "lr_rmsnorm_bwd": (_int, [_vp, _i64, _vp, _vp, _f32, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _i64, _int, _vp]),
+    "lr_act_fwd": (_int, [_vp, _i64, _vp, _i64, _i64, _i64, _int, _int, _vp]),
+    "lr_swiglu_fwd": (_int, [_vp, _vp, _vp, _i64, _i64, _i64, _int, _vp]),
+    "lr_swiglu_bwd": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _int, _vp]),
+}
+EXPORTS = tuple(_SIGS)
+
+
+def lib():
+    """Loads liblrboost.so on first use.  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise LrError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                          "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGS.items():
+            fn = getattr(L, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = L
+    return _lib
+
+
+def _check(status: int, what: str):
+    if status != 0:
+        raise LrError(f"{what} failed: {lib().lr_status_string(status).decode()}")
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return LR_F32
+    if t.dtype == torch.bfloat16:
+        return LR_BF16
+    raise LrError(f"unsupported dtype {t.dtype}")
+
+
+def _p(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ws(nbytes: int, device):
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def _rowmajor(t: torch.Tensor):
+    assert t.dim() == 2 and t.stride(1) == 1, "row-major 2-D tensor expected"
+    return t.stride(0)
+
+
+# ---- one bottleneck layer ------------------------------------------------------------------
+def lr_linear_workspace_bytes(T, d_in, r, d_out, dt, backward):
+    return lib().lr_linear_workspace_bytes(T, d_in, r, d_out, dt, int(backward))
+
+
+def lr_linear_fwd(x, w_down, w_up, act=LR_ACT_SILU):
+    """Returns (z[T, r], y[T, d_out])."""
+    T, d_in = x.shape
+    r, d_out = w_down.shape[0], w_up.shape[0]
+    dt = _dt(x)
+    z = torch.empty((T, r), dtype=x.dtype, device=x.device)
+    y = torch.empty((T, d_out), dtype=x.dtype, device=x.device)
+    nb = lr_linear_workspace_bytes(T, d_in, r, d_out, dt, 0)
+    ws = _ws(nb, x.device)
+    _check(lib().lr_linear_fwd(_p(x), _rowmajor(x), _p(w_down), _p(w_up), _p(z), _p(y), d_out, T, d_in, r, d_out, act,
+                               dt, _p(ws), nb, _stream()), "lr_linear_fwd")
+    return z, y
+
+
+def _tdt(dt):
+    return torch.float32 if dt == LR_F32 else torch.bfloat16
+
+
+def lr_linear_bwd(x, w_down, w_up, z, dy, act=LR_ACT_SILU, grads=None, grad_dt=LR_F32):
+    """Returns (dx, dw_down, dw_up).  With grads=(dw_down, dw_up) the weight grads are accumulated."""
+    T, d_in = x.shape
+    r, d_out = w_down.shape[0], w_up.shape[0]
+    dt = _dt(x)
+    dx = torch.empty((T, d_in), dtype=x.dtype, device=x.device)
+    acc = grads is not None
+    dwd, dwu = grads if acc else (torch.empty_like(w_down, dtype=_tdt(grad_dt)),
+                                  torch.empty_like(w_up, dtype=_tdt(grad_dt)))
+    nb = lr_linear_workspace_bytes(T, d_in, r, d_out, dt, 1)
+    ws = _ws(nb, x.device)
+    _check(lib().lr_linear_bwd(_p(x), _rowmajor(x), _p(w_down), _p(w_up), _p(z), _p(dy), _rowmajor(dy), _p(dx), d_in,
+                               _p(dwd), _p(dwu), T, d_in, r, d_out, act, dt, grad_dt, int(acc), _p(ws), nb, _stream()),
+           "lr_linear_bwd")
+    return dx, dwd, dwu
+
+
+# ---- G projections sharing one input ---------------------------------------------------------
+def lr_group_workspace_bytes(G, T, d_in, r, d_out, dt, backward):
+    return lib().lr_group_workspace_bytes(G, T, d_in, r, d_out, dt, int(backward))
+
+
+def lr_group_fwd(x, gamma, eps, norm, w_down_cat, w_up_stack, act=LR_ACT_SILU):
+    """Returns (z_cat[T, G*r], stat[T] fp32, y_stack[G, T, d_out])."""
+    T, d_in = x.shape
+    G, d_out, r = w_up_stack.shape
+    dt = _dt(x)
+    z = torch.empty((T, G * r), dtype=x.dtype, device=x.device)
+    stat = torch.empty((T,), dtype=torch.float32, device=x.device)
+    y = torch.empty((G, T, d_out), dtype=x.dtype, device=x.device)
+    nb = lr_group_workspace_bytes(G, T, d_in, r, d_out, dt, 0)
+    ws = _ws(nb, x.device)
+    _check(lib().lr_group_fwd(_p(x), _rowmajor(x), _p(gamma), eps, norm, _p(w_down_cat), _p(w_up_stack), _p(z),
+                              _p(stat), _p(y), d_out, T * d_out, G, T, d_in, r, d_out, act, dt, _p(ws), nb, _stream()),
+           "lr_group_fwd")
+    return z, stat, y
+
+
+def lr_group_bwd(x, gamma, eps, norm, w_down_cat, w_up_stack, z_cat, stat, dy_stack, act=LR_ACT_SILU, grads=None,
+                 grad_dt=LR_F32):
+    """Returns (dx, dgamma, dw_down_cat, dw_up_stack)."""
+    T, d_in = x.shape
+    G, d_out, r = w_up_stack.shape
+    dt = _dt(x)
+    dx = torch.empty((T, d_in), dtype=x.dtype, device=x.device)
+    acc = grads is not None
+    if acc:
+        dgamma, dwd, dwu = grads
+    else:
+        gt = _tdt(grad_dt)
+        dgamma = torch.empty((d_in,), dtype=gt, device=x.device)
+        dwd, dwu = torch.empty_like(w_down_cat, dtype=gt), torch.empty_like(w_up_stack, dtype=gt)
+    nb = lr_group_workspace_bytes(G, T, d_in, r, d_out, dt, 1)
+    ws = _ws(nb, x.device)
+    _check(lib().lr_group_bwd(_p(x), _rowmajor(x), _p(gamma), eps, norm, _p(w_down_cat), _p(w_up_stack), _p(z_cat),
+                              _p(stat), _p(dy_stack), d_out, T * d_out, _p(dx), d_in, _p(dgamma), _p(dwd), _p(dwu), G,
+                              T, d_in, r, d_out, act, dt, grad_dt, int(acc), _p(ws), nb, _stream()), "lr_group_bwd")
+    return dx, dgamma, dwd, dwu
+
+
+# ---- the decoder block -----------------------------------------------------------------------
+def make_block_desc(batch, seq, d_model, n_heads, head_dim, ffn, ffn_ld, rank, eps=1e-5, act=LR_ACT_SILU,
+                    norm=LR_NORM_ONLINE, dt=LR_BF16, grad_dt=LR_F32, causal=1):
+    return BlockDesc(batch, seq, d_model, n_heads, head_dim, ffn, ffn_ld, rank, eps, act, norm, dt, grad_dt, causal)
+
+
+def _params_struct(params: dict):
+    return BlockParams(*[C.c_void_p(params[n].data_ptr()) for n in PARAM_NAMES])
+
+
+def lr_block_workspace_bytes(desc, backward):
+    return lib().lr_block_workspace_bytes(C.byref(desc), int(backward))
+
+
+def lr_block_ckpt_bytes(desc):
+    return lib().lr_block_ckpt_bytes(C.byref(desc))
+
+
+def alloc_block_ckpt(desc, device):
+    T, r = desc.batch * desc.seq, desc.rank
+    tdt = torch.bfloat16 if desc.dt == LR_BF16 else torch.float32
+    return {
+        "z_qkv": torch.empty((T, 3 * r), dtype=tdt, device=device),
+        "z_o": torch.empty((T, r), dtype=tdt, device=device),
+        "z_gu": torch.empty((T, 2 * r), dtype=tdt, device=device),
+        "z_d": torch.empty((T, r), dtype=tdt, device=device),
+        "s1": torch.empty((T,), dtype=torch.float32, device=device),
+        "s2": torch.empty((T,), dtype=torch.float32, device=device),
+    }
+
+
+def _ckpt_struct(ck: dict):
+    return BlockCkpt(*[C.c_void_p(ck[n].data_ptr()) for n, _ in BlockCkpt._fields_])
+
+
+def lr_block_fwd(desc, params: dict, x, ckpt: dict = None, ws=None, y=None):
+    """Returns (y, ckpt).  `params` maps the lr_block_params field names to device tensors."""
+    if ckpt is None:
+        ckpt = alloc_block_ckpt(desc, x.device)
+    if y is None:
+        y = torch.empty_like(x)
+    nb = lr_block_workspace_bytes(desc, 0)
+    if nb == 0:
+        raise LrError("lr_block_workspace_bytes: invalid or unsupported block descriptor")
+    if ws is None:
+        ws = _ws(nb, x.device)
+    ps, cs = _params_struct(params), _ckpt_struct(ckpt)
+    _check(lib().lr_block_fwd(C.byref(desc), C.byref(ps), _p(x), _p(y), C.byref(cs), _p(ws), ws.numel(), _stream()),
+           "lr_block_fwd")
+    return y, ckpt
+
+
+def lr_block_bwd(desc, params: dict, x, dy, ckpt: dict, grads: dict = None, accumulate=False, ws=None, dx=None):
+    """Returns (dx, grads) with grads keyed like params."""
+    if grads is None:
+        grads = {n: torch.empty_like(params[n], dtype=_tdt(desc.grad_dt)) for n in PARAM_NAMES}
+    if dx is None:
+        dx = torch.empty_like(x)
+    nb = lr_block_workspace_bytes(desc, 1)
+    if nb == 0:
+        raise LrError("lr_block_workspace_bytes: invalid or unsupported block descriptor")
+    if ws is None:
+        ws = _ws(nb, x.device)
+    ps, cs, gs = _params_struct(params), _ckpt_struct(ckpt), _params_struct(grads)
+    _check(lib().lr_block_bwd(C.byref(desc), C.byref(ps), _p(x), _p(dy), C.byref(cs), _p(dx), C.byref(gs),
+                              int(accumulate), _p(ws), ws.numel(), _stream()), "lr_block_bwd")
+    return dx, grads
+
+
+# ---- attention -----------------------------------------------------------------------------
+def lr_attention_fwd(q, k, v, B, S, H, hd, causal=True):
+    o = torch.empty_like(q)
+    lse = torch.empty((B, H, S), dtype=torch.float32, device=q.device)
+    _check(lib().lr_attention_fwd(_p(q), _p(k), _p(v), _p(o), _p(lse), _rowmajor(q), B, S, H, hd, int(causal), _dt(q),
+                                  _stream()), "lr_attention_fwd")
+    return o, lse
+
+
+def lr_attention_bwd(q, k, v, o, dout, lse, B, S, H, hd, causal=True):
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    nb = lib().lr_attention_bwd_workspace_bytes(B, S, H, hd)
+    ws = _ws(nb, q.device)
+    _check(lib().lr_attention_bwd(_p(q), _p(k), _p(v), _p(o), _p(dout), _p(lse), _p(dq), _p(dk), _p(dv), _rowmajor(q),
+                                  B, S, H, hd, int(causal), _dt(q), _p(ws), ws.numel(), _stream()), "lr_attention_bwd")
+    return dq, dk, dv
+
+
+# ---- standalone memory-bound kernels ---------------------------------------------------------
+def lr_rms_stat(x):
+    T, d = x.shape
+    stat = torch.empty((T,), dtype=torch.float32, device=x.device)
+    _check(lib().lr_rms_stat(_p(x), _rowmajor(x), _p(stat), T, d, _dt(x), _stream()), "lr_rms_stat")
+    return stat
+
+
+def lr_rmsnorm_apply(x, gamma, stat, eps):
+    T, d = x.shape
+    out = torch.empty_like(x)
+    _check(lib().lr_rmsnorm_apply(_p(x), _rowmajor(x), _p(gamma), _p(stat), eps, _p(out), d, T, d, _dt(x), _stream()),
+           "lr_rmsnorm_apply")
+    return out
+
+
+def lr_rmsnorm_bwd(x, gamma, stat, eps, dxhat, dres=None):
+    """Returns (dx, dgamma_part[nparts, d] fp32)."""
+    T, d = x.shape
+    dx = torch.empty_like(x)
+    nparts = lib().lr_rmsnorm_bwd_parts(T)
+    part = torch.empty((max(nparts, 1), d), dtype=torch.float32, device=x.device)
+    _check(lib().lr_rmsnorm_bwd(_p(x), _rowmajor(x), _p(gamma), _p(stat), eps, _p(dxhat), _rowmajor(dxhat), _p(dres),
+                                _rowmajor(dres) if dres is not None else 0, _p(dx), d, _p(part), T, d, _dt(x),
+                                _stream()), "lr_rmsnorm_bwd")
+    return dx, part
+
+
+def lr_act_fwd(z, act=LR_ACT_SILU):
+    T, n = z.shape
+    a = torch.empty_like(z)
+    _check(lib().lr_act_fwd(_p(z), _rowmajor(z), _p(a), n, T, n, act, _dt(z), _stream()), "lr_act_fwd")
+    return a
+
+
+def lr_swiglu_fwd(g, u):
+    T, f = g.shape
+    m = torch.empty_like(g)
+    _check(lib().lr_swiglu_fwd(_p(g), _p(u), _p(m), _rowmajor(g), T, f, _dt(g), _stream()), "lr_swiglu_fwd")
+    return m
+
+
+def lr_swiglu_bwd(g, u, dm):
+    T, f = g.shape
+    dg, du = torch.empty_like(g), torch.empty_like(u)
+    _check(lib().lr_swiglu_bwd(_p(g), _p(u), _p(dm), _p(dg), _p(du), _rowmajor(g), T, f, _dt(g), _stream()),
+           "lr_swiglu_bwd")
+    return dg, du

@@ -1,0 +1,150 @@
+// Internal declarations shared by the kernel files and the C-ABI layer of lrboost.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "lrboost.h"
+
+namespace lrb {
+
+// ---------------------------------------------------------------------------------------------
+// Epilogue of C[M,N] = sum_k A(m,k) B(n,k): what happens to the fp32 accumulator tile before it
+// is rounded and stored.  Row scalars (rowa, rowb) are final per-row values, not partials.
+// ---------------------------------------------------------------------------------------------
+enum EpiKind : int {
+  EPI_STORE = 0,    // C = acc
+  EPI_DOWN = 1,     // v = acc * rho_m (rho = rsqrt(rowa/d + eps) if norm) ; C = v ; C2 = act(v)
+  EPI_UP = 2,       // v = acc + R ; C = v ; rowpart = sum_n v^2
+  EPI_ACTGRAD = 3,  // v = acc * act'(R) * rho_m ; C = v ; rowpart = sum_n v * R      (R = z)
+  EPI_NORMBWD = 4,  // v = acc - (rho_m/d) * rowb_m * R2 + R ; C = v     (R2 = x, R = residual grad)
+  EPI_PARTIAL = 5,  // fp32 store of a split-K partial: Cpart[split][M][N]
+  EPI_SWIGLU_BWD = 6  // v = acc (= dm); C = v*R2*silu'(R) (dg), C2 = v*silu(R) (du); R=g, R2=u
+};
+
+struct Epilogue {
+  int kind = EPI_STORE;
+  int act = LR_ACT_IDENTITY;
+  int use_rho = 0;            // multiply rows by rho_m
+  int stat_from_a = 0;        // rowa is gathered from the A tiles in the main loop (bf16 kernel)
+  const float* rowa = nullptr;  // [M] sum of squares
+  const float* rowb = nullptr;  // [M]
+  float inv_d = 0.f, eps = 0.f;
+  float* stat_out = nullptr;  // [M] final sum of squares, written by the n-tile 0 blocks
+  void* C2 = nullptr;
+  int64_t ldc2 = 0, sC2 = 0;
+  const void* R = nullptr;
+  int64_t ldr = 0, sR = 0;
+  const void* R2 = nullptr;
+  int64_t ldr2 = 0, sR2 = 0;
+  float* rowpart = nullptr;   // [M, rowpart_ld] per-(n-slab) partial row sums
+  int64_t rowpart_ld = 0;
+  int rowpart_off = 0;        // column offset (batched launches: g * slabs per batch)
+};
+
+struct GemmOp {
+  const void* A = nullptr;
+  const void* B = nullptr;
+  void* C = nullptr;
+  int64_t lda = 0, ldb = 0, ldc = 0;  // elements
+  int64_t sA = 0, sB = 0, sC = 0;     // batch strides, elements
+  int transA = 0, transB = 0;  // 0: operand(i,k) at p[i*ld + k]; 1: at p[k*ld + i]
+  int M = 0, N = 0, K = 0, batch = 1;
+  int splitk = 1;              // > 1: EPI_PARTIAL into fp32 C[batch][split][M][N] (ldc = N)
+  Epilogue epi;
+};
+
+// Number of n-slabs the bf16 kernel emits row partials for (rowpart_ld must be >= this * batch).
+int gemm_bf16_rowpart_slabs(int N);
+// Chooses a split-K factor for a weight-gradient GEMM with K = T.
+int gemm_bf16_pick_splitk(int M, int N, int K, int batch);
+hipError_t gemm_bf16(const GemmOp& op, hipStream_t st);
+hipError_t gemm_f32(const GemmOp& op, hipStream_t st);
+
+// ---- streaming kernels (stream_kernels.hip) ---------------------------------------------------
+hipError_t k_rms_stat(const void* x, int64_t ldx, float* stat, int64_t T, int64_t d, int dt, hipStream_t);
+hipError_t k_rmsnorm_apply(const void* x, int64_t ldx, const void* gamma, const float* stat, float eps,
+                           void* xhat, int64_t ldo, int64_t T, int64_t d, int dt, hipStream_t);
+int64_t k_rmsnorm_bwd_parts(int64_t T);
+hipError_t k_rmsnorm_bwd(const void* x, int64_t ldx, const void* gamma, const float* stat, float eps,
+                         const void* dxhat, int64_t lddxh, const void* dres, int64_t lddres, void* dx,
+                         int64_t lddx, float* dgamma_part, int64_t T, int64_t d, int dt, hipStream_t);
+hipError_t k_act_fwd(const void* z, int64_t ldz, void* a, int64_t lda, int64_t T, int64_t n, int act,
+                     int dt, hipStream_t);
+hipError_t k_swiglu_fwd(const void* g, const void* u, void* m, int64_t ld, int64_t T, int64_t f, int dt,
+                        hipStream_t);
+hipError_t k_swiglu_bwd(const void* g, const void* u, const void* dm, void* dg, void* du, int64_t ld,
+                        int64_t T, int64_t f, int dt, hipStream_t);
+// out[r, c] = in[c, r] for in[rows, cols] (ld_in) -> out[cols, rows] (ld_out)
+hipError_t k_transpose(const void* in, int64_t ld_in, void* out, int64_t ld_out, int64_t rows,
+                       int64_t cols, int dt, hipStream_t);
+// out[m] = sum_p part[m, p], p < nparts
+hipError_t k_rowsum_parts(const float* part, int64_t ld, int nparts, float* out, int64_t M, hipStream_t);
+// out[m] = sum_n a[m,n] * b[m,n]
+hipError_t k_rowdot(const void* a, int64_t lda, const void* b, int64_t ldb, float* out, int64_t M,
+                    int64_t N, int dt, hipStream_t);
+// wout[n, k] = w[n, k] * gamma[k]
+hipError_t k_scale_cols(const void* w, const void* gamma, void* wout, int64_t rows, int64_t cols, int dt,
+                        hipStream_t);
+// Sum `nsplit` fp32 partials [nsplit][count] (batch-major outside) and write / accumulate into dw.
+//   dw[i] (+)= colscale[i % cols] * sum_s part[s][i]      (colscale optional)
+// With wg_for_dgamma (the un-scaled weight) also emits dgamma_part[row_block][cols] partial sums of
+// w * sum_s part (dgamma = sum over all rows).
+hipError_t k_wgrad_finish(const float* part, int nsplit, int64_t rows, int64_t cols, void* dw,
+                          const void* colscale, const void* w_for_dgamma, float* dgamma_part,
+                          int accumulate, int dt, int out_dt, hipStream_t);
+int64_t k_wgrad_dgamma_parts(int64_t rows);
+// out[c] (+)= sum_p part[p, c]; out has dtype out_dt
+hipError_t k_colsum_parts(const float* part, int64_t nparts, int64_t cols, void* out, int accumulate,
+                          int out_dt, hipStream_t);
+
+// ---- attention (attention.hip) ---------------------------------------------------------------
+hipError_t attention_fwd_bf16(const void* q, const void* k, const void* v, void* o, float* lse, int64_t ld,
+                              int B, int S, int H, int hd, int causal, hipStream_t);
+size_t attention_bwd_ws_bytes(int B, int S, int H, int hd);
+hipError_t attention_bwd_bf16(const void* q, const void* k, const void* v, const void* o, const void* dout,
+                              const float* lse, void* dq, void* dk, void* dv, int64_t ld, int B, int S, int H,
+                              int hd, int causal, void* ws, hipStream_t);
+
+// ---------------------------------------------------------------------------------------------
+// device helpers
+// ---------------------------------------------------------------------------------------------
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t lo16) { return __uint_as_float(lo16 << 16); }
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+  // round to nearest even; NaN kept quiet
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+}
+__device__ __forceinline__ void unpack8(const uint4& q, float* v) {
+  v[0] = __uint_as_float(q.x << 16); v[1] = __uint_as_float(q.x & 0xffff0000u);
+  v[2] = __uint_as_float(q.y << 16); v[3] = __uint_as_float(q.y & 0xffff0000u);
+  v[4] = __uint_as_float(q.z << 16); v[5] = __uint_as_float(q.z & 0xffff0000u);
+  v[6] = __uint_as_float(q.w << 16); v[7] = __uint_as_float(q.w & 0xffff0000u);
+}
+__device__ __forceinline__ uint4 pack8(const float* v) {
+  uint4 q;
+  q.x = pack_bf16x2(v[0], v[1]); q.y = pack_bf16x2(v[2], v[3]);
+  q.z = pack_bf16x2(v[4], v[5]); q.w = pack_bf16x2(v[6], v[7]);
+  return q;
+}
+__device__ __forceinline__ float logistic_f(float z) { return 1.f / (1.f + __expf(-z)); }
+__device__ __forceinline__ float silu_f(float z) { return z * logistic_f(z); }
+__device__ __forceinline__ float silu_prime_f(float z) {
+  float s = logistic_f(z);
+  return s * (1.f + z * (1.f - s));
+}
+__device__ __forceinline__ float act_f(float z, int act) { return act == LR_ACT_SILU ? silu_f(z) : z; }
+__device__ __forceinline__ float act_prime_f(float z, int act) { return act == LR_ACT_SILU ? silu_prime_f(z) : 1.f; }
+
+}  // namespace lrb

@@ -1,0 +1,121 @@
+// Device-side epilogue shared by the bf16 MFMA GEMM and the fp32 GEMM: takes NV consecutive
+// accumulator columns of one output row, applies the fused elementwise work in fp32, rounds once
+// and stores.  See EpiKind in common.h for the formulas.
+#pragma once
+#include "common.h"
+
+namespace lrb {
+
+template <typename ST, int NV>
+struct VecIO;
+
+template <>
+struct VecIO<float, 1> {
+  static __device__ __forceinline__ void load(const void* p, int64_t off, float* v) { v[0] = ((const float*)p)[off]; }
+  static __device__ __forceinline__ void store(void* p, int64_t off, const float* v) { ((float*)p)[off] = v[0]; }
+};
+template <>
+struct VecIO<float, 8> {
+  static __device__ __forceinline__ void load(const void* p, int64_t off, float* v) {
+    const float4 a = *reinterpret_cast<const float4*>((const float*)p + off);
+    const float4 b = *reinterpret_cast<const float4*>((const float*)p + off + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  }
+  static __device__ __forceinline__ void store(void* p, int64_t off, const float* v) {
+    *reinterpret_cast<float4*>((float*)p + off) = make_float4(v[0], v[1], v[2], v[3]);
+    *reinterpret_cast<float4*>((float*)p + off + 4) = make_float4(v[4], v[5], v[6], v[7]);
+  }
+};
+template <>
+struct VecIO<bf16_t, 8> {
+  static __device__ __forceinline__ void load(const void* p, int64_t off, float* v) {
+    uint4 q = *reinterpret_cast<const uint4*>((const uint16_t*)p + off);
+    unpack8(q, v);
+  }
+  static __device__ __forceinline__ void store(void* p, int64_t off, const float* v) {
+    *reinterpret_cast<uint4*>((uint16_t*)p + off) = pack8(v);
+  }
+};
+
+template <>
+struct VecIO<bf16_t, 1> {
+  static __device__ __forceinline__ void load(const void* p, int64_t off, float* v) {
+    v[0] = bf16_bits_to_f32(((const uint16_t*)p)[off]);
+  }
+  static __device__ __forceinline__ void store(void* p, int64_t off, const float* v) {
+    ((uint16_t*)p)[off] = (uint16_t)f32_to_bf16_bits(v[0]);
+  }
+};
+
+// v[NV]: accumulators of row m, columns n..n+NV-1 of batch b.  rho / rowb: per-row scalars already
+// resolved by the caller (rho = 1 when unused).  Returns this thread's contribution to the row
+// partial (0 when the epilogue kind has none).
+template <typename ST, int NV, int KIND>
+__device__ __forceinline__ float epi_apply(const Epilogue& e, void* C, int64_t ldc, int64_t sC, int b, int64_t m,
+                                           int64_t n, float* v, float rho, float rowb) {
+  using IO = VecIO<ST, NV>;
+  float part = 0.f;
+  const int64_t coff = (int64_t)b * sC + m * ldc + n;
+  if constexpr (KIND == EPI_STORE) {
+    IO::store(C, coff, v);
+  } else if constexpr (KIND == EPI_DOWN) {
+#pragma unroll
+    for (int i = 0; i < NV; i++) v[i] *= rho;
+    IO::store(C, coff, v);
+    if (e.C2) {
+      float a[NV];
+#pragma unroll
+      for (int i = 0; i < NV; i++) a[i] = act_f(v[i], e.act);
+      IO::store(e.C2, (int64_t)b * e.sC2 + m * e.ldc2 + n, a);
+    }
+  } else if constexpr (KIND == EPI_UP) {
+    if (e.R) {
+      float r[NV];
+      IO::load(e.R, (int64_t)b * e.sR + m * e.ldr + n, r);
+#pragma unroll
+      for (int i = 0; i < NV; i++) v[i] += r[i];
+    }
+    IO::store(C, coff, v);
+#pragma unroll
+    for (int i = 0; i < NV; i++) part += v[i] * v[i];
+  } else if constexpr (KIND == EPI_ACTGRAD) {
+    float z[NV];
+    IO::load(e.R, (int64_t)b * e.sR + m * e.ldr + n, z);
+#pragma unroll
+    for (int i = 0; i < NV; i++) {
+      v[i] = v[i] * act_prime_f(z[i], e.act) * rho;
+      part += v[i] * z[i];
+    }
+    IO::store(C, coff, v);
+  } else if constexpr (KIND == EPI_NORMBWD) {
+    float x[NV];
+    IO::load(e.R2, (int64_t)b * e.sR2 + m * e.ldr2 + n, x);
+    const float coef = rho * e.inv_d * rowb;
+#pragma unroll
+    for (int i = 0; i < NV; i++) v[i] = v[i] - coef * x[i];
+    if (e.R) {
+      float r[NV];
+      IO::load(e.R, (int64_t)b * e.sR + m * e.ldr + n, r);
+#pragma unroll
+      for (int i = 0; i < NV; i++) v[i] += r[i];
+    }
+    IO::store(C, coff, v);
+  } else if constexpr (KIND == EPI_SWIGLU_BWD) {
+    float g[NV], u[NV], du[NV];
+    IO::load(e.R, (int64_t)b * e.sR + m * e.ldr + n, g);
+    IO::load(e.R2, (int64_t)b * e.sR2 + m * e.ldr2 + n, u);
+#pragma unroll
+    for (int i = 0; i < NV; i++) {
+      float dm = v[i];
+      du[i] = dm * silu_f(g[i]);
+      v[i] = dm * u[i] * silu_prime_f(g[i]);
+    }
+    IO::store(C, coff, v);
+    IO::store(e.C2, (int64_t)b * e.sC2 + m * e.ldc2 + n, du);
+  }
+  return part;
+}
+
+__device__ __forceinline__ float rho_of(const Epilogue& e, float sumsq) { return rsqrtf(sumsq * e.inv_d + e.eps); }
+
+}  // namespace lrb

@@ -1,0 +1,450 @@
+// Memory-bound kernels: per-token statistics, RMSNorm apply / backward, sigma at rank r, SwiGLU
+// forward / backward, transposes and the small reductions that finish weight gradients.
+// bf16 tensors move as 16-byte vectors (8 elements per lane, 1 KB per wavefront instruction);
+// fp32 tensors (precision path, arbitrary sizes) move element-wise.  All arithmetic is fp32.
+#include "epilogue.h"
+
+namespace lrb {
+namespace {
+
+template <int DT> struct St;
+template <> struct St<LR_F32> { using T = float; static constexpr int NV = 1; };
+template <> struct St<LR_BF16> { using T = bf16_t; static constexpr int NV = 8; };
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+// ---- S[t] = sum_j x[t,j]^2 : one wavefront per row ---------------------------------------------
+template <int DT>
+__global__ __launch_bounds__(256) void rms_stat_kernel(const void* x, int64_t ldx, float* stat, int64_t T, int64_t d) {
+  using S = St<DT>;
+  using IO = VecIO<typename S::T, S::NV>;
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= T) return;
+  float s = 0.f;
+  for (int64_t c = lane * S::NV; c < d; c += 64 * S::NV) {
+    float v[S::NV];
+    IO::load(x, row * ldx + c, v);
+#pragma unroll
+    for (int i = 0; i < S::NV; i++) s = fmaf(v[i], v[i], s);
+  }
+  s = wave_sum(s);
+  if (lane == 0) stat[row] = s;
+}
+
+template <int DT>
+__global__ __launch_bounds__(256) void rmsnorm_apply_kernel(const void* x, int64_t ldx, const void* gamma,
+                                                            const float* stat, float eps, void* out, int64_t ldo,
+                                                            int64_t T, int64_t d) {
+  using S = St<DT>;
+  using IO = VecIO<typename S::T, S::NV>;
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= T) return;
+  const float rho = rsqrtf(stat[row] / (float)d + eps);
+  for (int64_t c = lane * S::NV; c < d; c += 64 * S::NV) {
+    float v[S::NV], g[S::NV];
+    IO::load(x, row * ldx + c, v);
+    IO::load(gamma, c, g);
+#pragma unroll
+    for (int i = 0; i < S::NV; i++) v[i] = v[i] * g[i] * rho;
+    IO::store(out, row * ldo + c, v);
+  }
+}
+
+// ---- reverse mode of RMSNorm ----------------------------------------------------------------------
+// One workgroup owns RB consecutive rows.  Phase A: each wavefront reduces c = mean_j(dn*n) for its
+// rows.  Phase B: column super-chunks of 64*NV*IT columns; each lane keeps the column partial sums
+// of dxhat*n for its columns across the workgroup's rows, writes dx, and the four wavefronts'
+// partials are added through LDS into dgamma_part[blockIdx][.].
+constexpr int NB_RB = 64;
+constexpr int NB_IT = 4;
+
+template <int DT>
+__global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const void* x, int64_t ldx, const void* gamma,
+                                                          const float* stat, float eps, const void* dxh,
+                                                          int64_t lddxh, const void* dres, int64_t lddres, void* dx,
+                                                          int64_t lddx, float* dgpart, int64_t T, int64_t d) {
+  using S = St<DT>;
+  using IO = VecIO<typename S::T, S::NV>;
+  constexpr int NV = S::NV;
+  __shared__ float sc[NB_RB];
+  __shared__ float sred[4][64 * NV];  // one it-slice of a super-chunk at a time
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t row0 = (int64_t)blockIdx.x * NB_RB;
+  const float inv_d = 1.f / (float)d;
+  for (int r = wave; r < NB_RB; r += 4) {
+    const int64_t row = row0 + r;
+    if (row >= T) break;
+    const float rho = rsqrtf(stat[row] * inv_d + eps);
+    float s = 0.f;
+    for (int64_t c = lane * NV; c < d; c += 64 * NV) {
+      float xv[NV], gv[NV], dv[NV];
+      IO::load(x, row * ldx + c, xv);
+      IO::load(gamma, c, gv);
+      IO::load(dxh, row * lddxh + c, dv);
+#pragma unroll
+      for (int i = 0; i < NV; i++) s = fmaf(dv[i] * gv[i], xv[i] * rho, s);
+    }
+    s = wave_sum(s);
+    if (lane == 0) sc[r] = s * inv_d;
+  }
+  __syncthreads();
+  constexpr int SUPER = 64 * NV * NB_IT;
+  for (int64_t cb = 0; cb < d; cb += SUPER) {
+    float acc[NB_IT][NV];
+#pragma unroll
+    for (int it = 0; it < NB_IT; it++)
+#pragma unroll
+      for (int i = 0; i < NV; i++) acc[it][i] = 0.f;
+    for (int r = wave; r < NB_RB; r += 4) {
+      const int64_t row = row0 + r;
+      if (row >= T) break;
+      const float rho = rsqrtf(stat[row] * inv_d + eps);
+      const float c = sc[r];
+#pragma unroll
+      for (int it = 0; it < NB_IT; it++) {
+        const int64_t col = cb + (int64_t)it * 64 * NV + lane * NV;
+        if (col < d) {
+          float xv[NV], gv[NV], dv[NV], o[NV];
+          IO::load(x, row * ldx + col, xv);
+          IO::load(gamma, col, gv);
+          IO::load(dxh, row * lddxh + col, dv);
+#pragma unroll
+          for (int i = 0; i < NV; i++) {
+            const float n = xv[i] * rho;
+            o[i] = (dv[i] * gv[i] - n * c) * rho;
+            acc[it][i] = fmaf(dv[i], n, acc[it][i]);
+          }
+          if (dres) {
+            float rv[NV];
+            IO::load(dres, row * lddres + col, rv);
+#pragma unroll
+            for (int i = 0; i < NV; i++) o[i] += rv[i];
+          }
+          IO::store(dx, row * lddx + col, o);
+        }
+      }
+    }
+    // add the four wavefronts' column partials, one it-slice at a time
+#pragma unroll
+    for (int it = 0; it < NB_IT; it++) {
+#pragma unroll
+      for (int i = 0; i < NV; i++) sred[wave][lane * NV + i] = acc[it][i];
+      __syncthreads();
+      for (int e = threadIdx.x; e < 64 * NV; e += 256) {
+        const int64_t col = cb + (int64_t)it * 64 * NV + e;
+        if (col < d) dgpart[(int64_t)blockIdx.x * d + col] = sred[0][e] + sred[1][e] + sred[2][e] + sred[3][e];
+      }
+      __syncthreads();
+    }
+  }
+}
+
+// ---- elementwise on [T, n] with leading dimensions -------------------------------------------
+template <int DT>
+__global__ __launch_bounds__(256) void act_fwd_kernel(const void* z, int64_t ldz, void* a, int64_t lda, int64_t T,
+                                                      int64_t n, int act) {
+  using S = St<DT>;
+  using IO = VecIO<typename S::T, S::NV>;
+  const int64_t cpr = n / S::NV;  // vectors per row
+  const int64_t total = T * cpr;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    const int64_t t = i / cpr, c = (i % cpr) * S::NV;
+    float v[S::NV];
+    IO::load(z, t * ldz + c, v);
+#pragma unroll
+    for (int k = 0; k < S::NV; k++) v[k] = act_f(v[k], act);
+    IO::store(a, t * lda + c, v);
+  }
+}
+
+template <int DT>
+__global__ __launch_bounds__(256) void swiglu_fwd_kernel(const void* g, const void* u, void* m, int64_t ld, int64_t T,
+                                                         int64_t f) {
+  using S = St<DT>;
+  using IO = VecIO<typename S::T, S::NV>;
+  const int64_t cpr = f / S::NV, total = T * cpr;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    const int64_t off = (i / cpr) * ld + (i % cpr) * S::NV;
+    float gv[S::NV], uv[S::NV];
+    IO::load(g, off, gv);
+    IO::load(u, off, uv);
+#pragma unroll
+    for (int k = 0; k < S::NV; k++) gv[k] = silu_f(gv[k]) * uv[k];
+    IO::store(m, off, gv);
+  }
+}
+
+template <int DT>
+__global__ __launch_bounds__(256) void swiglu_bwd_kernel(const void* g, const void* u, const void* dm, void* dg,
+                                                         void* du, int64_t ld, int64_t T, int64_t f) {
+  using S = St<DT>;
+  using IO = VecIO<typename S::T, S::NV>;
+  const int64_t cpr = f / S::NV, total = T * cpr;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    const int64_t off = (i / cpr) * ld + (i % cpr) * S::NV;
+    float gv[S::NV], uv[S::NV], dv[S::NV], o1[S::NV], o2[S::NV];
+    IO::load(g, off, gv);
+    IO::load(u, off, uv);
+    IO::load(dm, off, dv);
+#pragma unroll
+    for (int k = 0; k < S::NV; k++) {
+      o1[k] = dv[k] * uv[k] * silu_prime_f(gv[k]);
+      o2[k] = dv[k] * silu_f(gv[k]);
+    }
+    IO::store(dg, off, o1);
+    IO::store(du, off, o2);
+  }
+}
+
+// ---- transpose: out[c, r] = in[r, c]; 64x64 tiles through LDS.  Output columns rows..pad_to-1
+// are written as zeros, so a transposed activation can serve as a k-contiguous GEMM operand whose
+// k extent is rounded up to the 16-byte vector.
+template <typename E>
+__global__ __launch_bounds__(256) void transpose_kernel(const E* in, int64_t ld_in, E* out, int64_t ld_out,
+                                                        int64_t rows, int64_t cols, int64_t pad_to) {
+  __shared__ E tile[64][64 + 2];
+  const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int i = ty; i < 64; i += 4) {
+    const int64_t r = r0 + i, c = c0 + tx;
+    if (r < rows && c < cols) tile[i][tx] = in[r * ld_in + c];
+  }
+  __syncthreads();
+  for (int i = ty; i < 64; i += 4) {
+    const int64_t c = c0 + i, r = r0 + tx;
+    if (c < cols) {
+      if (r < rows) out[c * ld_out + r] = tile[tx][i];
+      else if (r < pad_to) out[c * ld_out + r] = (E)0;
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void rowsum_parts_kernel(const float* part, int64_t ld, int nparts, float* out,
+                                                           int64_t M) {
+  const int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (m >= M) return;
+  float s = 0.f;
+  for (int p = 0; p < nparts; p++) s += part[m * ld + p];
+  out[m] = s;
+}
+
+template <int DT>
+__global__ __launch_bounds__(256) void rowdot_kernel(const void* a, int64_t lda, const void* b, int64_t ldb,
+                                                     float* out, int64_t M, int64_t N) {
+  using S = St<DT>;
+  using IO = VecIO<typename S::T, S::NV>;
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= M) return;
+  float s = 0.f;
+  for (int64_t c = lane * S::NV; c < N; c += 64 * S::NV) {
+    float av[S::NV], bv[S::NV];
+    IO::load(a, row * lda + c, av);
+    IO::load(b, row * ldb + c, bv);
+#pragma unroll
+    for (int i = 0; i < S::NV; i++) s = fmaf(av[i], bv[i], s);
+  }
+  s = wave_sum(s);
+  if (lane == 0) out[row] = s;
+}
+
+template <int DT>
+__global__ __launch_bounds__(256) void scale_cols_kernel(const void* w, const void* gamma, void* wout, int64_t rows,
+                                                         int64_t cols) {
+  using S = St<DT>;
+  using IO = VecIO<typename S::T, S::NV>;
+  const int64_t cpr = cols / S::NV, total = rows * cpr;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    const int64_t c = (i % cpr) * S::NV, off = (i / cpr) * cols + c;
+    float wv[S::NV], gv[S::NV];
+    IO::load(w, off, wv);
+    IO::load(gamma, c, gv);
+#pragma unroll
+    for (int k = 0; k < S::NV; k++) wv[k] *= gv[k];
+    IO::store(wout, off, wv);
+  }
+}
+
+// ---- finish a split-K weight gradient ------------------------------------------------------------
+constexpr int WF_RB = 32;  // rows per workgroup (and per dgamma partial)
+
+template <int DT, typename OT>
+__global__ __launch_bounds__(256) void wgrad_finish_kernel(const float* part, int nsplit, int64_t rows, int64_t cols,
+                                                           void* dw, const void* colscale, const void* wdg,
+                                                           float* dgpart, int accumulate) {
+  using S = St<DT>;
+  using IO = VecIO<typename S::T, S::NV>;
+  using OIO = VecIO<OT, S::NV>;
+  constexpr int NV = S::NV;
+  const int64_t c = ((int64_t)blockIdx.x * 256 + threadIdx.x) * NV;
+  if (c >= cols) return;
+  const int64_t rbeg = (int64_t)blockIdx.y * WF_RB, rend = min(rows, rbeg + WF_RB);
+  float cs[NV], dg[NV];
+#pragma unroll
+  for (int i = 0; i < NV; i++) { cs[i] = 1.f; dg[i] = 0.f; }
+  if (colscale) IO::load(colscale, c, cs);
+  const int64_t count = rows * cols;
+  for (int64_t r = rbeg; r < rend; r++) {
+    float s[NV];
+#pragma unroll
+    for (int i = 0; i < NV; i++) s[i] = 0.f;
+    for (int sp = 0; sp < nsplit; sp++) {
+      const float* p = part + (int64_t)sp * count + r * cols + c;
+#pragma unroll
+      for (int i = 0; i < NV; i++) s[i] += p[i];
+    }
+    if (wdg) {
+      float wv[NV];
+      IO::load(wdg, r * cols + c, wv);
+#pragma unroll
+      for (int i = 0; i < NV; i++) dg[i] = fmaf(wv[i], s[i], dg[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < NV; i++) s[i] *= cs[i];
+    if (accumulate) {
+      float old[NV];
+      OIO::load(dw, r * cols + c, old);
+#pragma unroll
+      for (int i = 0; i < NV; i++) s[i] += old[i];
+    }
+    OIO::store(dw, r * cols + c, s);
+  }
+  if (dgpart) {
+#pragma unroll
+    for (int i = 0; i < NV; i++) dgpart[(int64_t)blockIdx.y * cols + c + i] = dg[i];
+  }
+}
+
+template <typename OT>
+__global__ __launch_bounds__(256) void colsum_parts_kernel(const float* part, int64_t nparts, int64_t cols, void* out,
+                                                           int accumulate) {
+  using IO = VecIO<OT, 1>;
+  const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (c >= cols) return;
+  float s = 0.f;
+  for (int64_t p = 0; p < nparts; p++) s += part[p * cols + c];
+  if (accumulate) {
+    float o;
+    IO::load(out, c, &o);
+    s += o;
+  }
+  IO::store(out, c, &s);
+}
+
+inline int grid1d(int64_t total, int cap = 256 * 32) {
+  int64_t g = (total + 255) / 256;
+  if (g > cap) g = cap;
+  if (g < 1) g = 1;
+  return (int)g;
+}
+
+}  // namespace
+
+#define DISPATCH_DT(dt, KERNEL, grid, block, st, ...)                                              \
+  do {                                                                                             \
+    if ((dt) == LR_F32) hipLaunchKernelGGL(KERNEL<LR_F32>, grid, block, 0, st, __VA_ARGS__);       \
+    else hipLaunchKernelGGL(KERNEL<LR_BF16>, grid, block, 0, st, __VA_ARGS__);                     \
+    return hipGetLastError();                                                                      \
+  } while (0)
+
+hipError_t k_rms_stat(const void* x, int64_t ldx, float* stat, int64_t T, int64_t d, int dt, hipStream_t st) {
+  if (T <= 0) return hipSuccess;
+  DISPATCH_DT(dt, rms_stat_kernel, dim3((T + 3) / 4), dim3(256), st, x, ldx, stat, T, d);
+}
+hipError_t k_rmsnorm_apply(const void* x, int64_t ldx, const void* gamma, const float* stat, float eps, void* xhat,
+                           int64_t ldo, int64_t T, int64_t d, int dt, hipStream_t st) {
+  if (T <= 0) return hipSuccess;
+  DISPATCH_DT(dt, rmsnorm_apply_kernel, dim3((T + 3) / 4), dim3(256), st, x, ldx, gamma, stat, eps, xhat, ldo, T, d);
+}
+int64_t k_rmsnorm_bwd_parts(int64_t T) { return (T + NB_RB - 1) / NB_RB; }
+hipError_t k_rmsnorm_bwd(const void* x, int64_t ldx, const void* gamma, const float* stat, float eps,
+                         const void* dxhat, int64_t lddxh, const void* dres, int64_t lddres, void* dx, int64_t lddx,
+                         float* dgamma_part, int64_t T, int64_t d, int dt, hipStream_t st) {
+  if (T <= 0) return hipSuccess;
+  DISPATCH_DT(dt, rmsnorm_bwd_kernel, dim3(k_rmsnorm_bwd_parts(T)), dim3(256), st, x, ldx, gamma, stat, eps, dxhat,
+              lddxh, dres, lddres, dx, lddx, dgamma_part, T, d);
+}
+hipError_t k_act_fwd(const void* z, int64_t ldz, void* a, int64_t lda, int64_t T, int64_t n, int act, int dt,
+                     hipStream_t st) {
+  if (T <= 0 || n <= 0) return hipSuccess;
+  const int nv = dt == LR_BF16 ? 8 : 1;
+  DISPATCH_DT(dt, act_fwd_kernel, dim3(grid1d(T * (n / nv))), dim3(256), st, z, ldz, a, lda, T, n, act);
+}
+hipError_t k_swiglu_fwd(const void* g, const void* u, void* m, int64_t ld, int64_t T, int64_t f, int dt,
+                        hipStream_t st) {
+  if (T <= 0 || f <= 0) return hipSuccess;
+  const int nv = dt == LR_BF16 ? 8 : 1;
+  DISPATCH_DT(dt, swiglu_fwd_kernel, dim3(grid1d(T * (f / nv))), dim3(256), st, g, u, m, ld, T, f);
+}
+hipError_t k_swiglu_bwd(const void* g, const void* u, const void* dm, void* dg, void* du, int64_t ld, int64_t T,
+                        int64_t f, int dt, hipStream_t st) {
+  if (T <= 0 || f <= 0) return hipSuccess;
+  const int nv = dt == LR_BF16 ? 8 : 1;
+  DISPATCH_DT(dt, swiglu_bwd_kernel, dim3(grid1d(T * (f / nv))), dim3(256), st, g, u, dm, dg, du, ld, T, f);
+}
+hipError_t k_transpose(const void* in, int64_t ld_in, void* out, int64_t ld_out, int64_t rows, int64_t cols, int dt,
+                       hipStream_t st) {
+  if (rows <= 0 || cols <= 0) return hipSuccess;
+  const int64_t pad_to = ld_out;  // the whole output row is owned by the destination buffer
+  dim3 grid((cols + 63) / 64, (pad_to + 63) / 64);
+  if (dt == LR_F32)
+    hipLaunchKernelGGL(transpose_kernel<float>, grid, dim3(256), 0, st, (const float*)in, ld_in, (float*)out, ld_out,
+                       rows, cols, pad_to);
+  else
+    hipLaunchKernelGGL(transpose_kernel<uint16_t>, grid, dim3(256), 0, st, (const uint16_t*)in, ld_in, (uint16_t*)out,
+                       ld_out, rows, cols, pad_to);
+  return hipGetLastError();
+}
+hipError_t k_rowsum_parts(const float* part, int64_t ld, int nparts, float* out, int64_t M, hipStream_t st) {
+  if (M <= 0) return hipSuccess;
+  hipLaunchKernelGGL(rowsum_parts_kernel, dim3((M + 255) / 256), dim3(256), 0, st, part, ld, nparts, out, M);
+  return hipGetLastError();
+}
+hipError_t k_rowdot(const void* a, int64_t lda, const void* b, int64_t ldb, float* out, int64_t M, int64_t N, int dt,
+                    hipStream_t st) {
+  if (M <= 0) return hipSuccess;
+  DISPATCH_DT(dt, rowdot_kernel, dim3((M + 3) / 4), dim3(256), st, a, lda, b, ldb, out, M, N);
+}
+hipError_t k_scale_cols(const void* w, const void* gamma, void* wout, int64_t rows, int64_t cols, int dt,
+                        hipStream_t st) {
+  if (rows <= 0 || cols <= 0) return hipSuccess;
+  const int nv = dt == LR_BF16 ? 8 : 1;
+  DISPATCH_DT(dt, scale_cols_kernel, dim3(grid1d(rows * (cols / nv))), dim3(256), st, w, gamma, wout, rows, cols);
+}
+int64_t k_wgrad_dgamma_parts(int64_t rows) { return (rows + WF_RB - 1) / WF_RB; }
+hipError_t k_wgrad_finish(const float* part, int nsplit, int64_t rows, int64_t cols, void* dw, const void* colscale,
+                          const void* w_for_dgamma, float* dgamma_part, int accumulate, int dt, int out_dt,
+                          hipStream_t st) {
+  if (rows <= 0 || cols <= 0) return hipSuccess;
+  const int nv = dt == LR_BF16 ? 8 : 1;
+  dim3 grid((cols / nv + 255) / 256, (rows + WF_RB - 1) / WF_RB);
+  if (dt == LR_F32)
+    hipLaunchKernelGGL((wgrad_finish_kernel<LR_F32, float>), grid, dim3(256), 0, st, part, nsplit, rows, cols, dw,
+                       colscale, w_for_dgamma, dgamma_part, accumulate);
+  else if (out_dt == LR_F32)
+    hipLaunchKernelGGL((wgrad_finish_kernel<LR_BF16, float>), grid, dim3(256), 0, st, part, nsplit, rows, cols, dw,
+                       colscale, w_for_dgamma, dgamma_part, accumulate);
+  else
+    hipLaunchKernelGGL((wgrad_finish_kernel<LR_BF16, bf16_t>), grid, dim3(256), 0, st, part, nsplit, rows, cols, dw,
+                       colscale, w_for_dgamma, dgamma_part, accumulate);
+  return hipGetLastError();
+}
+hipError_t k_colsum_parts(const float* part, int64_t nparts, int64_t cols, void* out, int accumulate, int out_dt,
+                          hipStream_t st) {
+  if (cols <= 0) return hipSuccess;
+  if (out_dt == LR_F32)
+    hipLaunchKernelGGL(colsum_parts_kernel<float>, dim3((cols + 255) / 256), dim3(256), 0, st, part, nparts, cols, out,
+                       accumulate);
+  else
+    hipLaunchKernelGGL(colsum_parts_kernel<bf16_t>, dim3((cols + 255) / 256), dim3(256), 0, st, part, nparts, cols,
+                       out, accumulate);
+  return hipGetLastError();
+}
+
+}  // namespace lrb

@@ -1,0 +1,83 @@
+"""Host-side checks that need no GPU: the library loads, exports what the header declares, and
+rejects bad arguments before touching the device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2512_12131_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "lrboost.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lr_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.lib()
+    names = _declared()
+    assert len(names) >= 20
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in lrboost.h but not exported"
+    assert set(names) == set(B.EXPORTS), "binding and header disagree on the entry points"
+    assert lib.lr_version() >= 100
+
+
+def test_status_strings():
+    lib = B.lib()
+    for code in (0, -1, -2, -3, -4, -5):
+        assert lib.lr_status_string(code).decode().startswith("LR_")
+    assert b"unknown" in lib.lr_status_string(-99)
+
+
+def test_argument_errors_are_detected_on_the_host():
+    lib = B.lib()
+    fake = C.c_void_p(0x1000)          # 16-byte aligned, never dereferenced on these paths
+    odd = C.c_void_p(0x1002)
+    null = C.c_void_p(0)
+    f = lib.lr_linear_fwd
+    # null pointer
+    assert f(null, 64, fake, fake, fake, fake, 64, 8, 64, 16, 64, 1, 1, fake, 1 << 20, None) == -1
+    # unknown dtype / activation
+    assert f(fake, 64, fake, fake, fake, fake, 64, 8, 64, 16, 64, 1, 7, fake, 1 << 20, None) == -1
+    assert f(fake, 64, fake, fake, fake, fake, 64, 8, 64, 16, 64, 9, 1, fake, 1 << 20, None) == -1
+    # leading dimension smaller than the row
+    assert f(fake, 32, fake, fake, fake, fake, 64, 8, 64, 16, 64, 1, 1, fake, 1 << 20, None) == -1
+    # bf16 sizes must be multiples of 8, pointers 16-byte aligned
+    assert f(fake, 64, fake, fake, fake, fake, 64, 8, 64, 12, 64, 1, 1, fake, 1 << 20, None) == -4
+    assert f(odd, 64, fake, fake, fake, fake, 64, 8, 64, 16, 64, 1, 1, fake, 1 << 20, None) == -4
+    # workspace too small / missing
+    need = lib.lr_linear_workspace_bytes(8, 64, 16, 64, 1, 0)
+    assert need > 0
+    assert f(fake, 64, fake, fake, fake, fake, 64, 8, 64, 16, 64, 1, 1, fake, need - 1, None) == -3
+    assert f(fake, 64, fake, fake, fake, fake, 64, 8, 64, 16, 64, 1, 1, null, 0, None) == -3
+    # T = 0 is a valid no-op
+    assert f(fake, 64, fake, fake, fake, fake, 64, 0, 64, 16, 64, 1, 1, null, 0, None) == 0
+
+
+def test_workspace_queries_scale_and_reject():
+    lib = B.lib()
+    a = lib.lr_group_workspace_bytes(3, 1024, 256, 64, 256, 1, 0)
+    b = lib.lr_group_workspace_bytes(3, 2048, 256, 64, 256, 1, 0)
+    assert 0 < a < b
+    assert lib.lr_group_workspace_bytes(0, 1024, 256, 64, 256, 1, 0) == 0
+    assert lib.lr_linear_workspace_bytes(16, 64, 16, 64, 5, 0) == 0
+    d = B.make_block_desc(2, 256, 256, 2, 128, 344, 344, 64)
+    assert lib.lr_block_workspace_bytes(C.byref(d), 0) > 0
+    assert lib.lr_block_workspace_bytes(C.byref(d), 1) > lib.lr_block_workspace_bytes(C.byref(d), 0)
+    assert lib.lr_block_ckpt_bytes(C.byref(d)) == 7 * 512 * 64 * 2 + 2 * 512 * 4
+    bad = B.make_block_desc(2, 256, 256, 4, 128, 344, 344, 64)     # heads * head_dim != d_model
+    assert lib.lr_block_workspace_bytes(C.byref(bad), 0) == 0
+    f32 = B.make_block_desc(2, 256, 256, 2, 128, 344, 344, 64, dt=B.LR_F32)
+    assert lib.lr_block_workspace_bytes(C.byref(f32), 0) == 0
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", "/nonexistent/liblrboost.so")
+    with pytest.raises(B.LrError):
+        B.lib()
