@@ -558,8 +558,8 @@ int lr_linear_fwd(const void* x, int64_t ldx, const void* w_down, const void* w_
   if (T > 0x7fffffffLL) return LR_EINVAL;
   if (ldx < d_in || ldy < d_out) return LR_EINVAL;
   TRY(check_dims_bf16(dt, {d_in, r, d_out, ldx, ldy}));
+  if (T == 0) return LR_OK;   // no tokens: nothing to do (empty tensors may have null pointers)
   TRY(check_ptrs(dt, {x, w_down, w_up, z, y}));
-  if (T == 0) return LR_OK;
   TRY(check_ws(ws, ws_bytes, lr_linear_workspace_bytes(T, d_in, r, d_out, dt, 0)));
   Ctx c; c.base = (char*)ws; c.cap = ws_bytes; c.dt = dt; c.st = (hipStream_t)stream;
   LinArgs a{}; a.x = x; a.w_down = w_down; a.w_up = w_up; a.z = z; a.y = y; a.ldx = ldx; a.ldy = ldy;
@@ -577,9 +577,9 @@ int lr_linear_bwd(const void* x, int64_t ldx, const void* w_down, const void* w_
   TRY(check_sizes_fit_int({d_in, r, d_out}));
   if (ldx < d_in || lddy < d_out || lddx < d_in) return LR_EINVAL;
   TRY(check_dims_bf16(dt, {d_in, r, d_out, ldx, lddy, lddx}));
+  if (T == 0) return LR_OK;   // no tokens: gradients are left as they are
   TRY(check_ptrs(dt, {x, w_down, w_up, z, dy, dx}));
   TRY(check_gptrs(grad_dt, {dw_down, dw_up}));
-  if (T == 0) return LR_OK;   // no tokens: gradients are left as they are
   TRY(check_ws(ws, ws_bytes, lr_linear_workspace_bytes(T, d_in, r, d_out, dt, 1)));
   Ctx c; c.base = (char*)ws; c.cap = ws_bytes; c.dt = dt; c.gdt = grad_dt; c.st = (hipStream_t)stream;
   LinArgs a{}; a.x = x; a.w_down = w_down; a.w_up = w_up; a.zc = z; a.dy = dy; a.dx = dx; a.dw_down = dw_down;
@@ -618,6 +618,7 @@ int lr_group_fwd(const void* x, int64_t ldx, const void* gamma, float eps, int n
   if (ldx < d_in || ldy < d_out) return LR_EINVAL;
   if (G > 1 && y_batch_stride < d_out) return LR_EINVAL;
   TRY(check_dims_bf16(dt, {d_in, r, d_out, ldx, ldy, y_batch_stride}));
+  if (T == 0) return LR_OK;
   TRY(check_ptrs(dt, {x, w_down_cat, w_up_stack, z_cat, y_stack}));
   if (norm != LR_NORM_NONE) {
     TRY(check_ptrs(dt, {gamma}));
@@ -646,6 +647,7 @@ int lr_group_bwd(const void* x, int64_t ldx, const void* gamma, float eps, int n
   if (ldx < d_in || lddy < d_out || lddx < d_in) return LR_EINVAL;
   if (G > 1 && dy_batch_stride < d_out) return LR_EINVAL;
   TRY(check_dims_bf16(dt, {d_in, r, d_out, ldx, lddy, lddx, dy_batch_stride}));
+  if (T == 0) return LR_OK;
   TRY(check_ptrs(dt, {x, w_down_cat, w_up_stack, z_cat, dy_stack, dx}));
   TRY(check_gptrs(grad_dt, {dw_down_cat, dw_up_stack}));
   if (norm != LR_NORM_NONE) {

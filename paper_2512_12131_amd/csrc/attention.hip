@@ -1,11 +1,576 @@
-// Causal multi-head attention for the decoder block (placeholder until the kernels land).
+// Causal multi-head attention, head_dim 128, bf16 in / fp32 softmax, for gfx950.
+//
+// Forward (one workgroup = 4 wavefronts x MB*32 queries of one (batch, head); K/V stream through
+// LDS in 64-key tiles, double buffered):
+//   S^T = K Q^T      MFMA, A = K rows from LDS, B = Q rows kept in registers for the whole kernel
+//   online softmax   per query = per lane column of the S^T accumulators (one cross-half shuffle)
+//   O^T += V^T P^T   MFMA, B = P^T straight from the softmax registers, A = V^T through the LDS
+//                    transpose read (ds_read_b64_tr_b16), so V is stored as it arrives: [key][h]
+// Working on the transposed problem is what lets the probabilities feed the second MFMA without
+// leaving registers: the 32x32 accumulator layout (lane = column, 16 rows in 4-row groups) is, up
+// to a fixed permutation of the k slots that the V^T loads follow, the B-operand layout.
+//
+// Backward is two kernels, both free of atomics and therefore deterministic:
+//   dq kernel  - same walk as the forward (workgroup owns queries, streams keys):
+//                S^T, dP^T = V dO^T, dS^T = P^T*(dP^T - D), dQ^T += K^T dS^T
+//   dkv kernel - workgroup owns 128 keys, streams 64-query tiles from the diagonal on:
+//                S = Q K^T, dP = dO V^T, dV^T += dO^T P, dK^T += Q^T dS
+// with D[q] = sum_h dO[q,h] O[q,h] from a small preprocessing kernel.
 #include "common.h"
+
 namespace lrb {
-hipError_t attention_fwd_bf16(const void*, const void*, const void*, void*, float*, int64_t, int, int, int, int, int,
-                              hipStream_t) { return hipErrorNotSupported; }
-size_t attention_bwd_ws_bytes(int, int, int, int) { return 0; }
-hipError_t attention_bwd_bf16(const void*, const void*, const void*, const void*, const void*, const float*, void*,
-                              void*, void*, int64_t, int, int, int, int, int, void*, hipStream_t) {
-  return hipErrorNotSupported;
+namespace {
+
+constexpr int HD = 128;
+constexpr int KT = 64;            // keys (or queries, in the dkv kernel) per streamed tile
+constexpr int PB = 272;           // LDS row pitch for tiles read with ds_read_b128 (rows 4 banks apart)
+constexpr int PT = 320;           // LDS row pitch for tiles read with the transpose read
+constexpr float LOG2E = 1.4426950408889634f;
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ bf16x8 lds_b128(const unsigned char* p) { return *reinterpret_cast<const bf16x8*>(p); }
+
+// A operand of a 32x32x16 MFMA whose 32 rows are 32 consecutive columns (c0..c0+31) of an LDS tile
+// stored [k][col] with row pitch PT, and whose 16 k slots are tile rows
+//   slot (half, e) -> k0 + (e/4)*8 + half*4 + e%4        (the accumulator-row permutation).
+// Inside each group of 16 lanes the transpose read hands lane i the i-th 16-bit column of the 4 x 16
+// block that the 16 lanes fetched as 4 rows x 4 lanes x 8 bytes.
+__device__ __forceinline__ bf16x8 lds_tr_frag(const unsigned char* tile, int k0, int c0, int lane) {
+  const int g = lane >> 4, s = lane & 15;
+  const int half = g >> 1;
+  const int col = c0 + (g & 1) * 16 + (s & 3) * 4;
+  const int row = k0 + half * 4 + (s >> 2);
+  const unsigned char* p0 = tile + row * PT + col * 2;
+  const unsigned char* p1 = p0 + 8 * PT;
+  s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0));
+  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p1));
+  typedef short s16x8 __attribute__((ext_vector_type(8)));
+  s16x8 r = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  return __builtin_bit_cast(bf16x8, r);
 }
+
+// 8 consecutive accumulator values (v = t*8 .. t*8+7) packed as the bf16 B operand of one k16 step.
+__device__ __forceinline__ bf16x8 pack_acc_half(const f32x16& a, int t) {
+  uint4 q;
+  q.x = pack_bf16x2(a[t * 8 + 0], a[t * 8 + 1]);
+  q.y = pack_bf16x2(a[t * 8 + 2], a[t * 8 + 3]);
+  q.z = pack_bf16x2(a[t * 8 + 4], a[t * 8 + 5]);
+  q.w = pack_bf16x2(a[t * 8 + 6], a[t * 8 + 7]);
+  return __builtin_bit_cast(bf16x8, q);
+}
+
+// Row index of accumulator element v inside a 32-row block.
+__device__ __forceinline__ int acc_row(int v, int lane) { return 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3); }
+
+// Copies a [KT rows][128] bf16 tile (global row stride ld elements) into registers: 4 x 16 bytes per
+// thread; rows >= nrows read as zero.
+struct TileRegs { uint4 r[4]; };
+__device__ __forceinline__ TileRegs load_tile(const uint16_t* base, int64_t ld, int row0, int nrows, int tid) {
+  TileRegs t;
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    const int c = tid + i * 256, row = c >> 4, kc = c & 15;
+    const bool ok = (row0 + row) < nrows;
+    t.r[i] = ok ? *reinterpret_cast<const uint4*>(base + (int64_t)(row0 + row) * ld + kc * 8) : make_uint4(0, 0, 0, 0);
+  }
+  return t;
+}
+__device__ __forceinline__ void store_tile(unsigned char* lds, int pitch, const TileRegs& t, int tid) {
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    const int c = tid + i * 256, row = c >> 4, kc = c & 15;
+    *reinterpret_cast<uint4*>(lds + row * pitch + kc * 16) = t.r[i];
+  }
+}
+
+// Query-row fragments kept in registers: B operand (rows = queries) for all 8 k16 steps over h.
+template <int MB>
+__device__ __forceinline__ void load_row_frags(bf16x8 (&f)[MB][8], const uint16_t* base, int64_t ld, int row0,
+                                               int nrows, int lane) {
+#pragma unroll
+  for (int mb = 0; mb < MB; mb++) {
+    const int row = row0 + mb * 32 + (lane & 31);
+    const bool ok = row < nrows;
+#pragma unroll
+    for (int ks = 0; ks < 8; ks++) {
+      uint4 q = ok ? *reinterpret_cast<const uint4*>(base + (int64_t)row * ld + ks * 16 + (lane >> 5) * 8)
+                   : make_uint4(0, 0, 0, 0);
+      f[mb][ks] = __builtin_bit_cast(bf16x8, q);
+    }
+  }
+}
+
+// Writes a transposed accumulator block set acc[hb][.] (rows = h, column = the lane's token) as
+// out[token][h], 4 consecutive h (8 bytes) at a time, scaled by `mul`.
+__device__ __forceinline__ void store_acc_T(uint16_t* out_row, const f32x16 (&acc)[4], float mul, int lane) {
+#pragma unroll
+  for (int hb = 0; hb < 4; hb++)
+#pragma unroll
+    for (int g4 = 0; g4 < 4; g4++) {
+      const int h = hb * 32 + 8 * g4 + 4 * (lane >> 5);
+      uint2 w;
+      w.x = pack_bf16x2(acc[hb][g4 * 4 + 0] * mul, acc[hb][g4 * 4 + 1] * mul);
+      w.y = pack_bf16x2(acc[hb][g4 * 4 + 2] * mul, acc[hb][g4 * 4 + 3] * mul);
+      *reinterpret_cast<uint2*>(out_row + h) = w;
+    }
+}
+
+constexpr int FWD_LDS = 2 * (KT * PB + KT * PT);
+
+// ----------------------------------------------------------------------------------------------
+// forward
+// ----------------------------------------------------------------------------------------------
+template <int MB>
+__global__ __launch_bounds__(256) void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
+                                                       const uint16_t* __restrict__ v, uint16_t* __restrict__ o,
+                                                       float* __restrict__ lse, int64_t ld, int S, int H, float scale) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int BQ = 4 * MB * 32;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int nqb = (S + BQ - 1) / BQ;
+  const int q0 = (nqb - 1 - (int)blockIdx.x) * BQ;       // heaviest (latest) query blocks first
+  const int head = blockIdx.y, b = blockIdx.z;
+  const int64_t tok0 = (int64_t)b * S;
+  const uint16_t* qb = q + tok0 * ld + head * HD;
+  const uint16_t* kb = k + tok0 * ld + head * HD;
+  const uint16_t* vb = v + tok0 * ld + head * HD;
+  const int qw0 = q0 + wave * MB * 32;                   // first query of this wavefront
+  const float c = scale * LOG2E;
+
+  bf16x8 qf[MB][8];
+  load_row_frags<MB>(qf, qb, ld, qw0, S, lane);
+
+  f32x16 oacc[MB][4];
+  float mrun[MB], lrun[MB];
+#pragma unroll
+  for (int mb = 0; mb < MB; mb++) {
+    mrun[mb] = -INFINITY;
+    lrun[mb] = 0.f;
+#pragma unroll
+    for (int hb = 0; hb < 4; hb++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) oacc[mb][hb][e] = 0.f;
+  }
+
+  const int kv_end = min(S, q0 + BQ);                    // causal: keys up to the block's last query
+  const int ntiles = (kv_end + KT - 1) / KT;
+  constexpr int STAGE = KT * PB + KT * PT;               // K tile (b128 reads), V tile (transpose reads)
+
+  TileRegs tk = load_tile(kb, ld, 0, S, tid), tv = load_tile(vb, ld, 0, S, tid);
+  store_tile(smem, PB, tk, tid);
+  store_tile(smem + KT * PB, PT, tv, tid);
+  __syncthreads();
+
+  for (int j = 0; j < ntiles; j++) {
+    const int cur = j & 1;
+    const bool more = j + 1 < ntiles;
+    if (more) {
+      tk = load_tile(kb, ld, (j + 1) * KT, S, tid);
+      tv = load_tile(vb, ld, (j + 1) * KT, S, tid);
+    }
+    const int key0 = j * KT;
+    const unsigned char* sKc = smem + cur * STAGE;
+    const unsigned char* sVc = sKc + KT * PB;
+    if (key0 <= qw0 + MB * 32 - 1) {                     // this wavefront still has unmasked keys here
+      // ---- S^T[n][m] for 64 keys x MB*32 queries ----
+      f32x16 st[2][MB];
+#pragma unroll
+      for (int nb = 0; nb < 2; nb++)
+#pragma unroll
+        for (int mb = 0; mb < MB; mb++)
+#pragma unroll
+          for (int e = 0; e < 16; e++) st[nb][mb][e] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < 8; ks++)
+#pragma unroll
+        for (int nb = 0; nb < 2; nb++) {
+          const bf16x8 kf = lds_b128(sKc + (nb * 32 + (lane & 31)) * PB + (ks * 2 + (lane >> 5)) * 16);
+#pragma unroll
+          for (int mb = 0; mb < MB; mb++)
+            st[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[mb][ks], st[nb][mb], 0, 0, 0);
+        }
+      const bool need_mask = (key0 + KT - 1 > qw0) || (key0 + KT > S);
+#pragma unroll
+      for (int mb = 0; mb < MB; mb++) {
+        const int qi = qw0 + mb * 32 + (lane & 31);
+        float mx = -INFINITY;
+#pragma unroll
+        for (int nb = 0; nb < 2; nb++)
+#pragma unroll
+          for (int e = 0; e < 16; e++) {
+            if (need_mask) {
+              const int key = key0 + nb * 32 + acc_row(e, lane);
+              if (key > qi || key >= S) st[nb][mb][e] = -INFINITY;
+            }
+            mx = fmaxf(mx, st[nb][mb][e]);
+          }
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float mnew = fmaxf(mrun[mb], mx);          // finite: key 0 is visible to every query
+        const float alpha = exp2f((mrun[mb] - mnew) * c);
+        mrun[mb] = mnew;
+        const float mc = mnew * c;
+        float rs = 0.f;
+#pragma unroll
+        for (int nb = 0; nb < 2; nb++)
+#pragma unroll
+          for (int e = 0; e < 16; e++) {
+            const float p = exp2f(fmaf(st[nb][mb][e], c, -mc));
+            st[nb][mb][e] = p;
+            rs += p;
+          }
+        lrun[mb] = lrun[mb] * alpha + rs;
+#pragma unroll
+        for (int hb = 0; hb < 4; hb++)
+#pragma unroll
+          for (int e = 0; e < 16; e++) oacc[mb][hb][e] *= alpha;
+      }
+      // ---- O^T += V^T P^T ----
+#pragma unroll
+      for (int nb = 0; nb < 2; nb++)
+#pragma unroll
+        for (int t = 0; t < 2; t++) {
+          bf16x8 pf[MB];
+#pragma unroll
+          for (int mb = 0; mb < MB; mb++) pf[mb] = pack_acc_half(st[nb][mb], t);
+#pragma unroll
+          for (int hb = 0; hb < 4; hb++) {
+            const bf16x8 vf = lds_tr_frag(sVc, nb * 32 + t * 16, hb * 32, lane);
+#pragma unroll
+            for (int mb = 0; mb < MB; mb++)
+              oacc[mb][hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[mb], oacc[mb][hb], 0, 0, 0);
+          }
+        }
+    }
+    if (more) {
+      store_tile(smem + (cur ^ 1) * STAGE, PB, tk, tid);
+      store_tile(smem + (cur ^ 1) * STAGE + KT * PB, PT, tv, tid);
+    }
+    __syncthreads();
+  }
+
+#pragma unroll
+  for (int mb = 0; mb < MB; mb++) {
+    const int qi = qw0 + mb * 32 + (lane & 31);
+    const float l = lrun[mb] + __shfl_xor(lrun[mb], 32);
+    if (qi < S) {
+      store_acc_T(o + (tok0 + qi) * ld + head * HD, oacc[mb], 1.f / l, lane);
+      if (lane < 32) lse[((int64_t)b * H + head) * S + qi] = mrun[mb] * scale + logf(l);
+    }
+  }
+}
+
+// ----------------------------------------------------------------------------------------------
+// D[b, head, q] = sum_h dO[q, h] * O[q, h] : 16 lanes per (token, head)
+// ----------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void attn_dot_kernel(const uint16_t* __restrict__ dout, const uint16_t* __restrict__ o,
+                                                       float* __restrict__ D, int64_t ld, int S, int H, int64_t total) {
+  const int64_t item = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 4;   // (token, head) pair
+  const int sub = threadIdx.x & 15;
+  float s = 0.f;
+  int64_t tok = 0;
+  int head = 0;
+  if (item < total) {
+    tok = item / H;
+    head = (int)(item % H);
+    const int64_t off = tok * ld + head * HD + sub * 8;
+    float a[8], bb[8];
+    unpack8(*reinterpret_cast<const uint4*>(dout + off), a);
+    unpack8(*reinterpret_cast<const uint4*>(o + off), bb);
+#pragma unroll
+    for (int i = 0; i < 8; i++) s = fmaf(a[i], bb[i], s);
+  }
+  s += __shfl_xor(s, 1);
+  s += __shfl_xor(s, 2);
+  s += __shfl_xor(s, 4);
+  s += __shfl_xor(s, 8);
+  if (item < total && sub == 0) {
+    const int64_t bidx = tok / S, qi = tok % S;
+    D[(bidx * H + head) * S + qi] = s;
+  }
+}
+
+// ----------------------------------------------------------------------------------------------
+// backward, dQ: workgroup owns 4 x 32 queries, streams 64-key tiles of K and V
+// ----------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
+                                                          const uint16_t* __restrict__ v,
+                                                          const uint16_t* __restrict__ dout,
+                                                          const float* __restrict__ lse, const float* __restrict__ D,
+                                                          uint16_t* __restrict__ dq, int64_t ld, int S, int H,
+                                                          float scale) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int BQ = 128;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int nqb = (S + BQ - 1) / BQ;
+  const int q0 = (nqb - 1 - (int)blockIdx.x) * BQ;
+  const int head = blockIdx.y, b = blockIdx.z;
+  const int64_t tok0 = (int64_t)b * S;
+  const int64_t hoff = head * HD;
+  const int qw0 = q0 + wave * 32;
+  const float c = scale * LOG2E;
+
+  bf16x8 qf[1][8], dof[1][8];
+  load_row_frags<1>(qf, q + tok0 * ld + hoff, ld, qw0, S, lane);
+  load_row_frags<1>(dof, dout + tok0 * ld + hoff, ld, qw0, S, lane);
+  const int qi = qw0 + (lane & 31);
+  const int64_t sidx = ((int64_t)b * H + head) * S + min(qi, S - 1);
+  const float lse2 = lse[sidx] * LOG2E, Dq = D[sidx];
+
+  f32x16 acc[4];
+#pragma unroll
+  for (int hb = 0; hb < 4; hb++)
+#pragma unroll
+    for (int e = 0; e < 16; e++) acc[hb][e] = 0.f;
+
+  // K is needed both row-wise (S^T) and transposed (dQ^T): keep two LDS copies with the two pitches.
+  constexpr int STAGE = KT * PB + KT * PT + KT * PB;     // K (b128), K (transpose read), V (b128)
+  const int kv_end = min(S, q0 + BQ);
+  const int ntiles = (kv_end + KT - 1) / KT;
+  const uint16_t* kb = k + tok0 * ld + hoff;
+  const uint16_t* vb = v + tok0 * ld + hoff;
+  TileRegs tk = load_tile(kb, ld, 0, S, tid), tv = load_tile(vb, ld, 0, S, tid);
+  store_tile(smem, PB, tk, tid);
+  store_tile(smem + KT * PB, PT, tk, tid);
+  store_tile(smem + KT * PB + KT * PT, PB, tv, tid);
+  __syncthreads();
+
+  for (int j = 0; j < ntiles; j++) {
+    const int cur = j & 1;
+    const bool more = j + 1 < ntiles;
+    if (more) {
+      tk = load_tile(kb, ld, (j + 1) * KT, S, tid);
+      tv = load_tile(vb, ld, (j + 1) * KT, S, tid);
+    }
+    const unsigned char* sKb = smem + cur * STAGE;
+    const unsigned char* sKt = sKb + KT * PB;
+    const unsigned char* sVb = sKt + KT * PT;
+    const int key0 = j * KT;
+    if (key0 <= qw0 + 31) {
+      f32x16 st[2], dp[2];
+#pragma unroll
+      for (int nb = 0; nb < 2; nb++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) { st[nb][e] = 0.f; dp[nb][e] = 0.f; }
+#pragma unroll
+      for (int ks = 0; ks < 8; ks++)
+#pragma unroll
+        for (int nb = 0; nb < 2; nb++) {
+          const int off = (nb * 32 + (lane & 31)) * PB + (ks * 2 + (lane >> 5)) * 16;
+          st[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_b128(sKb + off), qf[0][ks], st[nb], 0, 0, 0);
+          dp[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_b128(sVb + off), dof[0][ks], dp[nb], 0, 0, 0);
+        }
+      // dS^T = P^T * (dP^T - D), masked
+#pragma unroll
+      for (int nb = 0; nb < 2; nb++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+          const int key = key0 + nb * 32 + acc_row(e, lane);
+          const float p = (key > qi || key >= S) ? 0.f : exp2f(fmaf(st[nb][e], c, -lse2));
+          st[nb][e] = p * (dp[nb][e] - Dq);
+        }
+#pragma unroll
+      for (int nb = 0; nb < 2; nb++)
+#pragma unroll
+        for (int t = 0; t < 2; t++) {
+          const bf16x8 dsf = pack_acc_half(st[nb], t);
+#pragma unroll
+          for (int hb = 0; hb < 4; hb++)
+            acc[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr_frag(sKt, nb * 32 + t * 16, hb * 32, lane), dsf,
+                                                              acc[hb], 0, 0, 0);
+        }
+    }
+    if (more) {
+      unsigned char* nx = smem + (cur ^ 1) * STAGE;
+      store_tile(nx, PB, tk, tid);
+      store_tile(nx + KT * PB, PT, tk, tid);
+      store_tile(nx + KT * PB + KT * PT, PB, tv, tid);
+    }
+    __syncthreads();
+  }
+  if (qi < S) store_acc_T(dq + (tok0 + qi) * ld + hoff, acc, scale, lane);
+}
+constexpr int DQ_LDS = 2 * (KT * PB + KT * PT + KT * PB);
+
+// ----------------------------------------------------------------------------------------------
+// backward, dK and dV: workgroup owns 4 x 32 keys, streams 64-query tiles of Q and dO
+// ----------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
+                                                           const uint16_t* __restrict__ v,
+                                                           const uint16_t* __restrict__ dout,
+                                                           const float* __restrict__ lse, const float* __restrict__ D,
+                                                           uint16_t* __restrict__ dk, uint16_t* __restrict__ dv,
+                                                           int64_t ld, int S, int H, float scale) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int BN = 128;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n0 = blockIdx.x * BN;                          // early key blocks (most queries) first
+  const int head = blockIdx.y, b = blockIdx.z;
+  const int64_t tok0 = (int64_t)b * S;
+  const int64_t hoff = head * HD;
+  const int nw0 = n0 + wave * 32;
+  const float c = scale * LOG2E;
+
+  bf16x8 kf[1][8], vf[1][8];                               // B operands: rows = this wavefront's keys
+  load_row_frags<1>(kf, k + tok0 * ld + hoff, ld, nw0, S, lane);
+  load_row_frags<1>(vf, v + tok0 * ld + hoff, ld, nw0, S, lane);
+  const int ni = nw0 + (lane & 31);
+
+  f32x16 akv[2][4];                                        // [0] = dK^T, [1] = dV^T
+#pragma unroll
+  for (int w = 0; w < 2; w++)
+#pragma unroll
+    for (int hb = 0; hb < 4; hb++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) akv[w][hb][e] = 0.f;
+
+  // per stage: Q (b128), Q (transpose), dO (b128), dO (transpose), lse*log2e[64], D[64]
+  constexpr int STAGE = 2 * (KT * PB + KT * PT) + 2 * KT * 4;
+  const uint16_t* qb = q + tok0 * ld + hoff;
+  const uint16_t* dob = dout + tok0 * ld + hoff;
+  const float* lseb = lse + ((int64_t)b * H + head) * S;
+  const float* Db = D + ((int64_t)b * H + head) * S;
+  const int jbeg = n0 / KT;                                // causal: first query tile that sees key n0
+  const int jend = (S + KT - 1) / KT;
+
+  auto stage_ptrs = [&](int st, unsigned char*& qB, unsigned char*& qT, unsigned char*& dB, unsigned char*& dT,
+                        float*& sl, float*& sd) {
+    unsigned char* p = smem + st * STAGE;
+    qB = p; qT = qB + KT * PB; dB = qT + KT * PT; dT = dB + KT * PB;
+    sl = reinterpret_cast<float*>(dT + KT * PT); sd = sl + KT;
+  };
+  unsigned char *qB, *qT, *dB, *dT;
+  float *sl, *sd;
+  TileRegs tq = load_tile(qb, ld, jbeg * KT, S, tid), td = load_tile(dob, ld, jbeg * KT, S, tid);
+  float rl = 0.f, rd = 0.f;
+  if (tid < KT) {
+    const int qq = min(jbeg * KT + tid, S - 1);
+    rl = lseb[qq] * LOG2E;
+    rd = Db[qq];
+  }
+  stage_ptrs(0, qB, qT, dB, dT, sl, sd);
+  store_tile(qB, PB, tq, tid); store_tile(qT, PT, tq, tid);
+  store_tile(dB, PB, td, tid); store_tile(dT, PT, td, tid);
+  if (tid < KT) { sl[tid] = rl; sd[tid] = rd; }
+  __syncthreads();
+
+  for (int j = jbeg; j < jend; j++) {
+    const int cur = (j - jbeg) & 1;
+    const bool more = j + 1 < jend;
+    if (more) {
+      tq = load_tile(qb, ld, (j + 1) * KT, S, tid);
+      td = load_tile(dob, ld, (j + 1) * KT, S, tid);
+      if (tid < KT) {
+        const int qq = min((j + 1) * KT + tid, S - 1);
+        rl = lseb[qq] * LOG2E;
+        rd = Db[qq];
+      }
+    }
+    stage_ptrs(cur, qB, qT, dB, dT, sl, sd);
+    const int qt0 = j * KT;
+    if (qt0 + KT - 1 >= nw0) {                             // some query of the tile sees this wavefront's keys
+      f32x16 st[2], dp[2];                                 // [qblock]: rows = queries, column = key
+#pragma unroll
+      for (int qb2 = 0; qb2 < 2; qb2++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) { st[qb2][e] = 0.f; dp[qb2][e] = 0.f; }
+#pragma unroll
+      for (int ks = 0; ks < 8; ks++)
+#pragma unroll
+        for (int qb2 = 0; qb2 < 2; qb2++) {
+          const int off = (qb2 * 32 + (lane & 31)) * PB + (ks * 2 + (lane >> 5)) * 16;
+          st[qb2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_b128(qB + off), kf[0][ks], st[qb2], 0, 0, 0);
+          dp[qb2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_b128(dB + off), vf[0][ks], dp[qb2], 0, 0, 0);
+        }
+#pragma unroll
+      for (int qb2 = 0; qb2 < 2; qb2++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+          const int ql = qb2 * 32 + acc_row(e, lane);
+          const int qg = qt0 + ql;
+          const float p = (ni > qg || qg >= S) ? 0.f : exp2f(fmaf(st[qb2][e], c, -sl[ql]));
+          st[qb2][e] = p;                                  // P
+          dp[qb2][e] = p * (dp[qb2][e] - sd[ql]);          // dS
+        }
+#pragma unroll
+      for (int qb2 = 0; qb2 < 2; qb2++)
+#pragma unroll
+        for (int t = 0; t < 2; t++) {
+          const bf16x8 pf = pack_acc_half(st[qb2], t), dsf = pack_acc_half(dp[qb2], t);
+#pragma unroll
+          for (int hb = 0; hb < 4; hb++) {
+            akv[1][hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr_frag(dT, qb2 * 32 + t * 16, hb * 32, lane), pf,
+                                                                 akv[1][hb], 0, 0, 0);
+            akv[0][hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr_frag(qT, qb2 * 32 + t * 16, hb * 32, lane), dsf,
+                                                                 akv[0][hb], 0, 0, 0);
+          }
+        }
+    }
+    if (more) {
+      stage_ptrs(cur ^ 1, qB, qT, dB, dT, sl, sd);
+      store_tile(qB, PB, tq, tid); store_tile(qT, PT, tq, tid);
+      store_tile(dB, PB, td, tid); store_tile(dT, PT, td, tid);
+      if (tid < KT) { sl[tid] = rl; sd[tid] = rd; }
+    }
+    __syncthreads();
+  }
+  if (ni < S) {
+    store_acc_T(dk + (tok0 + ni) * ld + hoff, akv[0], scale, lane);
+    store_acc_T(dv + (tok0 + ni) * ld + hoff, akv[1], 1.f, lane);
+  }
+}
+constexpr int DKV_LDS = 2 * (2 * (KT * PB + KT * PT) + 2 * KT * 4);
+
+template <class K>
+hipError_t set_lds(K kern, int bytes) {
+  return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+}
+
+}  // namespace
+
+hipError_t attention_fwd_bf16(const void* q, const void* k, const void* v, void* o, float* lse, int64_t ld, int B,
+                              int S, int H, int hd, int causal, hipStream_t st) {
+  if (hd != HD || !causal) return hipErrorNotSupported;
+  constexpr int MB = 1;
+  constexpr int BQ = 4 * MB * 32;
+  static bool once = false;
+  if (!once) {
+    hipError_t e = set_lds(attn_fwd_kernel<MB>, FWD_LDS);
+    if (e != hipSuccess) return e;
+    once = true;
+  }
+  dim3 grid((S + BQ - 1) / BQ, H, B);
+  hipLaunchKernelGGL(attn_fwd_kernel<MB>, grid, dim3(256), FWD_LDS, st, (const uint16_t*)q, (const uint16_t*)k,
+                     (const uint16_t*)v, (uint16_t*)o, lse, ld, S, H, 1.f / sqrtf((float)hd));
+  return hipGetLastError();
+}
+
+size_t attention_bwd_ws_bytes(int B, int S, int H, int hd) { return (size_t)B * H * S * sizeof(float); }
+
+hipError_t attention_bwd_bf16(const void* q, const void* k, const void* v, const void* o, const void* dout,
+                              const float* lse, void* dq, void* dk, void* dv, int64_t ld, int B, int S, int H, int hd,
+                              int causal, void* ws, hipStream_t st) {
+  if (hd != HD || !causal) return hipErrorNotSupported;
+  static bool once = false;
+  if (!once) {
+    hipError_t e = set_lds(attn_bwd_dq_kernel, DQ_LDS);
+    if (e != hipSuccess) return e;
+    e = set_lds(attn_bwd_dkv_kernel, DKV_LDS);
+    if (e != hipSuccess) return e;
+    once = true;
+  }
+  float* D = (float*)ws;
+  const int64_t items = (int64_t)B * S * H;
+  hipLaunchKernelGGL(attn_dot_kernel, dim3((unsigned)((items * 16 + 255) / 256)), dim3(256), 0, st,
+                     (const uint16_t*)dout, (const uint16_t*)o, D, ld, S, H, items);
+  const float scale = 1.f / sqrtf((float)hd);
+  hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3((S + 127) / 128, H, B), dim3(256), DQ_LDS, st, (const uint16_t*)q,
+                     (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)dout, lse, D, (uint16_t*)dq, ld, S, H,
+                     scale);
+  hipLaunchKernelGGL(attn_bwd_dkv_kernel, dim3((S + 127) / 128, H, B), dim3(256), DKV_LDS, st, (const uint16_t*)q,
+                     (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)dout, lse, D, (uint16_t*)dk,
+                     (uint16_t*)dv, ld, S, H, scale);
+  return hipGetLastError();
+}
+
 }  // namespace lrb
