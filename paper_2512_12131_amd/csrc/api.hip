@@ -222,7 +222,8 @@ void group_bwd_seq(Ctx& c, const GrpArgs& a, const void* act) {
   for (int g = 0; g < a.G; g++)
     wgrad(c, (const char*)a.dy_stack + (size_t)g * a.dy_bs * es, a.lddy, (int)a.d_out,
           (const char*)act + (size_t)g * a.r * es, GR, (int)a.r, a.T,
-          (char*)a.dw_up_stack + (size_t)g * a.d_out * a.r * es, nullptr, nullptr, nullptr, a.accumulate);
+          (char*)a.dw_up_stack + (size_t)g * a.d_out * a.r * esize(c.gdt), nullptr, nullptr, nullptr,
+          a.accumulate);
   // dp_g = rho * (dy_g . W_up_g) * sigma'(z_g), batched over g, written into the columns of dp_cat;
   // cdot[t] = sum_n dp[t,n] z[t,n] is the RMSNorm-backward statistic, taken at rank r.
   void* dp = c.take((size_t)a.T * GR * es);

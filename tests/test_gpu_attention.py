@@ -8,6 +8,10 @@ from oracle import lowrank_oracle as orc
 from parity import check
 from paper_2512_12131_amd import binding as B
 
+# Tolerance: unit-variance Gaussian q, k, v make the first tokens of a sequence (single values) several
+# times larger than the RMS over all tokens (averages), so rounding the exact result to bf16 already
+# costs about 2e-2 of the RMS.  The output passes through one such rounding (o) or three (P, dS and
+# the result for dq, dk, dv), hence the floor terms below on top of the 2e-2 path tolerance.
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
@@ -31,13 +35,13 @@ def test_attention_fwd_bwd(Bn, S, H):
     Q, K, V, DO = (si.f64(t) for t in (q, k, v, do))
     o_ref, lse_ref = orc.attention_fwd(Q, K, V, Bn, S, H, hd, True)
     dq_ref, dk_ref, dv_ref = orc.attention_bwd(Q, K, V, DO, Bn, S, H, hd, True)
-    check("o", o, o_ref, dt)
+    check("o", o, o_ref, dt, floor=1.0)
     e = float(np.max(np.abs(lse.cpu().double().numpy() - lse_ref)))
     print(f"    lse max abs err {e:.3e}", flush=True)
     assert e < 2e-3
-    check("dq", dq, dq_ref, dt)
-    check("dk", dk, dk_ref, dt)
-    check("dv", dv, dv_ref, dt)
+    check("dq", dq, dq_ref, dt, floor=3.0)
+    check("dk", dk, dk_ref, dt, floor=3.0)
+    check("dv", dv, dv_ref, dt, floor=3.0)
     # first token of every sequence attends only to itself
     for b in range(Bn):
         assert torch.equal(o[b * S], vd[b * S])
