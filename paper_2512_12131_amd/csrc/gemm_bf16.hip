@@ -7,11 +7,12 @@
 //
 // Work decomposition: one workgroup owns a BM x BN output tile, WM x WN wavefronts each own a
 // (BM/WM) x (BN/WN) sub-tile built from 32x32x16 MFMA blocks.  The k loop moves 64-wide slices
-// global -> registers -> LDS with two LDS stages (one barrier per slice); LDS rows are 128 bytes
-// with the 16-byte chunk index XOR-swizzled by the row so that both the row-wise stores and the
-// MFMA-operand reads (32 rows x one chunk) are conflict free.  The accumulator tile leaves through
-// LDS as well, so that every global access of the epilogue (C, the auxiliary tiles it reads, the
-// secondary output) is a row-contiguous 16-byte vector.
+// straight from global memory into LDS (buffer_load ... lds, no register staging, whole 128-byte
+// cache lines per row) through two LDS stages, one workgroup barrier per slice; the 16-byte chunk
+// index of a row is XOR-swizzled by the row so that the MFMA-operand reads (32 rows x one chunk)
+// spread over all banks.  The accumulator tile leaves through LDS as well, so that every global access of the
+// epilogue (C, the auxiliary tiles it reads, the secondary output) is a row-contiguous 16-byte
+// vector.
 #include <type_traits>
 
 #include "epilogue.h"
@@ -19,23 +20,26 @@
 namespace lrb {
 namespace {
 
-constexpr int BK = 64;          // k elements per slice (128 bytes per LDS row)
+constexpr int BK = 64;          // k elements per LDS stage: 128-byte rows, i.e. whole cache lines per request
+constexpr int NST = 2;          // LDS stages: one being multiplied, one in flight from global memory
 constexpr int NXCD = 8;
 
 template <int BM_, int BN_, int WM_, int WN_>
 struct Tile {
   static constexpr int BM = BM_, BN = BN_, WM = WM_, WN = WN_;
-  static constexpr int NT = WM * WN * 64;
+  static constexpr int NW = WM * WN, NT = NW * 64;
   static constexpr int TM = BM / WM, TN = BN / WN;
   static constexpr int FM = TM / 32, FN = TN / 32;
   static constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
-  static constexpr int ACH = BM * 8 / NT, BCH = BN * 8 / NT;
+  static constexpr int WLOADS = (BM + BN) / 8 / NW;   // 1 KB wavefront loads (8 rows x 128 B) per wavefront per stage
+  static constexpr int WLOADS_A = BM / 8 / NW;        // the first WLOADS_A of them fetch A rows, the rest B rows
   static constexpr int CS = TN + 8;  // fp32 row stride of the epilogue staging tile
-  static constexpr int EPI_BYTES = WM * WN * 32 * CS * 4;
+  static constexpr int EPI_BYTES = NW * 32 * CS * 4;
   static constexpr int STAT_BYTES = BM * 4;
-  static constexpr int MAIN_BYTES = 2 * STAGE;
+  static constexpr int MAIN_BYTES = NST * STAGE;
   static constexpr int LDS_BYTES = (MAIN_BYTES > EPI_BYTES ? MAIN_BYTES : EPI_BYTES) + STAT_BYTES;
-  static_assert(ACH >= 1 && BCH >= 1 && FM >= 1 && FN >= 1, "tile too small for the thread count");
+  static_assert(BM / 8 % NW == 0 && BN / 8 % NW == 0 && FM >= 1 && FN >= 1 && BM <= NT,
+                "tile / wavefront layout mismatch");
 };
 
 // Compile-time loop: the body receives std::integral_constant indices, so register arrays indexed
@@ -48,11 +52,6 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
-__device__ __forceinline__ uint4 ldg16(const uint16_t* p, bool ok) {
-  uint4 z = make_uint4(0, 0, 0, 0);
-  return ok ? *reinterpret_cast<const uint4*>(p) : z;
-}
-
 __device__ __forceinline__ float sumsq8(const uint4& q) {
   float v[8];
   unpack8(q, v);
@@ -61,6 +60,13 @@ __device__ __forceinline__ float sumsq8(const uint4& q) {
   for (int i = 0; i < 8; i++) s = fmaf(v[i], v[i], s);
   return s;
 }
+
+// s_waitcnt vmcnt(N) with the other counters left alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14).
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0f70);
+}
+__device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xc07f); }
 
 // Maps the linear workgroup id to an output tile so that (a) the workgroups that the hardware
 // deals round-robin to one XCD form a contiguous range of tiles, and (b) consecutive tiles of that
@@ -77,6 +83,8 @@ __device__ __forceinline__ void tile_of_block(int bid, int total, int tiles_m, i
   tn = within / pm_eff;
   tm = panel * PM + within % pm_eff;
 }
+
+#define LRB_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 
 template <class T, int KIND, bool STAT_A>
 __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, int tiles_m, int tiles_n) {
@@ -96,49 +104,49 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
   const uint16_t* A = (const uint16_t*)op.A + (int64_t)b * op.sA;
   const uint16_t* B = (const uint16_t*)op.B + (int64_t)b * op.sB;
 
-  // ---- global -> register staging -------------------------------------------------------------
-  const int kc = tid & 7;          // 16-byte chunk of the 128-byte k slice this thread moves
-  const int r0 = tid >> 3;         // first tile row this thread moves; further rows every NT/8
-  const uint16_t* ap[T::ACH];
-  const uint16_t* bp[T::BCH];
-  bool aok[T::ACH], bok[T::BCH];
+  // ---- global -> LDS, without passing through registers ---------------------------------------
+  // One buffer_load_dwordx4 ... lds per wavefront moves 8 tile rows x 128 bytes (1 KB, eight whole
+  // cache lines): lane L's 16 bytes land at LDS base + 16 L, i.e. tile row L/8, physical chunk L%8.
+  // The 16-byte chunks of a row are stored XOR-swizzled by row%8, so each lane fetches the logical
+  // chunk that belongs in its slot; MFMA operand reads (32 rows x one logical chunk) then spread over
+  // all banks.  A lane whose chunk lies outside the matrix (row tail, k tail) uses an offset past the
+  // resource size: the load returns zeros and zeros are what reaches LDS.
+  constexpr uint32_t OOB = 0x80000000u;
+  const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)(A + (int64_t)m0 * op.lda + kbeg), 0, 0x7fffffff, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsB = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)(B + (int64_t)n0 * op.ldb + kbeg), 0, 0x7fffffff, 0x00020000);
+  const int lrow = lane >> 3;                              // row inside the 8-row group
+  const int lchunk = (lane & 7) ^ lrow;                    // logical 16-byte chunk this lane fetches
+  uint32_t goff[T::WLOADS];
 #pragma unroll
-  for (int i = 0; i < T::ACH; i++) {
-    int row = r0 + i * (T::NT / 8);
-    aok[i] = (m0 + row) < op.M;
-    ap[i] = A + (int64_t)(aok[i] ? m0 + row : 0) * op.lda + kbeg + kc * 8;
-  }
-#pragma unroll
-  for (int i = 0; i < T::BCH; i++) {
-    int row = r0 + i * (T::NT / 8);
-    bok[i] = (n0 + row) < op.N;
-    bp[i] = B + (int64_t)(bok[i] ? n0 + row : 0) * op.ldb + kbeg + kc * 8;
-  }
-  uint4 ra[T::ACH], rb[T::BCH];
-  float ssq[T::ACH];
-#pragma unroll
-  for (int i = 0; i < T::ACH; i++) ssq[i] = 0.f;
-
-  auto load_slice = [&](int kt) {
-    const bool kok = (kbeg + kt * BK + kc * 8) < kend;
-#pragma unroll
-    for (int i = 0; i < T::ACH; i++) ra[i] = ldg16(ap[i] + kt * BK, aok[i] && kok);
-#pragma unroll
-    for (int i = 0; i < T::BCH; i++) rb[i] = ldg16(bp[i] + kt * BK, bok[i] && kok);
-  };
-  auto store_slice = [&](int stage) {
-    unsigned char* sa = smem + stage * T::STAGE;
-    unsigned char* sb = sa + T::A_BYTES;
-#pragma unroll
-    for (int i = 0; i < T::ACH; i++) {
-      int row = r0 + i * (T::NT / 8);
-      *reinterpret_cast<uint4*>(sa + row * 128 + ((kc ^ (row & 7)) << 4)) = ra[i];
-      if constexpr (STAT_A) ssq[i] += sumsq8(ra[i]);
+  for (int i = 0; i < T::WLOADS; i++) {
+    const int g = wave + T::NW * i;                        // 8-row group: A groups first, then B
+    if (i < T::WLOADS_A) {
+      const int row = g * 8 + lrow;
+      goff[i] = (m0 + row) < op.M ? (uint32_t)(row * (int)op.lda + lchunk * 8) * 2u : OOB;
+    } else {
+      const int row = (g - T::BM / 8) * 8 + lrow;
+      goff[i] = (n0 + row) < op.N ? (uint32_t)(row * (int)op.ldb + lchunk * 8) * 2u : OOB;
     }
+  }
+  // Each workgroup walks its k range from a different starting slice (the sum does not care about
+  // the order), so that workgroups do not all sit at the same k offset, i.e. on the same L2 / memory
+  // channels, when row pitches are powers of two.
+  const int rot = nk > 0 ? ((tm * 5 + tn * 3 + ks * 7) & 15) * 2 % nk : 0;
+  auto issue_stage = [&](int kt) {
+    int kte = kt + rot;
+    if (kte >= nk) kte -= nk;
+    const uint32_t kmask = (kt < nk && (kbeg + kte * BK + lchunk * 8) < kend) ? 0u : OOB;
+    const uint32_t ktoff = (uint32_t)kte * (BK * 2);
+    unsigned char* dst = smem + (kt % NST) * T::STAGE + wave * 1024;
 #pragma unroll
-    for (int i = 0; i < T::BCH; i++) {
-      int row = r0 + i * (T::NT / 8);
-      *reinterpret_cast<uint4*>(sb + row * 128 + ((kc ^ (row & 7)) << 4)) = rb[i];
+    for (int i = 0; i < T::WLOADS; i++) {
+      const int voff = (int)((goff[i] + ktoff) | kmask);
+      if (i < T::WLOADS_A)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, LRB_LDS_PTR(dst + i * (T::NW * 1024)), 16, voff, 0, 0, 0);
+      else
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, LRB_LDS_PTR(dst + i * (T::NW * 1024)), 16, voff, 0, 0, 0);
     }
   };
 
@@ -150,48 +158,89 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
 #pragma unroll
       for (int v = 0; v < 16; v++) acc[i][j][v] = 0.f;
 
-  const int frow = lane & 31, fk = lane >> 5, fsw = lane & 7;
-
-  if (nk > 0) {
-    load_slice(0);
-    store_slice(0);
-  }
-  __syncthreads();
-  for (int kt = 0; kt < nk; kt++) {
-    const bool more = kt + 1 < nk;
-    if (more) load_slice(kt + 1);
-    const unsigned char* sa = smem + (kt & 1) * T::STAGE + (wm * T::TM + frow) * 128;
-    const unsigned char* sb = smem + (kt & 1) * T::STAGE + T::A_BYTES + (wn * T::TN + frow) * 128;
+  // MFMA operand addressing: row = lane%32 of a 32-row block, logical chunk kk*2 + lane/32
+  const int frow = lane & 31, fk = lane >> 5, fsw = frow & 7;
+  bf16x8 af[2][T::FM], bf[2][T::FN];
+  auto load_frags = [&](int buf, int kt, int kk) {
+    const unsigned char* sa = smem + (kt % NST) * T::STAGE + (wm * T::TM + frow) * 128;
+    const unsigned char* sb = smem + (kt % NST) * T::STAGE + T::A_BYTES + (wn * T::TN + frow) * 128;
+    const int coff = ((kk * 2 + fk) ^ fsw) << 4;
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; kk++) {
-      const int coff = ((kk * 2 + fk) ^ fsw) << 4;
-      bf16x8 af[T::FM], bf[T::FN];
+    for (int i = 0; i < T::FM; i++) af[buf][i] = *reinterpret_cast<const bf16x8*>(sa + i * 32 * 128 + coff);
 #pragma unroll
-      for (int i = 0; i < T::FM; i++) af[i] = *reinterpret_cast<const bf16x8*>(sa + i * 32 * 128 + coff);
+    for (int j = 0; j < T::FN; j++) bf[buf][j] = *reinterpret_cast<const bf16x8*>(sb + j * 32 * 128 + coff);
+  };
+  auto mfma_step = [&](int buf) {
 #pragma unroll
-      for (int j = 0; j < T::FN; j++) bf[j] = *reinterpret_cast<const bf16x8*>(sb + j * 32 * 128 + coff);
+    for (int i = 0; i < T::FM; i++)
 #pragma unroll
-      for (int i = 0; i < T::FM; i++)
+      for (int j = 0; j < T::FN; j++)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], bf[buf][j], acc[i][j], 0, 0, 0);
+  };
+  float ssq = 0.f;   // STAT_A: thread t accumulates the sum of squares of tile row t from the LDS copy
+  auto stat_row = [&](int kt, int half) {
+    if constexpr (STAT_A) {
+      if (tid < T::BM) {
+        const unsigned char* sr = smem + (kt % NST) * T::STAGE + tid * 128 + half * 64;
 #pragma unroll
-        for (int j = 0; j < T::FN; j++)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+        for (int c = 0; c < 4; c++) ssq += sumsq8(*reinterpret_cast<const uint4*>(sr + c * 16));
+      }
     }
-    if (more) store_slice((kt + 1) & 1);
-    __syncthreads();
+  };
+
+  // ---- main loop ---------------------------------------------------------------------------------
+  // Slice kt (64 wide) is multiplied in four k16 steps.  While step s runs, the operands of step s+1
+  // are read from LDS.  Before step 3 a barrier establishes that every wavefront's part of slice
+  // kt+1 has landed and that nobody reads stage kt%2 any more (the step-3 operands are in registers),
+  // so the loads of slice kt+2 are issued into it, with a whole slice of MFMA time to arrive.
+  // The loop body is branch free: slices past the end of k are "loaded" with every lane out of range
+  // (zeros into a stage nobody reads again), so the wait counts are compile-time constants.
+  // Instruction interleave: a wavefront issues in order, and an MFMA occupies the matrix pipe for
+  // 32 cycles during which the same wavefront may issue other work.  The scheduler is therefore
+  // told to thread the LDS reads and global->LDS loads between the MFMAs instead of issuing them
+  // in a burst while the matrix pipe idles.
+  constexpr int MPR = (T::FM * T::FN) / (T::FM + T::FN);   // MFMAs per LDS operand read
+  issue_stage(0);
+  issue_stage(1);
+  wait_vmcnt<T::WLOADS>();
+  __builtin_amdgcn_s_barrier();
+  load_frags(0, 0, 0);
+  for (int kt = 0; kt < nk; kt++) {
+#pragma unroll
+    for (int kk = 0; kk < 3; kk++) {
+      load_frags((kk + 1) & 1, kt, kk + 1);
+      if (kk < 2) stat_row(kt, kk);
+      mfma_step(kk & 1);
+#pragma unroll
+      for (int i = 0; i < T::FM + T::FN; i++) {
+        __builtin_amdgcn_sched_group_barrier(0x008, MPR, 0);   // MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     // DS read
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    wait_vmcnt<0>();                       // this wavefront's part of slice kt+1 has landed
+    wait_lgkmcnt0();                       // and its reads of stage kt%2 are complete
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    issue_stage(kt + 2);
+    load_frags(0, kt + 1, 0);
+    mfma_step(1);
+#pragma unroll
+    for (int i = 0; i < T::FM * T::FN; i++) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);     // MFMA
+      if (i < T::WLOADS) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // VMEM read (global -> LDS)
+      if (i % MPR == MPR - 1) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     // DS read
+    }
+    __builtin_amdgcn_sched_barrier(0);
   }
+  wait_vmcnt<0>();
 
   // ---- per-row sum of squares gathered from the A slices ---------------------------------------
+  __syncthreads();  // main-loop LDS is dead from here on
   if constexpr (STAT_A) {
-#pragma unroll
-    for (int i = 0; i < T::ACH; i++) {
-      float s = ssq[i];
-      s += __shfl_xor(s, 1);
-      s += __shfl_xor(s, 2);
-      s += __shfl_xor(s, 4);
-      if (kc == 0) sStat[r0 + i * (T::NT / 8)] = s;
-    }
+    if (tid < T::BM) sStat[tid] = ssq;
+    __syncthreads();
   }
-  __syncthreads();  // main-loop LDS is dead from here on; sStat is visible
 
   // ---- epilogue: accumulators -> LDS (per-wave region) -> row-contiguous 8-wide vectors ---------
   const Epilogue& e = op.epi;
@@ -209,7 +258,9 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
         sC[rl * T::CS + j * 32 + (lane & 31)] = acc[i][j][v];
       }
     });
-    __syncthreads();
+    // No barrier: the staging region belongs to this wavefront alone and a wavefront's LDS operations
+    // complete in order.  (A workgroup barrier here would also wait for the global stores of the
+    // previous pass, serialising the passes on the store round trip.)
 #pragma unroll
     for (int p = 0; p < 32 / RPP; p++) {
       const int rl = p * RPP + rsub;
@@ -255,7 +306,6 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
         }
       }
     }
-    __syncthreads();
   });
 }
 
