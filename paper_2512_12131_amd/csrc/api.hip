@@ -54,6 +54,10 @@ void gemm(Ctx& c, GemmOp op) {
     LAUNCH(c, gemm_f32(op, c.st));
     return;
   }
+  if (gemm_bf16_kmajor_ok(op)) {   // weight gradient: both operands k-major, read in place
+    LAUNCH(c, gemm_bf16(op, c.st));
+    return;
+  }
   const size_t m = c.mark();
   if (op.transA) {
     // only un-batched k-major A operands occur (weight gradients)

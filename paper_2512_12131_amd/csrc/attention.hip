@@ -29,6 +29,9 @@ constexpr float LOG2E = 1.4426950408889634f;
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 
+// raw v_exp_f32 (2^x): the arguments here are differences to a running maximum, never denormal-critical
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
 __device__ __forceinline__ bf16x8 lds_b128(const unsigned char* p) { return *reinterpret_cast<const bf16x8*>(p); }
 
 // A operand of a 32x32x16 MFMA whose 32 rows are 32 consecutive columns (c0..c0+31) of an LDS tile
@@ -122,7 +125,7 @@ constexpr int FWD_LDS = 2 * (KT * PB + KT * PT);
 // forward
 // ----------------------------------------------------------------------------------------------
 template <int MB>
-__global__ __launch_bounds__(256) void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
+__global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                                                        const uint16_t* __restrict__ v, uint16_t* __restrict__ o,
                                                        float* __restrict__ lse, int64_t ld, int S, int H, float scale) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -190,24 +193,30 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const uint16_t* __restric
           for (int mb = 0; mb < MB; mb++)
             st[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[mb][ks], st[nb][mb], 0, 0, 0);
         }
-      const bool need_mask = (key0 + KT - 1 > qw0) || (key0 + KT > S);
+      const bool need_mask = (key0 + KT - 1 > qw0) || (key0 + KT > S);   // wavefront-uniform: diagonal / tail tile
+      if (need_mask) {
+#pragma unroll
+        for (int mb = 0; mb < MB; mb++) {
+          const int qi = qw0 + mb * 32 + (lane & 31);
+#pragma unroll
+          for (int nb = 0; nb < 2; nb++)
+#pragma unroll
+            for (int e = 0; e < 16; e++) {
+              const int key = key0 + nb * 32 + acc_row(e, lane);
+              st[nb][mb][e] = (key > qi || key >= S) ? -INFINITY : st[nb][mb][e];
+            }
+        }
+      }
 #pragma unroll
       for (int mb = 0; mb < MB; mb++) {
-        const int qi = qw0 + mb * 32 + (lane & 31);
         float mx = -INFINITY;
 #pragma unroll
         for (int nb = 0; nb < 2; nb++)
 #pragma unroll
-          for (int e = 0; e < 16; e++) {
-            if (need_mask) {
-              const int key = key0 + nb * 32 + acc_row(e, lane);
-              if (key > qi || key >= S) st[nb][mb][e] = -INFINITY;
-            }
-            mx = fmaxf(mx, st[nb][mb][e]);
-          }
+          for (int e = 0; e < 16; e++) mx = fmaxf(mx, st[nb][mb][e]);
         mx = fmaxf(mx, __shfl_xor(mx, 32));
         const float mnew = fmaxf(mrun[mb], mx);          // finite: key 0 is visible to every query
-        const float alpha = exp2f((mrun[mb] - mnew) * c);
+        const float alpha = fast_exp2((mrun[mb] - mnew) * c);
         mrun[mb] = mnew;
         const float mc = mnew * c;
         float rs = 0.f;
@@ -215,15 +224,18 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(const uint16_t* __restric
         for (int nb = 0; nb < 2; nb++)
 #pragma unroll
           for (int e = 0; e < 16; e++) {
-            const float p = exp2f(fmaf(st[nb][mb][e], c, -mc));
+            const float p = fast_exp2(fmaf(st[nb][mb][e], c, -mc));
             st[nb][mb][e] = p;
             rs += p;
           }
         lrun[mb] = lrun[mb] * alpha + rs;
+        // the running maximum settles after the first tiles: skip the rescale when no lane needs it
+        if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {
 #pragma unroll
-        for (int hb = 0; hb < 4; hb++)
+          for (int hb = 0; hb < 4; hb++)
 #pragma unroll
-          for (int e = 0; e < 16; e++) oacc[mb][hb][e] *= alpha;
+            for (int e = 0; e < 16; e++) oacc[mb][hb][e] *= alpha;
+        }
       }
       // ---- O^T += V^T P^T ----
 #pragma unroll
@@ -346,39 +358,39 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const uint16_t* __rest
     const unsigned char* sKt = sKb + KT * PB;
     const unsigned char* sVb = sKt + KT * PT;
     const int key0 = j * KT;
-    if (key0 <= qw0 + 31) {
-      f32x16 st[2], dp[2];
+    // one 32-key block at a time; blocks entirely after this wavefront's queries are skipped
+#pragma unroll 1
+    for (int nb = 0; nb < 2; nb++) {
+      const int kb0 = key0 + nb * 32;
+      if (kb0 > qw0 + 31 || kb0 >= S) continue;
+      f32x16 st, dp;
 #pragma unroll
-      for (int nb = 0; nb < 2; nb++)
+      for (int e = 0; e < 16; e++) { st[e] = 0.f; dp[e] = 0.f; }
 #pragma unroll
-        for (int e = 0; e < 16; e++) { st[nb][e] = 0.f; dp[nb][e] = 0.f; }
+      for (int ks = 0; ks < 8; ks++) {
+        const int off = (nb * 32 + (lane & 31)) * PB + (ks * 2 + (lane >> 5)) * 16;
+        st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_b128(sKb + off), qf[0][ks], st, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_b128(sVb + off), dof[0][ks], dp, 0, 0, 0);
+      }
+      // dS^T = P^T * (dP^T - D), masked on the diagonal / tail blocks only
+      const bool need_mask = (kb0 + 31 > qw0) || (kb0 + 32 > S);
 #pragma unroll
-      for (int ks = 0; ks < 8; ks++)
-#pragma unroll
-        for (int nb = 0; nb < 2; nb++) {
-          const int off = (nb * 32 + (lane & 31)) * PB + (ks * 2 + (lane >> 5)) * 16;
-          st[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_b128(sKb + off), qf[0][ks], st[nb], 0, 0, 0);
-          dp[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_b128(sVb + off), dof[0][ks], dp[nb], 0, 0, 0);
+      for (int e = 0; e < 16; e++) {
+        float p = fast_exp2(fmaf(st[e], c, -lse2));
+        if (need_mask) {
+          const int key = kb0 + acc_row(e, lane);
+          p = (key > qi || key >= S) ? 0.f : p;
         }
-      // dS^T = P^T * (dP^T - D), masked
+        st[e] = p * (dp[e] - Dq);
+      }
 #pragma unroll
-      for (int nb = 0; nb < 2; nb++)
+      for (int t = 0; t < 2; t++) {
+        const bf16x8 dsf = pack_acc_half(st, t);
 #pragma unroll
-        for (int e = 0; e < 16; e++) {
-          const int key = key0 + nb * 32 + acc_row(e, lane);
-          const float p = (key > qi || key >= S) ? 0.f : exp2f(fmaf(st[nb][e], c, -lse2));
-          st[nb][e] = p * (dp[nb][e] - Dq);
-        }
-#pragma unroll
-      for (int nb = 0; nb < 2; nb++)
-#pragma unroll
-        for (int t = 0; t < 2; t++) {
-          const bf16x8 dsf = pack_acc_half(st[nb], t);
-#pragma unroll
-          for (int hb = 0; hb < 4; hb++)
-            acc[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr_frag(sKt, nb * 32 + t * 16, hb * 32, lane), dsf,
-                                                              acc[hb], 0, 0, 0);
-        }
+        for (int hb = 0; hb < 4; hb++)
+          acc[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr_frag(sKt, nb * 32 + t * 16, hb * 32, lane), dsf,
+                                                            acc[hb], 0, 0, 0);
+      }
     }
     if (more) {
       unsigned char* nx = smem + (cur ^ 1) * STAGE;
@@ -468,43 +480,41 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const uint16_t* __res
     }
     stage_ptrs(cur, qB, qT, dB, dT, sl, sd);
     const int qt0 = j * KT;
-    if (qt0 + KT - 1 >= nw0) {                             // some query of the tile sees this wavefront's keys
-      f32x16 st[2], dp[2];                                 // [qblock]: rows = queries, column = key
+    // one 32-query block at a time (keeps the register footprint down); blocks entirely before this
+    // wavefront's keys are skipped, blocks entirely after them need no mask
+#pragma unroll 1
+    for (int qb2 = 0; qb2 < 2; qb2++) {
+      const int qb0 = qt0 + qb2 * 32;
+      if (qb0 + 31 < nw0 || qb0 >= S) continue;
+      f32x16 st, dp;                                       // rows = queries, column = key
 #pragma unroll
-      for (int qb2 = 0; qb2 < 2; qb2++)
+      for (int e = 0; e < 16; e++) { st[e] = 0.f; dp[e] = 0.f; }
 #pragma unroll
-        for (int e = 0; e < 16; e++) { st[qb2][e] = 0.f; dp[qb2][e] = 0.f; }
+      for (int ks = 0; ks < 8; ks++) {
+        const int off = (qb2 * 32 + (lane & 31)) * PB + (ks * 2 + (lane >> 5)) * 16;
+        st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_b128(qB + off), kf[0][ks], st, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_b128(dB + off), vf[0][ks], dp, 0, 0, 0);
+      }
+      const bool need_mask = (qb0 < nw0 + 31) || (qb0 + 32 > S);
 #pragma unroll
-      for (int ks = 0; ks < 8; ks++)
+      for (int e = 0; e < 16; e++) {
+        const int ql = qb2 * 32 + acc_row(e, lane);
+        float p = fast_exp2(fmaf(st[e], c, -sl[ql]));
+        if (need_mask) p = (ni > qt0 + ql || qt0 + ql >= S) ? 0.f : p;
+        st[e] = p;                                         // P
+        dp[e] = p * (dp[e] - sd[ql]);                      // dS
+      }
 #pragma unroll
-        for (int qb2 = 0; qb2 < 2; qb2++) {
-          const int off = (qb2 * 32 + (lane & 31)) * PB + (ks * 2 + (lane >> 5)) * 16;
-          st[qb2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_b128(qB + off), kf[0][ks], st[qb2], 0, 0, 0);
-          dp[qb2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_b128(dB + off), vf[0][ks], dp[qb2], 0, 0, 0);
+      for (int t = 0; t < 2; t++) {
+        const bf16x8 pf = pack_acc_half(st, t), dsf = pack_acc_half(dp, t);
+#pragma unroll
+        for (int hb = 0; hb < 4; hb++) {
+          akv[1][hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr_frag(dT, qb2 * 32 + t * 16, hb * 32, lane), pf,
+                                                               akv[1][hb], 0, 0, 0);
+          akv[0][hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr_frag(qT, qb2 * 32 + t * 16, hb * 32, lane), dsf,
+                                                               akv[0][hb], 0, 0, 0);
         }
-#pragma unroll
-      for (int qb2 = 0; qb2 < 2; qb2++)
-#pragma unroll
-        for (int e = 0; e < 16; e++) {
-          const int ql = qb2 * 32 + acc_row(e, lane);
-          const int qg = qt0 + ql;
-          const float p = (ni > qg || qg >= S) ? 0.f : exp2f(fmaf(st[qb2][e], c, -sl[ql]));
-          st[qb2][e] = p;                                  // P
-          dp[qb2][e] = p * (dp[qb2][e] - sd[ql]);          // dS
-        }
-#pragma unroll
-      for (int qb2 = 0; qb2 < 2; qb2++)
-#pragma unroll
-        for (int t = 0; t < 2; t++) {
-          const bf16x8 pf = pack_acc_half(st[qb2], t), dsf = pack_acc_half(dp[qb2], t);
-#pragma unroll
-          for (int hb = 0; hb < 4; hb++) {
-            akv[1][hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr_frag(dT, qb2 * 32 + t * 16, hb * 32, lane), pf,
-                                                                 akv[1][hb], 0, 0, 0);
-            akv[0][hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr_frag(qT, qb2 * 32 + t * 16, hb * 32, lane), dsf,
-                                                                 akv[0][hb], 0, 0, 0);
-          }
-        }
+      }
     }
     if (more) {
       stage_ptrs(cur ^ 1, qB, qT, dB, dT, sl, sd);

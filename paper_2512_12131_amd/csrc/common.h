@@ -59,6 +59,8 @@ int gemm_bf16_rowpart_slabs(int N);
 // Chooses a split-K factor for a weight-gradient GEMM with K = T.
 int gemm_bf16_pick_splitk(int M, int N, int K, int batch);
 hipError_t gemm_bf16(const GemmOp& op, hipStream_t st);
+// true when gemm_bf16 can run `op` with both operands k-major (no transposed copies needed)
+bool gemm_bf16_kmajor_ok(const GemmOp& op);
 hipError_t gemm_f32(const GemmOp& op, hipStream_t st);
 
 // ---- streaming kernels (stream_kernels.hip) ---------------------------------------------------

@@ -86,8 +86,14 @@ __device__ __forceinline__ void tile_of_block(int bid, int total, int tiles_m, i
 
 #define LRB_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 
-template <class T, int KIND, bool STAT_A>
+// KM = false: operands k-contiguous, A[m][k], B[n][k].
+// KM = true:  operands k-major,      A[k][m], B[k][n]  (weight gradients: k runs over tokens).  The
+//             slices are stored in LDS as they arrive, [k][m], and the MFMA operands are gathered
+//             with the LDS transpose read, so no transposed copy of an activation is ever written.
+template <class T, int KIND, bool STAT_A, bool KM>
 __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, int tiles_m, int tiles_n) {
+  static_assert(!KM || (KIND == EPI_PARTIAL && !STAT_A && T::BM == 256 && T::BN % 128 == 0),
+                "the k-major form only serves split-K weight gradients");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   float* sStat = reinterpret_cast<float*>(smem + T::LDS_BYTES - T::STAT_BYTES);
 
@@ -113,21 +119,41 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
   // resource size: the load returns zeros and zeros are what reaches LDS.
   constexpr uint32_t OOB = 0x80000000u;
   const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc(
-      (void*)(A + (int64_t)m0 * op.lda + kbeg), 0, 0x7fffffff, 0x00020000);
+      (void*)(KM ? A + (int64_t)kbeg * op.lda + m0 : A + (int64_t)m0 * op.lda + kbeg), 0, 0x7fffffff, 0x00020000);
   const __amdgpu_buffer_rsrc_t rsB = __builtin_amdgcn_make_buffer_rsrc(
-      (void*)(B + (int64_t)n0 * op.ldb + kbeg), 0, 0x7fffffff, 0x00020000);
-  const int lrow = lane >> 3;                              // row inside the 8-row group
-  const int lchunk = (lane & 7) ^ lrow;                    // logical 16-byte chunk this lane fetches
+      (void*)(KM ? B + (int64_t)kbeg * op.ldb + n0 : B + (int64_t)n0 * op.ldb + kbeg), 0, 0x7fffffff, 0x00020000);
+  // k-contiguous form: 8 rows x 128 B per wavefront load; k-major form: 2 k-rows x 512 B (BM = 256
+  // columns) or 4 k-rows x 256 B (128 columns).  In both, the 16-byte chunk index inside a row is
+  // XOR-swizzled so that the operand reads spread over the banks.
+  const int lrow = KM ? 0 : lane >> 3;
+  const int lchunk = KM ? 0 : (lane & 7) ^ lrow;
   uint32_t goff[T::WLOADS];
+  int kml_a = 0, kml_b = 0;          // KM: k-row (inside the slice, modulo the per-load stride) of this lane
 #pragma unroll
   for (int i = 0; i < T::WLOADS; i++) {
-    const int g = wave + T::NW * i;                        // 8-row group: A groups first, then B
-    if (i < T::WLOADS_A) {
-      const int row = g * 8 + lrow;
-      goff[i] = (m0 + row) < op.M ? (uint32_t)(row * (int)op.lda + lchunk * 8) * 2u : OOB;
+    const int g = wave + T::NW * i;                        // 1 KB group: A groups first, then B
+    if constexpr (!KM) {
+      if (i < T::WLOADS_A) {
+        const int row = g * 8 + lrow;
+        goff[i] = (m0 + row) < op.M ? (uint32_t)(row * (int)op.lda + lchunk * 8) * 2u : OOB;
+      } else {
+        const int row = (g - T::BM / 8) * 8 + lrow;
+        goff[i] = (n0 + row) < op.N ? (uint32_t)(row * (int)op.ldb + lchunk * 8) * 2u : OOB;
+      }
     } else {
-      const int row = (g - T::BM / 8) * 8 + lrow;
-      goff[i] = (n0 + row) < op.N ? (uint32_t)(row * (int)op.ldb + lchunk * 8) * 2u : OOB;
+      if (i < T::WLOADS_A) {
+        constexpr int CPR = T::BM / 8, RPL = 64 / CPR;       // chunks per k-row, k-rows per wavefront load
+        const int krow = g * RPL + lane / CPR;
+        const int lc = (lane % CPR) ^ ((krow & 7) << 2);
+        goff[i] = (m0 + lc * 8) < op.M ? (uint32_t)(krow * (int)op.lda + lc * 8) * 2u : OOB;
+        if (i == 0) kml_a = krow;
+      } else {
+        constexpr int CPR = T::BN / 8, RPL = 64 / CPR;
+        const int krow = (g - T::BM / 8) * RPL + lane / CPR;
+        const int lc = (lane % CPR) ^ (((krow & 7) << 2) & (CPR - 1));
+        goff[i] = (n0 + lc * 8) < op.N ? (uint32_t)(krow * (int)op.ldb + lc * 8) * 2u : OOB;
+        if (i == T::WLOADS_A) kml_b = krow;
+      }
     }
   }
   // Each workgroup walks its k range from a different starting slice (the sum does not care about
@@ -137,16 +163,35 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
   auto issue_stage = [&](int kt) {
     int kte = kt + rot;
     if (kte >= nk) kte -= nk;
-    const uint32_t kmask = (kt < nk && (kbeg + kte * BK + lchunk * 8) < kend) ? 0u : OOB;
-    const uint32_t ktoff = (uint32_t)kte * (BK * 2);
     unsigned char* dst = smem + (kt % NST) * T::STAGE + wave * 1024;
+    if constexpr (!KM) {
+      const uint32_t kmask = (kt < nk && (kbeg + kte * BK + lchunk * 8) < kend) ? 0u : OOB;
+      const uint32_t ktoff = (uint32_t)kte * (BK * 2);
 #pragma unroll
-    for (int i = 0; i < T::WLOADS; i++) {
-      const int voff = (int)((goff[i] + ktoff) | kmask);
-      if (i < T::WLOADS_A)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, LRB_LDS_PTR(dst + i * (T::NW * 1024)), 16, voff, 0, 0, 0);
-      else
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, LRB_LDS_PTR(dst + i * (T::NW * 1024)), 16, voff, 0, 0, 0);
+      for (int i = 0; i < T::WLOADS; i++) {
+        const int voff = (int)((goff[i] + ktoff) | kmask);
+        if (i < T::WLOADS_A)
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, LRB_LDS_PTR(dst + i * (T::NW * 1024)), 16, voff, 0, 0, 0);
+        else
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, LRB_LDS_PTR(dst + i * (T::NW * 1024)), 16, voff, 0, 0, 0);
+      }
+    } else {
+      // k-rows of load i: kml + i * (NW * rows-per-load); rows at or past the end of k read as zeros
+      constexpr int RPL_A = 64 / (T::BM / 8), RPL_B = 64 / (T::BN / 8);
+      const int krem = kt < nk ? (kend - kbeg) - kte * BK : 0;      // valid k-rows left from this slice's start
+      const uint32_t offa = (uint32_t)kte * BK * (uint32_t)op.lda * 2u, offb = (uint32_t)kte * BK * (uint32_t)op.ldb * 2u;
+#pragma unroll
+      for (int i = 0; i < T::WLOADS; i++) {
+        if (i < T::WLOADS_A) {
+          const uint32_t km = (kml_a + i * T::NW * RPL_A) < krem ? 0u : OOB;
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, LRB_LDS_PTR(dst + i * (T::NW * 1024)), 16,
+                                                   (int)((goff[i] + offa) | km), 0, 0, 0);
+        } else {
+          const uint32_t km = (kml_b + (i - T::WLOADS_A) * T::NW * RPL_B) < krem ? 0u : OOB;
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, LRB_LDS_PTR(dst + i * (T::NW * 1024)), 16,
+                                                   (int)((goff[i] + offb) | km), 0, 0, 0);
+        }
+      }
     }
   };
 
@@ -162,13 +207,40 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
   const int frow = lane & 31, fk = lane >> 5, fsw = frow & 7;
   bf16x8 af[2][T::FM], bf[2][T::FN];
   auto load_frags = [&](int buf, int kt, int kk) {
-    const unsigned char* sa = smem + (kt % NST) * T::STAGE + (wm * T::TM + frow) * 128;
-    const unsigned char* sb = smem + (kt % NST) * T::STAGE + T::A_BYTES + (wn * T::TN + frow) * 128;
-    const int coff = ((kk * 2 + fk) ^ fsw) << 4;
+    if constexpr (!KM) {
+      const unsigned char* sa = smem + (kt % NST) * T::STAGE + (wm * T::TM + frow) * 128;
+      const unsigned char* sb = smem + (kt % NST) * T::STAGE + T::A_BYTES + (wn * T::TN + frow) * 128;
+      const int coff = ((kk * 2 + fk) ^ fsw) << 4;
 #pragma unroll
-    for (int i = 0; i < T::FM; i++) af[buf][i] = *reinterpret_cast<const bf16x8*>(sa + i * 32 * 128 + coff);
+      for (int i = 0; i < T::FM; i++) af[buf][i] = *reinterpret_cast<const bf16x8*>(sa + i * 32 * 128 + coff);
 #pragma unroll
-    for (int j = 0; j < T::FN; j++) bf[buf][j] = *reinterpret_cast<const bf16x8*>(sb + j * 32 * 128 + coff);
+      for (int j = 0; j < T::FN; j++) bf[buf][j] = *reinterpret_cast<const bf16x8*>(sb + j * 32 * 128 + coff);
+    } else {
+      // Transpose reads.  Inside each group of 16 lanes, lane s supplies the address of 4 consecutive
+      // columns of k-row (s/4) and receives column s of the 4 x 16 block; two reads (k-rows +0 and +8)
+      // give the 8 k slots of a lane: slot (half, e) -> k = kk*16 + (e/4)*8 + half*4 + e%4, the same
+      // assignment for both operands.
+      const int g = lane >> 4, sl = lane & 15;
+      const int krow = kk * 16 + (g >> 1) * 4 + (sl >> 2);
+      const int ksw = (krow & 7) << 2;                      // (krow + 8) & 7 is the same
+      const int cin = (g & 1) * 16 + (sl & 3) * 4;          // column inside the 32-column block
+      const unsigned char* sa = smem + (kt % NST) * T::STAGE + krow * (T::BM * 2);
+      const unsigned char* sb = smem + (kt % NST) * T::STAGE + T::A_BYTES + krow * (T::BN * 2);
+      typedef short s16x4 __attribute__((ext_vector_type(4)));
+      typedef short s16x8 __attribute__((ext_vector_type(8)));
+      auto tr_pair = [&](const unsigned char* base, int pitch, int col, int swz) -> bf16x8 {
+        const int off = (((col >> 3) ^ swz) << 4) + (col & 7) * 2;
+        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(base + off));
+        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(base + 8 * pitch + off));
+        s16x8 r = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        return __builtin_bit_cast(bf16x8, r);
+      };
+#pragma unroll
+      for (int i = 0; i < T::FM; i++) af[buf][i] = tr_pair(sa, T::BM * 2, wm * T::TM + i * 32 + cin, ksw);
+#pragma unroll
+      for (int j = 0; j < T::FN; j++)
+        bf[buf][j] = tr_pair(sb, T::BN * 2, wn * T::TN + j * 32 + cin, ksw & (T::BN / 8 - 1));
+    }
   };
   auto mfma_step = [&](int buf) {
 #pragma unroll
@@ -214,7 +286,7 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
 #pragma unroll
       for (int i = 0; i < T::FM + T::FN; i++) {
         __builtin_amdgcn_sched_group_barrier(0x008, MPR, 0);   // MFMA
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     // DS read
+        __builtin_amdgcn_sched_group_barrier(0x100, KM ? 2 : 1, 0);     // DS read
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -229,7 +301,7 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
     for (int i = 0; i < T::FM * T::FN; i++) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);     // MFMA
       if (i < T::WLOADS) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // VMEM read (global -> LDS)
-      if (i % MPR == MPR - 1) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     // DS read
+      if (i % MPR == MPR - 1) __builtin_amdgcn_sched_group_barrier(0x100, KM ? 2 : 1, 0);     // DS read
     }
     __builtin_amdgcn_sched_barrier(0);
   }
@@ -310,10 +382,10 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
 }
 
 // ---------------------------------------------------------------------------------------------
-template <class T, int KIND, bool STAT_A>
+template <class T, int KIND, bool STAT_A, bool KM = false>
 hipError_t launch(const GemmOp& op, hipStream_t st) {
   static bool attr_set = false;  // one-time opt-in to > 64 KB of dynamic LDS for this instantiation
-  auto kern = gemm_bf16_kernel<T, KIND, STAT_A>;
+  auto kern = gemm_bf16_kernel<T, KIND, STAT_A, KM>;
   if (!attr_set) {
     hipError_t err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
     if (err != hipSuccess) return err;
@@ -366,8 +438,19 @@ int gemm_bf16_pick_splitk(int M, int N, int K, int batch) {
   return s;
 }
 
+bool gemm_bf16_kmajor_ok(const GemmOp& op) {
+  // both operands k-major, fp32 partial output, offsets within the 2 GB a buffer resource addresses
+  return op.transA && op.transB && op.batch == 1 && op.epi.kind == EPI_PARTIAL && op.M % 8 == 0 && op.N % 8 == 0 &&
+         (int64_t)op.K * op.lda * 2 < 0x7fffffffLL && (int64_t)op.K * op.ldb * 2 < 0x7fffffffLL;
+}
+
 hipError_t gemm_bf16(const GemmOp& op, hipStream_t st) {
   if (op.M <= 0 || op.N <= 0 || op.batch <= 0) return hipSuccess;
+  if (op.transA && op.transB) {
+    if (!gemm_bf16_kmajor_ok(op)) return hipErrorInvalidValue;
+    if (use_big_tile(op.N)) return launch<TileBig, EPI_PARTIAL, false, true>(op, st);
+    return launch<TileMid, EPI_PARTIAL, false, true>(op, st);
+  }
   if (op.transA || op.transB) return hipErrorInvalidValue;
   if (op.epi.stat_from_a && op.splitk > 1) return hipErrorInvalidValue;
   if (use_big_tile(op.N)) return dispatch<TileBig>(op, st);
