@@ -91,44 +91,59 @@ def main():
     fl = block_flops(Bn, S, d, H, f, r)
     value = fl["exec"] / dt / 1e12
 
-    # ---- roofline of the dominant kernel class: the forward grouped down-projection GEMM
-    # (x[T,d] . w_dn_qkv[3r,d]^T with the online-RMSNorm epilogue), timed with HIP events on the
-    # stream it is launched on, through the same entry point the block uses for it.
+    # ---- roofline of the dominant kernel: gemm_bf16_kernel (all of the block's projection GEMMs,
+    # forward, re-forward, data-gradient and weight-gradient launches).  The same K steps are run
+    # again with the library's launch timer on: every GEMM launch is bracketed by HIP events on the
+    # stream it runs on, and the summed intervals give the average launch duration.
     T = Bn * S
-    G = 3
-    wdn, wup = params["w_dn_qkv"], params["w_up_qkv"]
-    nb = B.lr_group_workspace_bytes(G, T, d, r, d, B.LR_BF16, 0)
-    gws = torch.empty(nb, dtype=torch.uint8, device=dev)
-    z = torch.empty((T, G * r), dtype=torch.bfloat16, device=dev)
-    stat = torch.empty((T,), dtype=torch.float32, device=dev)
-    yq = torch.empty((G, T, d), dtype=torch.bfloat16, device=dev)
-    import ctypes as C
-    L = B.lib()
-    stream = torch.cuda.current_stream()
-
-    def group_fwd():
-        st = L.lr_group_fwd(x.data_ptr(), d, params["gamma1"].data_ptr(), eps, B.LR_NORM_ONLINE, wdn.data_ptr(),
-                            wup.data_ptr(), z.data_ptr(), stat.data_ptr(), yq.data_ptr(), d, T * d, G, T, d, r, d,
-                            B.LR_ACT_SILU, B.LR_BF16, gws.data_ptr(), nb, C.c_void_p(stream.cuda_stream))
-        assert st == 0
-
-    for _ in range(2):
-        group_fwd()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    reps = 10
-    stream.synchronize()
-    e0.record(stream)
-    for _ in range(reps):
-        group_fwd()
-    e1.record(stream)
-    e1.synchronize()
-    g_ms = e0.elapsed_time(e1) / reps
-    g_flops = 2.0 * T * d * (G * r) + G * 2.0 * T * r * d     # grouped down GEMM + batched up GEMM
-    achieved = g_flops / (g_ms * 1e-3) / 1e12
+    B.lr_gemm_timer_begin(64 * max(args.steps, 1) + 64)
+    for _ in range(args.steps):
+        step()
+    gemm_ms, gemm_launches = B.lr_gemm_timer_end()
+    launches_per_step = gemm_launches / max(args.steps, 1)
+    avg_launch_ms = gemm_ms / max(gemm_launches, 1)
+    flops_per_launch = fl["gemm_exec"] / launches_per_step        # algorithmic FLOPs (2MNK) per launch
+    achieved = flops_per_launch / (avg_launch_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
-                "kernel": "gemm_bf16_kernel (grouped down-projection + batched up-projection of Q/K/V)",
-                "ms_per_launch_pair": round(g_ms, 4)}
+                "kernel": "gemm_bf16_kernel (bf16 MFMA GEMM, all instantiations)",
+                "launches_per_step": round(launches_per_step, 1), "avg_launch_us": round(avg_launch_ms * 1e3, 2),
+                "gemm_ms_per_step": round(gemm_ms / max(args.steps, 1), 3),
+                "gflop_per_launch": round(flops_per_launch / 1e9, 2)}
+
+    # ---- the memory-bound kernels against the HBM peak (fp32 statistic / bf16 tensors >= 0.5 GB so that
+    # the 256 MB last-level cache cannot hold them)
+    def time_ms(fn, reps=5):
+        for _ in range(2):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    Ts, fs = 32768, 11008
+    g = torch.randn((Ts, fs), device=dev, dtype=torch.bfloat16)
+    u = torch.randn((Ts, fs), device=dev, dtype=torch.bfloat16)
+    nbytes = Ts * fs * 2
+    stream_kernels = {}
+    t = time_ms(lambda: B.lr_rms_stat(g))
+    stream_kernels["lr_rms_stat"] = round(nbytes / t / 1e6, 1)
+    t = time_ms(lambda: B.lr_swiglu_fwd(g, u))
+    stream_kernels["lr_swiglu_fwd"] = round(3 * nbytes / t / 1e6, 1)
+    t = time_ms(lambda: B.lr_swiglu_bwd(g, u, g))
+    stream_kernels["lr_swiglu_bwd"] = round(5 * nbytes / t / 1e6, 1)
+    xs = g[:, :4096].contiguous()
+    gam = torch.ones((4096,), device=dev, dtype=torch.bfloat16)
+    st_ = B.lr_rms_stat(xs)
+    t = time_ms(lambda: B.lr_rmsnorm_bwd(xs, gam, st_, eps, xs, xs))
+    stream_kernels["lr_rmsnorm_bwd"] = round(5 * Ts * 4096 * 2 / t / 1e6, 1)
+    del g, u, xs
+    stream = {"unit": "GB/s", "peak": HBM_PEAK_GBS, "algorithmic_bytes_over_time": stream_kernels,
+              "frac": {k: round(v / HBM_PEAK_GBS, 3) for k, v in stream_kernels.items()}}
 
     out = {
         "metric": "TFLOP/s + % MFMA bf16 peak, low-rank decoder block fwd+bwd (1 MI355X)",
@@ -142,6 +157,7 @@ def main():
                    "frac_mfma_peak_executed": round(value / MFMA_BF16_PEAK_TFLOPS, 4),
                    "model_tflops": round(fl["model"] / dt / 1e12, 2)},
         "roofline": roofline,
+        "hbm_bound_kernels": stream,
     }
 
     if not args.no_cpu_baseline:
@@ -149,7 +165,7 @@ def main():
         # first `s_len` tokens of batch element 0.
         import numpy as np
         from oracle import lowrank_oracle as orc
-        s_len = min(S, 256)
+        s_len = S   # all of batch element 0: about 10 s of fp64 work at the 7B shape
         P = {k: si.f64(v) for k, v in case["params"].items()}
         X0, DY0 = si.f64(case["x"][:s_len]), si.f64(case["dy"][:s_len])
         t0 = time.perf_counter()

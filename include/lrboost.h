@@ -163,6 +163,16 @@ int lr_attention_bwd(const void* q, const void* k, const void* v, const void* o,
                      int64_t ld, int64_t B, int64_t S, int64_t H, int64_t hd, int causal,
                      int dt, void* ws, size_t ws_bytes, void* stream);
 
+/* ---- measurement aid (not on the compute path) ------------------------------------------ */
+/* Between begin and end every bf16 MFMA GEMM launch the library makes is bracketed by two HIP
+ * events on its stream; end waits for the last one and returns the summed kernel time (HOST
+ * pointers: total_ms, launches).  begin creates max_launches event pairs and end destroys
+ * them: the one place where the library creates runtime objects, and only on request.  Used
+ * by the benchmark to obtain the average GEMM launch duration (Sec. 5.3 of the paper measures
+ * the same quantity per linear layer: kernel time and utilisation).                        */
+int lr_gemm_timer_begin(int max_launches);
+int lr_gemm_timer_end(double* total_ms, int* launches);
+
 /* ---- standalone memory-bound kernels: the unfused twins of the fused epilogues ---------- */
 /* stat[t] = sum_j x[t,j]^2  (Alg. 1 line 1).                                               */
 int lr_rms_stat(const void* x, int64_t ldx, float* stat, int64_t T, int64_t d, int dt,

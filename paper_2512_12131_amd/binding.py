@@ -67,6 +67,8 @@ _SIGS = {
     "lr_attention_bwd_workspace_bytes": (_sz, [_i64, _i64, _i64, _i64]),
     "lr_attention_bwd": (_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _int, _int,
                                 _vp, _sz, _vp]),
+    "lr_gemm_timer_begin": (_int, [_int]),
+    "lr_gemm_timer_end": (_int, [C.POINTER(C.c_double), C.POINTER(_int)]),
     "lr_rms_stat": (_int, [_vp, _i64, _vp, _i64, _i64, _int, _vp]),
     "lr_rmsnorm_apply": (_int, [_vp, _i64, _vp, _vp, _f32, _vp, _i64, _i64, _i64, _int, _vp]),
     "lr_rmsnorm_bwd_parts": (_i64, [_i64]),
@@ -291,6 +293,18 @@ def lr_attention_bwd(q, k, v, o, dout, lse, B, S, H, hd, causal=True):
     _check(lib().lr_attention_bwd(_p(q), _p(k), _p(v), _p(o), _p(dout), _p(lse), _p(dq), _p(dk), _p(dv), _rowmajor(q),
                                   B, S, H, hd, int(causal), _dt(q), _p(ws), ws.numel(), _stream()), "lr_attention_bwd")
     return dq, dk, dv
+
+
+# ---- measurement aid -----------------------------------------------------------------------
+def lr_gemm_timer_begin(max_launches=4096):
+    _check(lib().lr_gemm_timer_begin(max_launches), "lr_gemm_timer_begin")
+
+
+def lr_gemm_timer_end():
+    """Returns (summed GEMM kernel time in ms, number of GEMM launches) since lr_gemm_timer_begin."""
+    ms, n = C.c_double(0.0), C.c_int(0)
+    _check(lib().lr_gemm_timer_end(C.byref(ms), C.byref(n)), "lr_gemm_timer_end")
+    return ms.value, n.value
 
 
 # ---- standalone memory-bound kernels ---------------------------------------------------------

@@ -761,6 +761,12 @@ int lr_attention_bwd(const void* q, const void* k, const void* v, const void* o,
   return e == hipSuccess ? LR_OK : (e == hipErrorNotSupported ? LR_EUNSUPPORTED : LR_ELAUNCH);
 }
 
+// ---- measurement aid ---------------------------------------------------------------------------
+int lr_gemm_timer_begin(int max_launches) { return gemm_timer_begin(max_launches) == 0 ? LR_OK : LR_EINVAL; }
+int lr_gemm_timer_end(double* total_ms, int* launches) {
+  return gemm_timer_end(total_ms, launches) == 0 ? LR_OK : LR_EINVAL;
+}
+
 // ---- standalone memory-bound kernels ---------------------------------------------------------
 int lr_rms_stat(const void* x, int64_t ldx, float* stat, int64_t T, int64_t d, int dt, void* stream) {
   TRY(check_dt(dt));

@@ -62,6 +62,9 @@ hipError_t gemm_bf16(const GemmOp& op, hipStream_t st);
 // true when gemm_bf16 can run `op` with both operands k-major (no transposed copies needed)
 bool gemm_bf16_kmajor_ok(const GemmOp& op);
 hipError_t gemm_f32(const GemmOp& op, hipStream_t st);
+// Benchmark aid: time every bf16 GEMM launch between begin and end with HIP events on its stream.
+int gemm_timer_begin(int max_launches);
+int gemm_timer_end(double* total_ms, int* launches);
 
 // ---- streaming kernels (stream_kernels.hip) ---------------------------------------------------
 hipError_t k_rms_stat(const void* x, int64_t ldx, float* stat, int64_t T, int64_t d, int dt, hipStream_t);

@@ -14,6 +14,7 @@
 // epilogue (C, the auxiliary tiles it reads, the secondary output) is a row-contiguous 16-byte
 // vector.
 #include <type_traits>
+#include <vector>
 
 #include "epilogue.h"
 
@@ -438,13 +439,65 @@ int gemm_bf16_pick_splitk(int M, int N, int K, int batch) {
   return s;
 }
 
+// ---- optional timing of the GEMM launches (for the benchmark's roofline figure) -----------------
+// When enabled, every gemm_bf16 launch is bracketed by two HIP events on the launch stream; the sum of
+// the bracketed intervals is the time the stream spent in these kernels.  Off by default; the events
+// are created by gemm_timer_begin and released by gemm_timer_end, never on the compute path.
+namespace {
+struct GemmTimer {
+  bool on = false;
+  std::vector<hipEvent_t> ev;
+  size_t used = 0;
+} g_timer;
+}  // namespace
+
+int gemm_timer_begin(int max_launches) {
+  if (g_timer.on || max_launches <= 0) return -1;
+  g_timer.ev.resize((size_t)max_launches * 2);
+  for (auto& e : g_timer.ev)
+    if (hipEventCreate(&e) != hipSuccess) return -1;
+  g_timer.used = 0;
+  g_timer.on = true;
+  return 0;
+}
+
+int gemm_timer_end(double* total_ms, int* launches) {
+  if (!g_timer.on) return -1;
+  g_timer.on = false;
+  double sum = 0.0;
+  const size_t n = g_timer.used / 2;
+  if (n > 0) hipEventSynchronize(g_timer.ev[2 * n - 1]);
+  for (size_t i = 0; i < n; i++) {
+    float ms = 0.f;
+    hipEventElapsedTime(&ms, g_timer.ev[2 * i], g_timer.ev[2 * i + 1]);
+    sum += ms;
+  }
+  for (auto& e : g_timer.ev) hipEventDestroy(e);
+  g_timer.ev.clear();
+  if (total_ms) *total_ms = sum;
+  if (launches) *launches = (int)n;
+  return 0;
+}
+
+static hipError_t gemm_bf16_untimed(const GemmOp& op, hipStream_t st);
+
+hipError_t gemm_bf16(const GemmOp& op, hipStream_t st) {
+  if (!g_timer.on || g_timer.used + 2 > g_timer.ev.size() || op.M <= 0 || op.N <= 0 || op.batch <= 0)
+    return gemm_bf16_untimed(op, st);
+  hipEventRecord(g_timer.ev[g_timer.used], st);
+  hipError_t e = gemm_bf16_untimed(op, st);
+  hipEventRecord(g_timer.ev[g_timer.used + 1], st);
+  g_timer.used += 2;
+  return e;
+}
+
 bool gemm_bf16_kmajor_ok(const GemmOp& op) {
   // both operands k-major, fp32 partial output, offsets within the 2 GB a buffer resource addresses
   return op.transA && op.transB && op.batch == 1 && op.epi.kind == EPI_PARTIAL && op.M % 8 == 0 && op.N % 8 == 0 &&
          (int64_t)op.K * op.lda * 2 < 0x7fffffffLL && (int64_t)op.K * op.ldb * 2 < 0x7fffffffLL;
 }
 
-hipError_t gemm_bf16(const GemmOp& op, hipStream_t st) {
+static hipError_t gemm_bf16_untimed(const GemmOp& op, hipStream_t st) {
   if (op.M <= 0 || op.N <= 0 || op.batch <= 0) return hipSuccess;
   if (op.transA && op.transB) {
     if (!gemm_bf16_kmajor_ok(op)) return hipErrorInvalidValue;
