@@ -160,7 +160,9 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
   // Each workgroup walks its k range from a different starting slice (the sum does not care about
   // the order), so that workgroups do not all sit at the same k offset, i.e. on the same L2 / memory
   // channels, when row pitches are powers of two.
-  const int rot = nk > 0 ? ((tm * 5 + tn * 3 + ks * 7) & 15) * 2 % nk : 0;
+  // The start depends on the tile row only through tm % 8, so the summation order of a token row (and
+  // with it every rounding decision) does not depend on how many 2048-token sequences are batched.
+  const int rot = nk > 0 ? (((tm & 7) * 5 + tn * 3 + ks * 7) & 15) * 2 % nk : 0;
   auto issue_stage = [&](int kt) {
     int kte = kt + rot;
     if (kte >= nk) kte -= nk;
