@@ -47,12 +47,25 @@ struct VecIO<bf16_t, 1> {
   }
 };
 
-// v[NV]: accumulators of row m, columns n..n+NV-1 of batch b.  rho / rowb: per-row scalars already
-// resolved by the caller (rho = 1 when unused).  Returns this thread's contribution to the row
-// partial (0 when the epilogue kind has none).
+// Which auxiliary tiles an epilogue kind reads (same shape as C): R and / or R2.
+template <int KIND>
+__device__ __forceinline__ bool epi_reads_r(const Epilogue& e) {
+  if constexpr (KIND == EPI_UP || KIND == EPI_NORMBWD) return e.R != nullptr;
+  return KIND == EPI_ACTGRAD || KIND == EPI_SWIGLU_BWD;
+}
+template <int KIND>
+__device__ __forceinline__ bool epi_reads_r2(const Epilogue&) {
+  return KIND == EPI_NORMBWD || KIND == EPI_SWIGLU_BWD;
+}
+
+// v[NV]: accumulators of row m, columns n..n+NV-1 of batch b; r[NV], r2[NV]: the matching entries of
+// the auxiliary tiles (already loaded; ignored by kinds that do not use them).  rho / rowb: per-row
+// scalars resolved by the caller (rho = 1 when unused).  Applies the fused elementwise work in fp32,
+// rounds once, stores, and returns this thread's contribution to the row partial (0 if none).
 template <typename ST, int NV, int KIND>
-__device__ __forceinline__ float epi_apply(const Epilogue& e, void* C, int64_t ldc, int64_t sC, int b, int64_t m,
-                                           int64_t n, float* v, float rho, float rowb) {
+__device__ __forceinline__ float epi_compute(const Epilogue& e, void* C, int64_t ldc, int64_t sC, int b, int64_t m,
+                                             int64_t n, float* v, float rho, float rowb, const float* r,
+                                             const float* r2) {
   using IO = VecIO<ST, NV>;
   float part = 0.f;
   const int64_t coff = (int64_t)b * sC + m * ldc + n;
@@ -70,8 +83,6 @@ __device__ __forceinline__ float epi_apply(const Epilogue& e, void* C, int64_t l
     }
   } else if constexpr (KIND == EPI_UP) {
     if (e.R) {
-      float r[NV];
-      IO::load(e.R, (int64_t)b * e.sR + m * e.ldr + n, r);
 #pragma unroll
       for (int i = 0; i < NV; i++) v[i] += r[i];
     }
@@ -79,41 +90,46 @@ __device__ __forceinline__ float epi_apply(const Epilogue& e, void* C, int64_t l
 #pragma unroll
     for (int i = 0; i < NV; i++) part += v[i] * v[i];
   } else if constexpr (KIND == EPI_ACTGRAD) {
-    float z[NV];
-    IO::load(e.R, (int64_t)b * e.sR + m * e.ldr + n, z);
 #pragma unroll
     for (int i = 0; i < NV; i++) {
-      v[i] = v[i] * act_prime_f(z[i], e.act) * rho;
-      part += v[i] * z[i];
+      v[i] = v[i] * act_prime_f(r[i], e.act) * rho;
+      part += v[i] * r[i];
     }
     IO::store(C, coff, v);
   } else if constexpr (KIND == EPI_NORMBWD) {
-    float x[NV];
-    IO::load(e.R2, (int64_t)b * e.sR2 + m * e.ldr2 + n, x);
     const float coef = rho * e.inv_d * rowb;
 #pragma unroll
-    for (int i = 0; i < NV; i++) v[i] = v[i] - coef * x[i];
+    for (int i = 0; i < NV; i++) v[i] = v[i] - coef * r2[i];
     if (e.R) {
-      float r[NV];
-      IO::load(e.R, (int64_t)b * e.sR + m * e.ldr + n, r);
 #pragma unroll
       for (int i = 0; i < NV; i++) v[i] += r[i];
     }
     IO::store(C, coff, v);
   } else if constexpr (KIND == EPI_SWIGLU_BWD) {
-    float g[NV], u[NV], du[NV];
-    IO::load(e.R, (int64_t)b * e.sR + m * e.ldr + n, g);
-    IO::load(e.R2, (int64_t)b * e.sR2 + m * e.ldr2 + n, u);
+    float du[NV];
 #pragma unroll
     for (int i = 0; i < NV; i++) {
-      float dm = v[i];
-      du[i] = dm * silu_f(g[i]);
-      v[i] = dm * u[i] * silu_prime_f(g[i]);
+      const float dm = v[i];
+      du[i] = dm * silu_f(r[i]);
+      v[i] = dm * r2[i] * silu_prime_f(r[i]);
     }
     IO::store(C, coff, v);
     IO::store(e.C2, (int64_t)b * e.sC2 + m * e.ldc2 + n, du);
   }
   return part;
+}
+
+// Load the auxiliary entries, then epi_compute.
+template <typename ST, int NV, int KIND>
+__device__ __forceinline__ float epi_apply(const Epilogue& e, void* C, int64_t ldc, int64_t sC, int b, int64_t m,
+                                           int64_t n, float* v, float rho, float rowb) {
+  using IO = VecIO<ST, NV>;
+  float r[NV], r2[NV];
+#pragma unroll
+  for (int i = 0; i < NV; i++) { r[i] = 0.f; r2[i] = 0.f; }
+  if (epi_reads_r<KIND>(e)) IO::load(e.R, (int64_t)b * e.sR + m * e.ldr + n, r);
+  if (epi_reads_r2<KIND>(e)) IO::load(e.R2, (int64_t)b * e.sR2 + m * e.ldr2 + n, r2);
+  return epi_compute<ST, NV, KIND>(e, C, ldc, sC, b, m, n, v, rho, rowb, r, r2);
 }
 
 __device__ __forceinline__ float rho_of(const Epilogue& e, float sumsq) { return rsqrtf(sumsq * e.inv_d + e.eps); }

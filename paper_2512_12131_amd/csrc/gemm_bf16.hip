@@ -318,67 +318,96 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
   }
 
   // ---- epilogue: accumulators -> LDS (per-wave region) -> row-contiguous 8-wide vectors ---------
+  // The wavefront's sub-tile leaves in FM x (32/RPP) passes of RPP rows.  The auxiliary tiles an
+  // epilogue reads (residual, z, x, g, u) are fetched PF passes ahead into a small register ring, so
+  // their latency is covered by the passes in between instead of being paid once per pass.
   const Epilogue& e = op.epi;
   float* sC = reinterpret_cast<float*>(smem) + wave * (32 * T::CS);
   constexpr int LPR = T::TN / 8;            // lanes per output row
   constexpr int RPP = 64 / LPR;             // rows per pass
+  constexpr int PPB = 32 / RPP;             // passes per 32-row block
+  constexpr int NQ = T::FM * PPB;           // passes per wavefront
+  constexpr int PF = 4;                     // prefetch distance, in passes
   const int cg = lane % LPR, rsub = lane / LPR;
-  static_for<T::FM>([&](auto I) {
-    constexpr int i = decltype(I)::value;
-    static_for<T::FN>([&](auto J) {
-      constexpr int j = decltype(J)::value;
-#pragma unroll
-      for (int v = 0; v < 16; v++) {
-        int rl = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        sC[rl * T::CS + j * 32 + (lane & 31)] = acc[i][j][v];
-      }
+  const int64_t gn = (int64_t)n0 + wn * T::TN + cg * 8;
+  const bool use_r = KIND != EPI_PARTIAL && epi_reads_r<KIND>(e), use_r2 = KIND != EPI_PARTIAL && epi_reads_r2<KIND>(e);
+  uint4 auxr[PF], auxr2[PF];
+  auto row_of = [&](int q) { return wm * T::TM + (q / PPB) * 32 + (q % PPB) * RPP + rsub; };   // row inside the tile
+  auto fetch = [&](int q, uint4& ar, uint4& ar2) {
+    const int64_t gm = (int64_t)m0 + row_of(q);
+    ar = make_uint4(0, 0, 0, 0);
+    ar2 = make_uint4(0, 0, 0, 0);
+    if (gm < op.M && gn < op.N) {
+      if (use_r) ar = *reinterpret_cast<const uint4*>((const uint16_t*)e.R + (int64_t)b * e.sR + gm * e.ldr + gn);
+      if (use_r2) ar2 = *reinterpret_cast<const uint4*>((const uint16_t*)e.R2 + (int64_t)b * e.sR2 + gm * e.ldr2 + gn);
+    }
+  };
+  if (use_r || use_r2) {
+    static_for<PF>([&](auto Q) {
+      constexpr int q = decltype(Q)::value;
+      if constexpr (q < NQ) fetch(q, auxr[q], auxr2[q]);
     });
-    // No barrier: the staging region belongs to this wavefront alone and a wavefront's LDS operations
-    // complete in order.  (A workgroup barrier here would also wait for the global stores of the
-    // previous pass, serialising the passes on the store round trip.)
+  }
+  static_for<NQ>([&](auto Q) {
+    constexpr int q = decltype(Q)::value;
+    constexpr int i = q / PPB, p = q % PPB;
+    if constexpr (p == 0) {
+      static_for<T::FN>([&](auto J) {
+        constexpr int j = decltype(J)::value;
 #pragma unroll
-    for (int p = 0; p < 32 / RPP; p++) {
-      const int rl = p * RPP + rsub;
-      const int lm = wm * T::TM + i * 32 + rl;      // row inside the block tile
-      const int64_t gm = (int64_t)m0 + lm;
-      const int64_t gn = (int64_t)n0 + wn * T::TN + cg * 8;
-      float v[8];
-      {
-        const float4 lo = *reinterpret_cast<const float4*>(sC + rl * T::CS + cg * 8);
-        const float4 hi = *reinterpret_cast<const float4*>(sC + rl * T::CS + cg * 8 + 4);
-        v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w;
-        v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
+        for (int v = 0; v < 16; v++) {
+          int rl = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+          sC[rl * T::CS + j * 32 + (lane & 31)] = acc[i][j][v];
+        }
+      });
+      // No barrier: the staging region belongs to this wavefront alone and a wavefront's LDS
+      // operations complete in order.
+    }
+    const int rl = p * RPP + rsub;
+    const int lm = wm * T::TM + i * 32 + rl;      // row inside the block tile
+    const int64_t gm = (int64_t)m0 + lm;
+    float v[8];
+    {
+      const float4 lo = *reinterpret_cast<const float4*>(sC + rl * T::CS + cg * 8);
+      const float4 hi = *reinterpret_cast<const float4*>(sC + rl * T::CS + cg * 8 + 4);
+      v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w;
+      v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
+    }
+    const bool ok = gm < op.M && gn < op.N;
+    float part = 0.f;
+    if constexpr (KIND == EPI_PARTIAL) {
+      if (ok) {
+        float* cp = (float*)op.C + ((int64_t)bz * op.M + gm) * op.N + gn;
+        *reinterpret_cast<float4*>(cp) = make_float4(v[0], v[1], v[2], v[3]);
+        *reinterpret_cast<float4*>(cp + 4) = make_float4(v[4], v[5], v[6], v[7]);
       }
-      const bool ok = gm < op.M && gn < op.N;
-      float part = 0.f;
-      if constexpr (KIND == EPI_PARTIAL) {
-        if (ok) {
-          float* cp = (float*)op.C + ((int64_t)bz * op.M + gm) * op.N + gn;
-          *reinterpret_cast<float4*>(cp) = make_float4(v[0], v[1], v[2], v[3]);
-          *reinterpret_cast<float4*>(cp + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    } else {
+      if (ok) {
+        float rho = 1.f, rowb = 0.f;
+        if (e.use_rho) {
+          float ss;
+          if constexpr (STAT_A) ss = sStat[lm]; else ss = e.rowa[gm];
+          rho = rho_of(e, ss);
         }
-      } else {
-        if (ok) {
-          float rho = 1.f, rowb = 0.f;
-          if (e.use_rho) {
-            float ss;
-            if constexpr (STAT_A) ss = sStat[lm]; else ss = e.rowa[gm];
-            rho = rho_of(e, ss);
-          }
-          if (e.rowb) rowb = e.rowb[gm];
-          part = epi_apply<bf16_t, 8, KIND>(e, op.C, op.ldc, op.sC, b, gm, gn, v, rho, rowb);
-        }
-        if constexpr (KIND == EPI_UP || KIND == EPI_ACTGRAD) {
-          if (e.rowpart) {
+        if (e.rowb) rowb = e.rowb[gm];
+        float r[8], r2[8];
+        unpack8(auxr[q % PF], r);
+        unpack8(auxr2[q % PF], r2);
+        part = epi_compute<bf16_t, 8, KIND>(e, op.C, op.ldc, op.sC, b, gm, gn, v, rho, rowb, r, r2);
+      }
+      if constexpr (q + PF < NQ) {
+        if (use_r || use_r2) fetch(q + PF, auxr[q % PF], auxr2[q % PF]);
+      }
+      if constexpr (KIND == EPI_UP || KIND == EPI_ACTGRAD) {
+        if (e.rowpart) {
 #pragma unroll
-            for (int o = 1; o < LPR; o <<= 1) part += __shfl_xor(part, o);
-            if (cg == 0 && gm < op.M)
-              e.rowpart[gm * e.rowpart_ld + e.rowpart_off + b * (tiles_n * T::WN) + tn * T::WN + wn] = part;
-          }
+          for (int o = 1; o < LPR; o <<= 1) part += __shfl_xor(part, o);
+          if (cg == 0 && gm < op.M)
+            e.rowpart[gm * e.rowpart_ld + e.rowpart_off + b * (tiles_n * T::WN) + tn * T::WN + wn] = part;
         }
-        if constexpr (STAT_A) {
-          if (e.stat_out && tn == 0 && wn == 0 && b == 0 && cg == 0 && gm < op.M) e.stat_out[gm] = sStat[lm];
-        }
+      }
+      if constexpr (STAT_A) {
+        if (e.stat_out && tn == 0 && wn == 0 && b == 0 && cg == 0 && gm < op.M) e.stat_out[gm] = sStat[lm];
       }
     }
   });
@@ -431,10 +460,13 @@ int gemm_bf16_rowpart_slabs(int N) {
 }
 
 int gemm_bf16_pick_splitk(int M, int N, int K, int batch) {
+  // One workgroup per CU is resident at a time (LDS), so the launch should fill the 256 CUs in as few
+  // full rounds as possible with as few splits as possible (every split costs an fp32 partial tile).
   const int bm = 256, bn = use_big_tile(N) ? 256 : 128;
   const long tiles = (long)((M + bm - 1) / bm) * ((N + bn - 1) / bn) * batch;
-  int s = (int)((2 * 256 + tiles - 1) / tiles);   // aim at >= 2 workgroups per CU
-  const int maxs = (K + 4 * BK - 1) / (4 * BK);   // at least 4 slices per split
+  int s = (int)((256 + tiles - 1) / tiles);
+  if (tiles * s > 256 && tiles * (s - 1) >= 224 && s > 1) s -= 1;   // 7/8 of the CUs busy beats a second round
+  const int maxs = (K + 8 * BK - 1) / (8 * BK);   // at least 8 slices per split
   if (s > maxs) s = maxs;
   if (s > 64) s = 64;
   if (s < 1) s = 1;
@@ -468,13 +500,13 @@ int gemm_timer_end(double* total_ms, int* launches) {
   g_timer.on = false;
   double sum = 0.0;
   const size_t n = g_timer.used / 2;
-  if (n > 0) hipEventSynchronize(g_timer.ev[2 * n - 1]);
+  if (n > 0) (void)hipEventSynchronize(g_timer.ev[2 * n - 1]);
   for (size_t i = 0; i < n; i++) {
     float ms = 0.f;
-    hipEventElapsedTime(&ms, g_timer.ev[2 * i], g_timer.ev[2 * i + 1]);
+    (void)hipEventElapsedTime(&ms, g_timer.ev[2 * i], g_timer.ev[2 * i + 1]);
     sum += ms;
   }
-  for (auto& e : g_timer.ev) hipEventDestroy(e);
+  for (auto& e : g_timer.ev) (void)hipEventDestroy(e);
   g_timer.ev.clear();
   if (total_ms) *total_ms = sum;
   if (launches) *launches = (int)n;
@@ -486,9 +518,9 @@ static hipError_t gemm_bf16_untimed(const GemmOp& op, hipStream_t st);
 hipError_t gemm_bf16(const GemmOp& op, hipStream_t st) {
   if (!g_timer.on || g_timer.used + 2 > g_timer.ev.size() || op.M <= 0 || op.N <= 0 || op.batch <= 0)
     return gemm_bf16_untimed(op, st);
-  hipEventRecord(g_timer.ev[g_timer.used], st);
+  (void)hipEventRecord(g_timer.ev[g_timer.used], st);
   hipError_t e = gemm_bf16_untimed(op, st);
-  hipEventRecord(g_timer.ev[g_timer.used + 1], st);
+  (void)hipEventRecord(g_timer.ev[g_timer.used + 1], st);
   g_timer.used += 2;
   return e;
 }

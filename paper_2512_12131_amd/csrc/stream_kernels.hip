@@ -272,34 +272,36 @@ __global__ __launch_bounds__(256) void scale_cols_kernel(const void* w, const vo
 }
 
 // ---- finish a split-K weight gradient ------------------------------------------------------------
-constexpr int WF_RB = 32;  // rows per workgroup (and per dgamma partial)
+// One thread per 8-column (bf16) / 1-column (fp32) vector of one row: sums the nsplit fp32 partials,
+// scales, accumulates, stores.  When dgamma partials are wanted a workgroup covers WF_RB rows of a
+// 64-vector column strip: its 4 wavefronts take rows r, r+4, ... and add their column sums through LDS.
+constexpr int WF_RB = 32;  // rows per dgamma partial
 
-template <int DT, typename OT>
+template <int DT, typename OT, bool DG>
 __global__ __launch_bounds__(256) void wgrad_finish_kernel(const float* part, int nsplit, int64_t rows, int64_t cols,
                                                            void* dw, const void* colscale, const void* wdg,
                                                            float* dgpart, int accumulate) {
   using S = St<DT>;
   using IO = VecIO<typename S::T, S::NV>;
   using OIO = VecIO<OT, S::NV>;
+  using PIO = VecIO<float, S::NV>;
   constexpr int NV = S::NV;
-  const int64_t c = ((int64_t)blockIdx.x * 256 + threadIdx.x) * NV;
-  if (c >= cols) return;
-  const int64_t rbeg = (int64_t)blockIdx.y * WF_RB, rend = min(rows, rbeg + WF_RB);
+  __shared__ float sred[DG ? 4 * 64 * NV : 1];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t count = rows * cols;
   float cs[NV], dg[NV];
 #pragma unroll
   for (int i = 0; i < NV; i++) { cs[i] = 1.f; dg[i] = 0.f; }
-  if (colscale) IO::load(colscale, c, cs);
-  const int64_t count = rows * cols;
-  for (int64_t r = rbeg; r < rend; r++) {
+  auto one = [&](int64_t r, int64_t c) {
     float s[NV];
+    PIO::load(part, r * cols + c, s);
+    for (int sp = 1; sp < nsplit; sp++) {
+      float t[NV];
+      PIO::load(part, (int64_t)sp * count + r * cols + c, t);
 #pragma unroll
-    for (int i = 0; i < NV; i++) s[i] = 0.f;
-    for (int sp = 0; sp < nsplit; sp++) {
-      const float* p = part + (int64_t)sp * count + r * cols + c;
-#pragma unroll
-      for (int i = 0; i < NV; i++) s[i] += p[i];
+      for (int i = 0; i < NV; i++) s[i] += t[i];
     }
-    if (wdg) {
+    if constexpr (DG) {
       float wv[NV];
       IO::load(wdg, r * cols + c, wv);
 #pragma unroll
@@ -314,10 +316,30 @@ __global__ __launch_bounds__(256) void wgrad_finish_kernel(const float* part, in
       for (int i = 0; i < NV; i++) s[i] += old[i];
     }
     OIO::store(dw, r * cols + c, s);
-  }
-  if (dgpart) {
+  };
+  if constexpr (!DG) {
+    const int64_t vpr = cols / NV;                               // vectors per row
+    const int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (v >= rows * vpr) return;
+    const int64_t r = v / vpr, c = (v % vpr) * NV;
+    if (colscale) IO::load(colscale, c, cs);
+    one(r, c);
+  } else {
+    const int64_t c = ((int64_t)blockIdx.x * 64 + lane) * NV;
+    const bool cok = c < cols;
+    if (cok && colscale) IO::load(colscale, c, cs);
+    const int64_t rbeg = (int64_t)blockIdx.y * WF_RB, rend = min(rows, rbeg + WF_RB);
+    if (cok)
+      for (int64_t r = rbeg + wave; r < rend; r += 4) one(r, c);
 #pragma unroll
-    for (int i = 0; i < NV; i++) dgpart[(int64_t)blockIdx.y * cols + c + i] = dg[i];
+    for (int i = 0; i < NV; i++) sred[(wave * 64 + lane) * NV + i] = dg[i];
+    __syncthreads();
+    if (wave == 0 && cok) {
+#pragma unroll
+      for (int i = 0; i < NV; i++)
+        dgpart[(int64_t)blockIdx.y * cols + c + i] = sred[lane * NV + i] + sred[(64 + lane) * NV + i] +
+                                                     sred[(128 + lane) * NV + i] + sred[(192 + lane) * NV + i];
+    }
   }
 }
 
@@ -423,16 +445,22 @@ hipError_t k_wgrad_finish(const float* part, int nsplit, int64_t rows, int64_t c
                           hipStream_t st) {
   if (rows <= 0 || cols <= 0) return hipSuccess;
   const int nv = dt == LR_BF16 ? 8 : 1;
-  dim3 grid((cols / nv + 255) / 256, (rows + WF_RB - 1) / WF_RB);
-  if (dt == LR_F32)
-    hipLaunchKernelGGL((wgrad_finish_kernel<LR_F32, float>), grid, dim3(256), 0, st, part, nsplit, rows, cols, dw,
-                       colscale, w_for_dgamma, dgamma_part, accumulate);
-  else if (out_dt == LR_F32)
-    hipLaunchKernelGGL((wgrad_finish_kernel<LR_BF16, float>), grid, dim3(256), 0, st, part, nsplit, rows, cols, dw,
-                       colscale, w_for_dgamma, dgamma_part, accumulate);
-  else
-    hipLaunchKernelGGL((wgrad_finish_kernel<LR_BF16, bf16_t>), grid, dim3(256), 0, st, part, nsplit, rows, cols, dw,
-                       colscale, w_for_dgamma, dgamma_part, accumulate);
+  const bool dg = w_for_dgamma != nullptr && dgamma_part != nullptr;
+  dim3 grid = dg ? dim3((unsigned)((cols / nv + 63) / 64), (unsigned)((rows + WF_RB - 1) / WF_RB))
+                 : dim3((unsigned)((rows * (cols / nv) + 255) / 256));
+#define LRB_WF(DT_, OT_)                                                                                         \
+  do {                                                                                                           \
+    if (dg)                                                                                                      \
+      hipLaunchKernelGGL((wgrad_finish_kernel<DT_, OT_, true>), grid, dim3(256), 0, st, part, nsplit, rows, cols, dw, \
+                         colscale, w_for_dgamma, dgamma_part, accumulate);                                      \
+    else                                                                                                         \
+      hipLaunchKernelGGL((wgrad_finish_kernel<DT_, OT_, false>), grid, dim3(256), 0, st, part, nsplit, rows, cols, dw, \
+                         colscale, w_for_dgamma, dgamma_part, accumulate);                                      \
+  } while (0)
+  if (dt == LR_F32) LRB_WF(LR_F32, float);
+  else if (out_dt == LR_F32) LRB_WF(LR_BF16, float);
+  else LRB_WF(LR_BF16, bf16_t);
+#undef LRB_WF
   return hipGetLastError();
 }
 hipError_t k_colsum_parts(const float* part, int64_t nparts, int64_t cols, void* out, int accumulate, int out_dt,
