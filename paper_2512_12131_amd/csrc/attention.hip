@@ -305,6 +305,7 @@ __global__ __launch_bounds__(256) void attn_dot_kernel(const uint16_t* __restric
 // ----------------------------------------------------------------------------------------------
 // backward, dQ: workgroup owns 4 x 32 queries, streams 64-key tiles of K and V
 // ----------------------------------------------------------------------------------------------
+template <int MB>
 __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                                                           const uint16_t* __restrict__ v,
                                                           const uint16_t* __restrict__ dout,
@@ -312,28 +313,37 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const uint16_t* __rest
                                                           uint16_t* __restrict__ dq, int64_t ld, int S, int H,
                                                           float scale) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  constexpr int BQ = 128;
+  constexpr int BQ = 4 * MB * 32;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nqb = (S + BQ - 1) / BQ;
   const int q0 = (nqb - 1 - (int)blockIdx.x) * BQ;
   const int head = blockIdx.y, b = blockIdx.z;
   const int64_t tok0 = (int64_t)b * S;
   const int64_t hoff = head * HD;
-  const int qw0 = q0 + wave * 32;
+  const int qw0 = q0 + wave * MB * 32;
   const float c = scale * LOG2E;
 
-  bf16x8 qf[1][8], dof[1][8];
-  load_row_frags<1>(qf, q + tok0 * ld + hoff, ld, qw0, S, lane);
-  load_row_frags<1>(dof, dout + tok0 * ld + hoff, ld, qw0, S, lane);
-  const int qi = qw0 + (lane & 31);
-  const int64_t sidx = ((int64_t)b * H + head) * S + min(qi, S - 1);
-  const float lse2 = lse[sidx] * LOG2E, Dq = D[sidx];
+  // Q and dO rows of this wavefront stay in registers (B operands); every K / V fragment read from
+  // LDS then feeds MB MFMAs.
+  bf16x8 qf[MB][8], dof[MB][8];
+  load_row_frags<MB>(qf, q + tok0 * ld + hoff, ld, qw0, S, lane);
+  load_row_frags<MB>(dof, dout + tok0 * ld + hoff, ld, qw0, S, lane);
+  float lse2[MB], Dq[MB];
+#pragma unroll
+  for (int mb = 0; mb < MB; mb++) {
+    const int qi = qw0 + mb * 32 + (lane & 31);
+    const int64_t sidx = ((int64_t)b * H + head) * S + min(qi, S - 1);
+    lse2[mb] = lse[sidx] * LOG2E;
+    Dq[mb] = D[sidx];
+  }
 
-  f32x16 acc[4];
+  f32x16 acc[MB][4];
 #pragma unroll
-  for (int hb = 0; hb < 4; hb++)
+  for (int mb = 0; mb < MB; mb++)
 #pragma unroll
-    for (int e = 0; e < 16; e++) acc[hb][e] = 0.f;
+    for (int hb = 0; hb < 4; hb++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) acc[mb][hb][e] = 0.f;
 
   // K is needed both row-wise (S^T) and transposed (dQ^T): keep two LDS copies with the two pitches.
   constexpr int STAGE = KT * PB + KT * PT + KT * PB;     // K (b128), K (transpose read), V (b128)
@@ -362,34 +372,49 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const uint16_t* __rest
 #pragma unroll 1
     for (int nb = 0; nb < 2; nb++) {
       const int kb0 = key0 + nb * 32;
-      if (kb0 > qw0 + 31 || kb0 >= S) continue;
-      f32x16 st, dp;
+      if (kb0 > qw0 + MB * 32 - 1 || kb0 >= S) continue;
+      f32x16 st[MB], dp[MB];
 #pragma unroll
-      for (int e = 0; e < 16; e++) { st[e] = 0.f; dp[e] = 0.f; }
+      for (int mb = 0; mb < MB; mb++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) { st[mb][e] = 0.f; dp[mb][e] = 0.f; }
 #pragma unroll
       for (int ks = 0; ks < 8; ks++) {
         const int off = (nb * 32 + (lane & 31)) * PB + (ks * 2 + (lane >> 5)) * 16;
-        st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_b128(sKb + off), qf[0][ks], st, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_b128(sVb + off), dof[0][ks], dp, 0, 0, 0);
+        const bf16x8 kfr = lds_b128(sKb + off), vfr = lds_b128(sVb + off);
+#pragma unroll
+        for (int mb = 0; mb < MB; mb++) {
+          st[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr, qf[mb][ks], st[mb], 0, 0, 0);
+          dp[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr, dof[mb][ks], dp[mb], 0, 0, 0);
+        }
       }
       // dS^T = P^T * (dP^T - D), masked on the diagonal / tail blocks only
       const bool need_mask = (kb0 + 31 > qw0) || (kb0 + 32 > S);
 #pragma unroll
-      for (int e = 0; e < 16; e++) {
-        float p = fast_exp2(fmaf(st[e], c, -lse2));
-        if (need_mask) {
-          const int key = kb0 + acc_row(e, lane);
-          p = (key > qi || key >= S) ? 0.f : p;
+      for (int mb = 0; mb < MB; mb++) {
+        const int qi = qw0 + mb * 32 + (lane & 31);
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+          float p = fast_exp2(fmaf(st[mb][e], c, -lse2[mb]));
+          if (need_mask) {
+            const int key = kb0 + acc_row(e, lane);
+            p = (key > qi || key >= S) ? 0.f : p;
+          }
+          st[mb][e] = p * (dp[mb][e] - Dq[mb]);
         }
-        st[e] = p * (dp[e] - Dq);
       }
 #pragma unroll
       for (int t = 0; t < 2; t++) {
-        const bf16x8 dsf = pack_acc_half(st, t);
+        bf16x8 dsf[MB];
 #pragma unroll
-        for (int hb = 0; hb < 4; hb++)
-          acc[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr_frag(sKt, nb * 32 + t * 16, hb * 32, lane), dsf,
-                                                            acc[hb], 0, 0, 0);
+        for (int mb = 0; mb < MB; mb++) dsf[mb] = pack_acc_half(st[mb], t);
+#pragma unroll
+        for (int hb = 0; hb < 4; hb++) {
+          const bf16x8 ktf = lds_tr_frag(sKt, nb * 32 + t * 16, hb * 32, lane);
+#pragma unroll
+          for (int mb = 0; mb < MB; mb++)
+            acc[mb][hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf, dsf[mb], acc[mb][hb], 0, 0, 0);
+        }
       }
     }
     if (more) {
@@ -400,13 +425,18 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const uint16_t* __rest
     }
     __syncthreads();
   }
-  if (qi < S) store_acc_T(dq + (tok0 + qi) * ld + hoff, acc, scale, lane);
+#pragma unroll
+  for (int mb = 0; mb < MB; mb++) {
+    const int qi = qw0 + mb * 32 + (lane & 31);
+    if (qi < S) store_acc_T(dq + (tok0 + qi) * ld + hoff, acc[mb], scale, lane);
+  }
 }
 constexpr int DQ_LDS = 2 * (KT * PB + KT * PT + KT * PB);
 
 // ----------------------------------------------------------------------------------------------
 // backward, dK and dV: workgroup owns 4 x 32 keys, streams 64-query tiles of Q and dO
 // ----------------------------------------------------------------------------------------------
+template <int NB>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                                                            const uint16_t* __restrict__ v,
                                                            const uint16_t* __restrict__ dout,
@@ -414,27 +444,30 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const uint16_t* __res
                                                            uint16_t* __restrict__ dk, uint16_t* __restrict__ dv,
                                                            int64_t ld, int S, int H, float scale) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  constexpr int BN = 128;
+  constexpr int BN = 4 * NB * 32;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n0 = blockIdx.x * BN;                          // early key blocks (most queries) first
   const int head = blockIdx.y, b = blockIdx.z;
   const int64_t tok0 = (int64_t)b * S;
   const int64_t hoff = head * HD;
-  const int nw0 = n0 + wave * 32;
+  const int nw0 = n0 + wave * NB * 32;
   const float c = scale * LOG2E;
 
-  bf16x8 kf[1][8], vf[1][8];                               // B operands: rows = this wavefront's keys
-  load_row_frags<1>(kf, k + tok0 * ld + hoff, ld, nw0, S, lane);
-  load_row_frags<1>(vf, v + tok0 * ld + hoff, ld, nw0, S, lane);
-  const int ni = nw0 + (lane & 31);
+  // K and V rows of this wavefront stay in registers (B operands); every Q / dO fragment read from
+  // LDS then feeds NB MFMAs.
+  bf16x8 kf[NB][8], vf[NB][8];
+  load_row_frags<NB>(kf, k + tok0 * ld + hoff, ld, nw0, S, lane);
+  load_row_frags<NB>(vf, v + tok0 * ld + hoff, ld, nw0, S, lane);
 
-  f32x16 akv[2][4];                                        // [0] = dK^T, [1] = dV^T
+  f32x16 akv[2][NB][4];                                    // [0] = dK^T, [1] = dV^T
 #pragma unroll
   for (int w = 0; w < 2; w++)
 #pragma unroll
-    for (int hb = 0; hb < 4; hb++)
+    for (int nb = 0; nb < NB; nb++)
 #pragma unroll
-      for (int e = 0; e < 16; e++) akv[w][hb][e] = 0.f;
+      for (int hb = 0; hb < 4; hb++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) akv[w][nb][hb][e] = 0.f;
 
   // per stage: Q (b128), Q (transpose), dO (b128), dO (transpose), lse*log2e[64], D[64]
   constexpr int STAGE = 2 * (KT * PB + KT * PT) + 2 * KT * 4;
@@ -486,33 +519,48 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const uint16_t* __res
     for (int qb2 = 0; qb2 < 2; qb2++) {
       const int qb0 = qt0 + qb2 * 32;
       if (qb0 + 31 < nw0 || qb0 >= S) continue;
-      f32x16 st, dp;                                       // rows = queries, column = key
+      f32x16 st[NB], dp[NB];                               // rows = queries, column = key
 #pragma unroll
-      for (int e = 0; e < 16; e++) { st[e] = 0.f; dp[e] = 0.f; }
+      for (int nb = 0; nb < NB; nb++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) { st[nb][e] = 0.f; dp[nb][e] = 0.f; }
 #pragma unroll
       for (int ks = 0; ks < 8; ks++) {
         const int off = (qb2 * 32 + (lane & 31)) * PB + (ks * 2 + (lane >> 5)) * 16;
-        st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_b128(qB + off), kf[0][ks], st, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_b128(dB + off), vf[0][ks], dp, 0, 0, 0);
-      }
-      const bool need_mask = (qb0 < nw0 + 31) || (qb0 + 32 > S);
+        const bf16x8 qfr = lds_b128(qB + off), dfr = lds_b128(dB + off);
 #pragma unroll
-      for (int e = 0; e < 16; e++) {
-        const int ql = qb2 * 32 + acc_row(e, lane);
-        float p = fast_exp2(fmaf(st[e], c, -sl[ql]));
-        if (need_mask) p = (ni > qt0 + ql || qt0 + ql >= S) ? 0.f : p;
-        st[e] = p;                                         // P
-        dp[e] = p * (dp[e] - sd[ql]);                      // dS
+        for (int nb = 0; nb < NB; nb++) {
+          st[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qfr, kf[nb][ks], st[nb], 0, 0, 0);
+          dp[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dfr, vf[nb][ks], dp[nb], 0, 0, 0);
+        }
+      }
+      const bool need_mask = (qb0 < nw0 + NB * 32 - 1) || (qb0 + 32 > S);
+#pragma unroll
+      for (int nb = 0; nb < NB; nb++) {
+        const int ni = nw0 + nb * 32 + (lane & 31);
+#pragma unroll
+        for (int e = 0; e < 16; e++) {
+          const int ql = qb2 * 32 + acc_row(e, lane);
+          float p = fast_exp2(fmaf(st[nb][e], c, -sl[ql]));
+          if (need_mask) p = (ni > qt0 + ql || qt0 + ql >= S) ? 0.f : p;
+          st[nb][e] = p;                                   // P
+          dp[nb][e] = p * (dp[nb][e] - sd[ql]);            // dS
+        }
       }
 #pragma unroll
       for (int t = 0; t < 2; t++) {
-        const bf16x8 pf = pack_acc_half(st, t), dsf = pack_acc_half(dp, t);
+        bf16x8 pf[NB], dsf[NB];
+#pragma unroll
+        for (int nb = 0; nb < NB; nb++) { pf[nb] = pack_acc_half(st[nb], t); dsf[nb] = pack_acc_half(dp[nb], t); }
 #pragma unroll
         for (int hb = 0; hb < 4; hb++) {
-          akv[1][hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr_frag(dT, qb2 * 32 + t * 16, hb * 32, lane), pf,
-                                                               akv[1][hb], 0, 0, 0);
-          akv[0][hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr_frag(qT, qb2 * 32 + t * 16, hb * 32, lane), dsf,
-                                                               akv[0][hb], 0, 0, 0);
+          const bf16x8 dtf = lds_tr_frag(dT, qb2 * 32 + t * 16, hb * 32, lane);
+          const bf16x8 qtf = lds_tr_frag(qT, qb2 * 32 + t * 16, hb * 32, lane);
+#pragma unroll
+          for (int nb = 0; nb < NB; nb++) {
+            akv[1][nb][hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dtf, pf[nb], akv[1][nb][hb], 0, 0, 0);
+            akv[0][nb][hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qtf, dsf[nb], akv[0][nb][hb], 0, 0, 0);
+          }
         }
       }
     }
@@ -524,9 +572,13 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const uint16_t* __res
     }
     __syncthreads();
   }
-  if (ni < S) {
-    store_acc_T(dk + (tok0 + ni) * ld + hoff, akv[0], scale, lane);
-    store_acc_T(dv + (tok0 + ni) * ld + hoff, akv[1], 1.f, lane);
+#pragma unroll
+  for (int nb = 0; nb < NB; nb++) {
+    const int ni = nw0 + nb * 32 + (lane & 31);
+    if (ni < S) {
+      store_acc_T(dk + (tok0 + ni) * ld + hoff, akv[0][nb], scale, lane);
+      store_acc_T(dv + (tok0 + ni) * ld + hoff, akv[1][nb], 1.f, lane);
+    }
   }
 }
 constexpr int DKV_LDS = 2 * (2 * (KT * PB + KT * PT) + 2 * KT * 4);
@@ -557,15 +609,18 @@ hipError_t attention_fwd_bf16(const void* q, const void* k, const void* v, void*
 
 size_t attention_bwd_ws_bytes(int B, int S, int H, int hd) { return (size_t)B * H * S * sizeof(float); }
 
+constexpr int DQ_MB = 2;    // 32-query blocks per wavefront in the dQ kernel
+constexpr int DKV_NB = 1;   // 32-key blocks per wavefront in the dK/dV kernel
+
 hipError_t attention_bwd_bf16(const void* q, const void* k, const void* v, const void* o, const void* dout,
                               const float* lse, void* dq, void* dk, void* dv, int64_t ld, int B, int S, int H, int hd,
                               int causal, void* ws, hipStream_t st) {
   if (hd != HD || !causal) return hipErrorNotSupported;
   static bool once = false;
   if (!once) {
-    hipError_t e = set_lds(attn_bwd_dq_kernel, DQ_LDS);
+    hipError_t e = set_lds(attn_bwd_dq_kernel<DQ_MB>, DQ_LDS);
     if (e != hipSuccess) return e;
-    e = set_lds(attn_bwd_dkv_kernel, DKV_LDS);
+    e = set_lds(attn_bwd_dkv_kernel<DKV_NB>, DKV_LDS);
     if (e != hipSuccess) return e;
     once = true;
   }
@@ -574,10 +629,10 @@ hipError_t attention_bwd_bf16(const void* q, const void* k, const void* v, const
   hipLaunchKernelGGL(attn_dot_kernel, dim3((unsigned)((items * 16 + 255) / 256)), dim3(256), 0, st,
                      (const uint16_t*)dout, (const uint16_t*)o, D, ld, S, H, items);
   const float scale = 1.f / sqrtf((float)hd);
-  hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3((S + 127) / 128, H, B), dim3(256), DQ_LDS, st, (const uint16_t*)q,
+  hipLaunchKernelGGL(attn_bwd_dq_kernel<DQ_MB>, dim3((S + DQ_MB * 128 - 1) / (DQ_MB * 128), H, B), dim3(256), DQ_LDS, st, (const uint16_t*)q,
                      (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)dout, lse, D, (uint16_t*)dq, ld, S, H,
                      scale);
-  hipLaunchKernelGGL(attn_bwd_dkv_kernel, dim3((S + 127) / 128, H, B), dim3(256), DKV_LDS, st, (const uint16_t*)q,
+  hipLaunchKernelGGL(attn_bwd_dkv_kernel<DKV_NB>, dim3((S + DKV_NB * 128 - 1) / (DKV_NB * 128), H, B), dim3(256), DKV_LDS, st, (const uint16_t*)q,
                      (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)dout, lse, D, (uint16_t*)dk,
                      (uint16_t*)dv, ld, S, H, scale);
   return hipGetLastError();
