@@ -22,7 +22,8 @@ namespace lrb {
 namespace {
 
 constexpr int BK = 64;          // k elements per LDS stage: 128-byte rows, i.e. whole cache lines per request
-constexpr int NST = 2;          // LDS stages: one being multiplied, one in flight from global memory
+constexpr int NSA = 3;          // LDS slots of the A operand's slices: loads get two slices of lead
+constexpr int NSB = 2;          // LDS slots of the B operand's slices: loads get one slice of lead
 constexpr int NXCD = 8;
 
 template <int BM_, int BN_, int WM_, int WN_>
@@ -37,8 +38,11 @@ struct Tile {
   static constexpr int CS = TN + 8;  // fp32 row stride of the epilogue staging tile
   static constexpr int EPI_BYTES = NW * 32 * CS * 4;
   static constexpr int STAT_BYTES = BM * 4;
-  static constexpr int MAIN_BYTES = NST * STAGE;
-  static constexpr int LDS_BYTES = (MAIN_BYTES > EPI_BYTES ? MAIN_BYTES : EPI_BYTES) + STAT_BYTES;
+  static constexpr int MAIN_BYTES = NSA * A_BYTES + NSB * B_BYTES;
+  // The per-row statistic is written after the main loop, into main-loop space the epilogue staging
+  // does not reach (the 256x256 tile uses all 160 KB of LDS for its slices).
+  static constexpr int STAT_OFF = EPI_BYTES;
+  static constexpr int LDS_BYTES = MAIN_BYTES > EPI_BYTES + STAT_BYTES ? MAIN_BYTES : EPI_BYTES + STAT_BYTES;
   static_assert(BM / 8 % NW == 0 && BN / 8 % NW == 0 && FM >= 1 && FN >= 1 && BM <= NT,
                 "tile / wavefront layout mismatch");
 };
@@ -96,7 +100,7 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
   static_assert(!KM || (KIND == EPI_PARTIAL && !STAT_A && T::BM == 256 && T::BN % 128 == 0),
                 "the k-major form only serves split-K weight gradients");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  float* sStat = reinterpret_cast<float*>(smem + T::LDS_BYTES - T::STAT_BYTES);
+  float* sStat = reinterpret_cast<float*>(smem + T::STAT_OFF);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / T::WN, wn = wave % T::WN;
@@ -163,40 +167,44 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
   // The start depends on the tile row only through tm % 8, so the summation order of a token row (and
   // with it every rounding decision) does not depend on how many 2048-token sequences are batched.
   const int rot = nk > 0 ? (((tm & 7) * 5 + tn * 3 + ks * 7) & 15) * 2 % nk : 0;
-  auto issue_stage = [&](int kt) {
+  // slot addresses: A slices cycle through NSA slots at the bottom of LDS, B slices through NSB above
+  auto a_slot = [&](int kt) -> unsigned char* { return smem + (kt % NSA) * T::A_BYTES; };
+  auto b_slot = [&](int kt) -> unsigned char* { return smem + NSA * T::A_BYTES + (kt % NSB) * T::B_BYTES; };
+  constexpr int WLOADS_B = T::WLOADS - T::WLOADS_A;
+  // issue_ab(kt, IS_A, HALF): HALF = 0 / 1 issues the first / second half of the operand's loads of
+  // slice kt, HALF = 2 all of them
+  auto issue_ab = [&](int kt, auto IS_A, auto HALF) {
+    constexpr bool isA = decltype(IS_A)::value;
+    constexpr int half = decltype(HALF)::value;
     int kte = kt + rot;
     if (kte >= nk) kte -= nk;
-    unsigned char* dst = smem + (kt % NST) * T::STAGE + wave * 1024;
+    unsigned char* dst = (isA ? a_slot(kt) : b_slot(kt)) + wave * 1024;
+    constexpr int F0 = isA ? 0 : T::WLOADS_A, F1 = isA ? T::WLOADS_A : T::WLOADS;   // the operand's loads
+    constexpr int I0 = half == 1 ? (F0 + F1) / 2 : F0, I1 = half == 0 ? (F0 + F1) / 2 : F1;
     if constexpr (!KM) {
       const uint32_t kmask = (kt < nk && (kbeg + kte * BK + lchunk * 8) < kend) ? 0u : OOB;
       const uint32_t ktoff = (uint32_t)kte * (BK * 2);
 #pragma unroll
-      for (int i = 0; i < T::WLOADS; i++) {
-        const int voff = (int)((goff[i] + ktoff) | kmask);
-        if (i < T::WLOADS_A)
-          __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, LRB_LDS_PTR(dst + i * (T::NW * 1024)), 16, voff, 0, 0, 0);
-        else
-          __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, LRB_LDS_PTR(dst + i * (T::NW * 1024)), 16, voff, 0, 0, 0);
-      }
+      for (int i = I0; i < I1; i++)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(isA ? rsA : rsB, LRB_LDS_PTR(dst + (i - F0) * (T::NW * 1024)), 16,
+                                                 (int)((goff[i] + ktoff) | kmask), 0, 0, 0);
     } else {
       // k-rows of load i: kml + i * (NW * rows-per-load); rows at or past the end of k read as zeros
-      constexpr int RPL_A = 64 / (T::BM / 8), RPL_B = 64 / (T::BN / 8);
+      constexpr int RPL = 64 / ((isA ? T::BM : T::BN) / 8);
       const int krem = kt < nk ? (kend - kbeg) - kte * BK : 0;      // valid k-rows left from this slice's start
-      const uint32_t offa = (uint32_t)kte * BK * (uint32_t)op.lda * 2u, offb = (uint32_t)kte * BK * (uint32_t)op.ldb * 2u;
+      const uint32_t off = (uint32_t)kte * BK * (uint32_t)(isA ? op.lda : op.ldb) * 2u;
+      const int kml = isA ? kml_a : kml_b;
 #pragma unroll
-      for (int i = 0; i < T::WLOADS; i++) {
-        if (i < T::WLOADS_A) {
-          const uint32_t km = (kml_a + i * T::NW * RPL_A) < krem ? 0u : OOB;
-          __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, LRB_LDS_PTR(dst + i * (T::NW * 1024)), 16,
-                                                   (int)((goff[i] + offa) | km), 0, 0, 0);
-        } else {
-          const uint32_t km = (kml_b + (i - T::WLOADS_A) * T::NW * RPL_B) < krem ? 0u : OOB;
-          __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, LRB_LDS_PTR(dst + i * (T::NW * 1024)), 16,
-                                                   (int)((goff[i] + offb) | km), 0, 0, 0);
-        }
+      for (int i = I0; i < I1; i++) {
+        const uint32_t km = (kml + (i - F0) * T::NW * RPL) < krem ? 0u : OOB;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(isA ? rsA : rsB, LRB_LDS_PTR(dst + (i - F0) * (T::NW * 1024)), 16,
+                                                 (int)((goff[i] + off) | km), 0, 0, 0);
       }
     }
   };
+  using Half0 = std::integral_constant<int, 0>;
+  using Half1 = std::integral_constant<int, 1>;
+  using Whole = std::integral_constant<int, 2>;
 
   f32x16 acc[T::FM][T::FN];
 #pragma unroll
@@ -211,8 +219,8 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
   bf16x8 af[2][T::FM], bf[2][T::FN];
   auto load_frags = [&](int buf, int kt, int kk) {
     if constexpr (!KM) {
-      const unsigned char* sa = smem + (kt % NST) * T::STAGE + (wm * T::TM + frow) * 128;
-      const unsigned char* sb = smem + (kt % NST) * T::STAGE + T::A_BYTES + (wn * T::TN + frow) * 128;
+      const unsigned char* sa = a_slot(kt) + (wm * T::TM + frow) * 128;
+      const unsigned char* sb = b_slot(kt) + (wn * T::TN + frow) * 128;
       const int coff = ((kk * 2 + fk) ^ fsw) << 4;
 #pragma unroll
       for (int i = 0; i < T::FM; i++) af[buf][i] = *reinterpret_cast<const bf16x8*>(sa + i * 32 * 128 + coff);
@@ -227,8 +235,8 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
       const int krow = kk * 16 + (g >> 1) * 4 + (sl >> 2);
       const int ksw = (krow & 7) << 2;                      // (krow + 8) & 7 is the same
       const int cin = (g & 1) * 16 + (sl & 3) * 4;          // column inside the 32-column block
-      const unsigned char* sa = smem + (kt % NST) * T::STAGE + krow * (T::BM * 2);
-      const unsigned char* sb = smem + (kt % NST) * T::STAGE + T::A_BYTES + krow * (T::BN * 2);
+      const unsigned char* sa = a_slot(kt) + krow * (T::BM * 2);
+      const unsigned char* sb = b_slot(kt) + krow * (T::BN * 2);
       typedef short s16x4 __attribute__((ext_vector_type(4)));
       typedef short s16x8 __attribute__((ext_vector_type(8)));
       auto tr_pair = [&](const unsigned char* base, int pitch, int col, int swz) -> bf16x8 {
@@ -256,7 +264,7 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
   auto stat_row = [&](int kt, int half) {
     if constexpr (STAT_A) {
       if (tid < T::BM) {
-        const unsigned char* sr = smem + (kt % NST) * T::STAGE + tid * 128 + half * 64;
+        const unsigned char* sr = a_slot(kt) + tid * 128 + half * 64;
 #pragma unroll
         for (int c = 0; c < 4; c++) ssq += sumsq8(*reinterpret_cast<const uint4*>(sr + c * 16));
       }
@@ -266,45 +274,65 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
   // ---- main loop ---------------------------------------------------------------------------------
   // Slice kt (64 wide) is multiplied in four k16 steps.  While step s runs, the operands of step s+1
   // are read from LDS.  Before step 3 a barrier establishes that every wavefront's part of slice
-  // kt+1 has landed and that nobody reads stage kt%2 any more (the step-3 operands are in registers),
-  // so the loads of slice kt+2 are issued into it, with a whole slice of MFMA time to arrive.
+  // kt+1 has landed and that nobody reads slice kt's slots any more (the step-3 operands are in
+  // registers).
+  // The global->LDS loads are spread evenly over the four steps, because the CU's address/texture
+  // path accepts about one 1 KB wavefront load per 23 cycles: issued in one burst they block the
+  // issuing wavefronts (and with them their MFMAs) for most of a step.  LDS holds 3 slots for A
+  // slices and 2 for B slices (5 x 32 KB), which allows this order inside iteration kt:
+  //   step 0: second half of B(kt+1)      -> the slot B(kt-1) left at the previous barrier
+  //   step 1, 2: the halves of A(kt+2)    -> the slot A(kt-1) left at the previous barrier
+  //   barrier (needs A(kt+1), B(kt+1); loads retire in order, so A(kt+2) alone may stay in flight)
+  //   step 3: first half of B(kt+2)       -> the slot B(kt) just left
   // The loop body is branch free: slices past the end of k are "loaded" with every lane out of range
-  // (zeros into a stage nobody reads again), so the wait counts are compile-time constants.
+  // (zeros into a slot nobody reads again), so the wait counts are compile-time constants.
   // Instruction interleave: a wavefront issues in order, and an MFMA occupies the matrix pipe for
   // 32 cycles during which the same wavefront may issue other work.  The scheduler is therefore
   // told to thread the LDS reads and global->LDS loads between the MFMAs instead of issuing them
   // in a burst while the matrix pipe idles.
   constexpr int MPR = (T::FM * T::FN) / (T::FM + T::FN);   // MFMAs per LDS operand read
-  issue_stage(0);
-  issue_stage(1);
-  wait_vmcnt<T::WLOADS>();
+  constexpr int HLA = T::WLOADS_A / 2, HLB = WLOADS_B / 2; // loads per half slice of A, of B
+  constexpr std::true_type OPA{};
+  constexpr std::false_type OPB{};
+  issue_ab(0, OPA, Whole{});
+  issue_ab(0, OPB, Whole{});
+  issue_ab(1, OPA, Whole{});
+  issue_ab(1, OPB, Half0{});
+  wait_vmcnt<T::WLOADS_A + HLB>();   // A(0), B(0) landed; A(1) and half of B(1) may fly
   __builtin_amdgcn_s_barrier();
   load_frags(0, 0, 0);
   for (int kt = 0; kt < nk; kt++) {
-#pragma unroll
-    for (int kk = 0; kk < 3; kk++) {
+    static_for<3>([&](auto KK) {
+      constexpr int kk = decltype(KK)::value;
       load_frags((kk + 1) & 1, kt, kk + 1);
-      if (kk < 2) stat_row(kt, kk);
+      if constexpr (kk == 0) issue_ab(kt + 1, OPB, Half1{});
+      if constexpr (kk == 1) issue_ab(kt + 2, OPA, Half0{});
+      if constexpr (kk == 2) issue_ab(kt + 2, OPA, Half1{});
+      if constexpr (kk < 2) stat_row(kt, kk);
       mfma_step(kk & 1);
+      constexpr int NL = kk == 0 ? HLB : HLA;
 #pragma unroll
       for (int i = 0; i < T::FM + T::FN; i++) {
         __builtin_amdgcn_sched_group_barrier(0x008, MPR, 0);   // MFMA
         __builtin_amdgcn_sched_group_barrier(0x100, KM ? 2 : 1, 0);     // DS read
+        if (i * NL / (T::FM + T::FN) != (i + 1) * NL / (T::FM + T::FN))
+          __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // VMEM read (global -> LDS)
       }
       __builtin_amdgcn_sched_barrier(0);
-    }
-    wait_vmcnt<0>();                       // this wavefront's part of slice kt+1 has landed
-    wait_lgkmcnt0();                       // and its reads of stage kt%2 are complete
+    });
+    wait_vmcnt<T::WLOADS_A>();             // A(kt+1), B(kt+1) of this wavefront landed; A(kt+2) may fly
+    wait_lgkmcnt0();                       // and its reads of slice kt's slots are complete
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    issue_stage(kt + 2);
+    issue_ab(kt + 2, OPB, Half0{});
     load_frags(0, kt + 1, 0);
     mfma_step(1);
 #pragma unroll
-    for (int i = 0; i < T::FM * T::FN; i++) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);     // MFMA
-      if (i < T::WLOADS) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // VMEM read (global -> LDS)
-      if (i % MPR == MPR - 1) __builtin_amdgcn_sched_group_barrier(0x100, KM ? 2 : 1, 0);     // DS read
+    for (int i = 0; i < T::FM + T::FN; i++) {
+      __builtin_amdgcn_sched_group_barrier(0x008, MPR, 0);   // MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, KM ? 2 : 1, 0);     // DS read
+      if (i * HLB / (T::FM + T::FN) != (i + 1) * HLB / (T::FM + T::FN))
+        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // VMEM read (global -> LDS)
     }
     __builtin_amdgcn_sched_barrier(0);
   }
@@ -431,7 +459,7 @@ hipError_t launch(const GemmOp& op, hipStream_t st) {
   return hipGetLastError();
 }
 
-using TileBig = Tile<256, 256, 2, 2>;   // 4 waves, 128x128 per wave
+using TileBig = Tile<256, 256, 2, 4>;   // 8 waves, 128x64 per wave
 using TileMid = Tile<256, 128, 2, 2>;   // 4 waves, 128x64 per wave (narrow N, weight gradients)
 
 template <class T>
