@@ -119,7 +119,74 @@ __device__ __forceinline__ void store_acc_T(uint16_t* out_row, const f32x16 (&ac
     }
 }
 
-constexpr int FWD_LDS = 2 * (KT * PB + KT * PT);
+// ----------------------------------------------------------------------------------------------
+// 64-row x 128-column bf16 tiles moved global -> LDS without passing through registers.
+// One buffer_load_dwordx4 ... lds per wavefront writes 1 KB = 4 tile rows of 256 bytes; lane L's 16
+// bytes land at base + 16 L, i.e. row L/16, physical chunk L%16.  Rows are not padded; instead the
+// 16-byte chunks of a row are XOR-swizzled and each lane fetches the logical chunk that belongs in its
+// slot.  Two swizzles, one per read pattern:
+//   SWZ_ROW16  chunk ^ (row % 16)        16 consecutive rows x one logical chunk (ds_read_b128 of
+//                                        MFMA operand rows) cover all 64 banks
+//   SWZ_ROW4   chunk ^ ((row % 4) * 4)   4 consecutive rows x 64 bytes (the LDS transpose read)
+//                                        cover all 64 banks
+// Rows at or past `nrows` are fetched with an out-of-range offset: the load returns zeros.
+// ----------------------------------------------------------------------------------------------
+constexpr int TILE_BYTES = KT * HD * 2;
+constexpr uint32_t DMA_OOB = 0x80000000u;
+enum { SWZ_ROW16 = 0, SWZ_ROW4 = 1 };
+#define LRB_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rsrc(const uint16_t* base) {
+  return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, 0x7fffffff, 0x00020000);
+}
+
+// Per-lane byte offsets (row * ld + logical chunk) of the 4 wavefront loads that a wavefront of a
+// 4-wavefront workgroup contributes to one tile.
+template <int SWZ>
+__device__ __forceinline__ void dma_lane_offsets(uint32_t (&off)[4], int (&row)[4], int64_t ld, int wave, int lane) {
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    const int r = (i * 4 + wave) * 4 + (lane >> 4);
+    const int pc = lane & 15;
+    const int lc = SWZ == SWZ_ROW16 ? (pc ^ (r & 15)) : (pc ^ ((r & 3) << 2));
+    row[i] = r;
+    off[i] = (uint32_t)(r * (int)ld + lc * 8) * 2u;
+  }
+}
+__device__ __forceinline__ void dma_tile(__amdgpu_buffer_rsrc_t rs, unsigned char* tile, const uint32_t (&off)[4],
+                                         const int (&row)[4], int row0, int nrows, int64_t ld, int wave) {
+  const uint32_t base = (uint32_t)row0 * (uint32_t)ld * 2u;
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    const uint32_t o = (row0 + row[i]) < nrows ? base + off[i] : DMA_OOB;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, LRB_LDS_PTR(tile + (i * 4 + wave) * 1024), 16, (int)o, 0, 0, 0);
+  }
+}
+// s_waitcnt vmcnt(0) alone (gfx9 encoding), and lgkmcnt(0) alone
+__device__ __forceinline__ void wait_vm0() { __builtin_amdgcn_s_waitcnt(0x0f70); }
+
+// A operand (32 rows = tile rows r0 + lane%32, k slots = logical chunk ks*2 + lane/32) from a
+// SWZ_ROW16 tile.  r0 is a multiple of 16, so the swizzle term depends on the lane only.
+__device__ __forceinline__ bf16x8 swz_row_frag(const unsigned char* tile, int r0, int ks, int lane) {
+  const int row = r0 + (lane & 31);
+  return lds_b128(tile + row * 256 + (((ks * 2 + (lane >> 5)) ^ (lane & 15)) << 4));
+}
+// Transposed A operand from a SWZ_ROW4 tile stored [k][col]: rows = columns c0..c0+31 (c0 a multiple
+// of 32), k slots = tile rows k0 + (e/4)*8 + half*4 + e%4 (k0 a multiple of 16); see lds_tr_frag.
+__device__ __forceinline__ bf16x8 swz_tr_frag(const unsigned char* tile, int k0, int c0, int lane) {
+  const int g = lane >> 4, s = lane & 15;
+  const int rl = (g >> 1) * 4 + (s >> 2);                       // row inside the 16-row group; rl % 4 = s / 4
+  const int chunk = (c0 >> 3) + (g & 1) * 2 + ((s & 3) >> 1);   // logical 16-byte chunk
+  const unsigned char* p0 = tile + (k0 + rl) * 256 + ((chunk ^ ((s >> 2) << 2)) << 4) + (s & 1) * 8;
+  const unsigned char* p1 = p0 + 8 * 256;
+  s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0));
+  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p1));
+  typedef short s16x8 __attribute__((ext_vector_type(8)));
+  s16x8 r = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  return __builtin_bit_cast(bf16x8, r);
+}
+
+constexpr int FWD_LDS = 4 * TILE_BYTES;   // K and V, double buffered
 
 // ----------------------------------------------------------------------------------------------
 // forward
@@ -128,148 +195,163 @@ template <int MB>
 __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                                                        const uint16_t* __restrict__ v, uint16_t* __restrict__ o,
                                                        float* __restrict__ lse, int64_t ld, int S, int H, float scale) {
+  static_assert(MB == 1, "one 32-query block per wavefront");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int BQ = 4 * MB * 32;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nqb = (S + BQ - 1) / BQ;
-  const int q0 = (nqb - 1 - (int)blockIdx.x) * BQ;       // heaviest (latest) query blocks first
   const int head = blockIdx.y, b = blockIdx.z;
   const int64_t tok0 = (int64_t)b * S;
   const uint16_t* qb = q + tok0 * ld + head * HD;
-  const uint16_t* kb = k + tok0 * ld + head * HD;
-  const uint16_t* vb = v + tok0 * ld + head * HD;
-  const int qw0 = q0 + wave * MB * 32;                   // first query of this wavefront
+  const __amdgpu_buffer_rsrc_t rsK = tile_rsrc(k + tok0 * ld + head * HD);
+  const __amdgpu_buffer_rsrc_t rsV = tile_rsrc(v + tok0 * ld + head * HD);
   const float c = scale * LOG2E;
+  uint32_t offK[4], offV[4];
+  int rowK[4], rowV[4];
+  dma_lane_offsets<SWZ_ROW16>(offK, rowK, ld, wave, lane);
+  dma_lane_offsets<SWZ_ROW4>(offV, rowV, ld, wave, lane);
+  unsigned char* sK = smem;                              // 2 tiles
+  unsigned char* sV = smem + 2 * TILE_BYTES;             // 2 tiles
+
+  // Causal work grows linearly with the query block index.  Every workgroup takes one block from the
+  // late end and its mirror image from the early end, so that all workgroups of the launch do the
+  // same amount of work (the hardware deals workgroups to the XCDs in strict rotation: unequal
+  // workgroups leave most of the chip waiting for the XCD that drew the heavy ones).
+  for (int pass = 0; pass < 2; pass++) {
+  const int qblk = pass == 0 ? nqb - 1 - (int)blockIdx.x : (int)blockIdx.x;
+  if (pass == 1 && qblk >= nqb - 1 - (int)blockIdx.x) break;   // odd block count: the middle block has no mirror
+  const int q0 = qblk * BQ;
+  const int qw0 = q0 + wave * MB * 32;                   // first query of this wavefront
 
   bf16x8 qf[MB][8];
   load_row_frags<MB>(qf, qb, ld, qw0, S, lane);
 
-  f32x16 oacc[MB][4];
-  float mrun[MB], lrun[MB];
+  f32x16 oacc[4];
+  float mrun = -INFINITY, lrun = 0.f;
 #pragma unroll
-  for (int mb = 0; mb < MB; mb++) {
-    mrun[mb] = -INFINITY;
-    lrun[mb] = 0.f;
+  for (int hb = 0; hb < 4; hb++)
 #pragma unroll
-    for (int hb = 0; hb < 4; hb++)
-#pragma unroll
-      for (int e = 0; e < 16; e++) oacc[mb][hb][e] = 0.f;
-  }
+    for (int e = 0; e < 16; e++) oacc[hb][e] = 0.f;
 
   const int kv_end = min(S, q0 + BQ);                    // causal: keys up to the block's last query
   const int ntiles = (kv_end + KT - 1) / KT;
-  constexpr int STAGE = KT * PB + KT * PT;               // K tile (b128 reads), V tile (transpose reads)
 
-  TileRegs tk = load_tile(kb, ld, 0, S, tid), tv = load_tile(vb, ld, 0, S, tid);
-  store_tile(smem, PB, tk, tid);
-  store_tile(smem + KT * PB, PT, tv, tid);
+  dma_tile(rsK, sK, offK, rowK, 0, S, ld, wave);
+  dma_tile(rsV, sV, offV, rowV, 0, S, ld, wave);
+  wait_vm0();
   __syncthreads();
 
   for (int j = 0; j < ntiles; j++) {
     const int cur = j & 1;
-    const bool more = j + 1 < ntiles;
-    if (more) {
-      tk = load_tile(kb, ld, (j + 1) * KT, S, tid);
-      tv = load_tile(vb, ld, (j + 1) * KT, S, tid);
+    if (j + 1 < ntiles) {                                // next tiles land while this one is worked on
+      dma_tile(rsK, sK + (cur ^ 1) * TILE_BYTES, offK, rowK, (j + 1) * KT, S, ld, wave);
+      dma_tile(rsV, sV + (cur ^ 1) * TILE_BYTES, offV, rowV, (j + 1) * KT, S, ld, wave);
     }
     const int key0 = j * KT;
-    const unsigned char* sKc = smem + cur * STAGE;
-    const unsigned char* sVc = sKc + KT * PB;
+    const unsigned char* sKc = sK + cur * TILE_BYTES;
+    const unsigned char* sVc = sV + cur * TILE_BYTES;
     if (key0 <= qw0 + MB * 32 - 1) {                     // this wavefront still has unmasked keys here
-      // ---- S^T[n][m] for 64 keys x MB*32 queries ----
-      f32x16 st[2][MB];
-#pragma unroll
-      for (int nb = 0; nb < 2; nb++)
-#pragma unroll
-        for (int mb = 0; mb < MB; mb++)
-#pragma unroll
-          for (int e = 0; e < 16; e++) st[nb][mb][e] = 0.f;
+      // ---- S^T[n][m] for 64 keys x 32 queries: all 16 operand reads are issued up front, so the LDS
+      //      latency is paid once per tile and not once per MFMA pair ----
+      bf16x8 kf[8][2];
 #pragma unroll
       for (int ks = 0; ks < 8; ks++)
 #pragma unroll
-        for (int nb = 0; nb < 2; nb++) {
-          const bf16x8 kf = lds_b128(sKc + (nb * 32 + (lane & 31)) * PB + (ks * 2 + (lane >> 5)) * 16);
+        for (int nb = 0; nb < 2; nb++) kf[ks][nb] = swz_row_frag(sKc, nb * 32, ks, lane);
+      __builtin_amdgcn_sched_barrier(0);
+      f32x16 st[2];
 #pragma unroll
-          for (int mb = 0; mb < MB; mb++)
-            st[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[mb][ks], st[nb][mb], 0, 0, 0);
-        }
-      const bool need_mask = (key0 + KT - 1 > qw0) || (key0 + KT > S);   // wavefront-uniform: diagonal / tail tile
-      if (need_mask) {
+      for (int nb = 0; nb < 2; nb++)
 #pragma unroll
-        for (int mb = 0; mb < MB; mb++) {
-          const int qi = qw0 + mb * 32 + (lane & 31);
+        for (int e = 0; e < 16; e++) st[nb][e] = 0.f;
 #pragma unroll
-          for (int nb = 0; nb < 2; nb++)
-#pragma unroll
-            for (int e = 0; e < 16; e++) {
-              const int key = key0 + nb * 32 + acc_row(e, lane);
-              st[nb][mb][e] = (key > qi || key >= S) ? -INFINITY : st[nb][mb][e];
-            }
-        }
-      }
-#pragma unroll
-      for (int mb = 0; mb < MB; mb++) {
-        float mx = -INFINITY;
+      for (int ks = 0; ks < 8; ks++)
 #pragma unroll
         for (int nb = 0; nb < 2; nb++)
+          st[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks][nb], qf[0][ks], st[nb], 0, 0, 0);
+      // first half of the V^T operands: in flight during the softmax
+      bf16x8 vf[2][4];
 #pragma unroll
-          for (int e = 0; e < 16; e++) mx = fmaxf(mx, st[nb][mb][e]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float mnew = fmaxf(mrun[mb], mx);          // finite: key 0 is visible to every query
-        const float alpha = fast_exp2((mrun[mb] - mnew) * c);
-        mrun[mb] = mnew;
-        const float mc = mnew * c;
-        float rs = 0.f;
+      for (int t = 0; t < 2; t++)
+#pragma unroll
+        for (int hb = 0; hb < 4; hb++) vf[t][hb] = swz_tr_frag(sVc, t * 16, hb * 32, lane);
+      __builtin_amdgcn_sched_barrier(0);
+      if ((key0 + KT - 1 > qw0) || (key0 + KT > S)) {    // wavefront-uniform: diagonal / tail tile
+        asm volatile("" ::: "memory");                   // a real branch: the selects are not to be speculated
+        const int qi = qw0 + (lane & 31);
 #pragma unroll
         for (int nb = 0; nb < 2; nb++)
 #pragma unroll
           for (int e = 0; e < 16; e++) {
-            const float p = fast_exp2(fmaf(st[nb][mb][e], c, -mc));
-            st[nb][mb][e] = p;
-            rs += p;
+            const int key = key0 + nb * 32 + acc_row(e, lane);
+            st[nb][e] = (key > qi || key >= S) ? -INFINITY : st[nb][e];
           }
-        lrun[mb] = lrun[mb] * alpha + rs;
-        // the running maximum settles after the first tiles: skip the rescale when no lane needs it
-        if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {
-#pragma unroll
-          for (int hb = 0; hb < 4; hb++)
-#pragma unroll
-            for (int e = 0; e < 16; e++) oacc[mb][hb][e] *= alpha;
-        }
       }
-      // ---- O^T += V^T P^T ----
+      float mx = -INFINITY;
 #pragma unroll
       for (int nb = 0; nb < 2; nb++)
 #pragma unroll
-        for (int t = 0; t < 2; t++) {
-          bf16x8 pf[MB];
+        for (int e = 0; e < 16; e++) mx = fmaxf(mx, st[nb][e]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float mnew = fmaxf(mrun, mx);                // finite: key 0 is visible to every query
+      const float alpha = fast_exp2((mrun - mnew) * c);
+      mrun = mnew;
+      const float mc = mnew * c;
+      float rs = 0.f;
 #pragma unroll
-          for (int mb = 0; mb < MB; mb++) pf[mb] = pack_acc_half(st[nb][mb], t);
+      for (int nb = 0; nb < 2; nb++)
 #pragma unroll
-          for (int hb = 0; hb < 4; hb++) {
-            const bf16x8 vf = lds_tr_frag(sVc, nb * 32 + t * 16, hb * 32, lane);
-#pragma unroll
-            for (int mb = 0; mb < MB; mb++)
-              oacc[mb][hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[mb], oacc[mb][hb], 0, 0, 0);
-          }
+        for (int e = 0; e < 16; e++) {
+          const float p = fast_exp2(fmaf(st[nb][e], c, -mc));
+          st[nb][e] = p;
+          rs += p;
         }
+      lrun = lrun * alpha + rs;
+      // the running maximum settles after the first tiles: skip the rescale when no lane needs it
+      if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) {
+#pragma unroll
+        for (int hb = 0; hb < 4; hb++)
+#pragma unroll
+          for (int e = 0; e < 16; e++) oacc[hb][e] *= alpha;
+      }
+      // ---- O^T += V^T P^T ----
+#pragma unroll
+      for (int nb = 0; nb < 2; nb++) {
+        bf16x8 vn[2][4];
+        if (nb == 0) {                                   // second half of the operands, during the first half's MFMAs
+#pragma unroll
+          for (int t = 0; t < 2; t++)
+#pragma unroll
+            for (int hb = 0; hb < 4; hb++) vn[t][hb] = swz_tr_frag(sVc, 32 + t * 16, hb * 32, lane);
+        }
+#pragma unroll
+        for (int t = 0; t < 2; t++) {
+          const bf16x8 pf = pack_acc_half(st[nb], t);
+#pragma unroll
+          for (int hb = 0; hb < 4; hb++)
+            oacc[hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t][hb], pf, oacc[hb], 0, 0, 0);
+        }
+        if (nb == 0) {
+#pragma unroll
+          for (int t = 0; t < 2; t++)
+#pragma unroll
+            for (int hb = 0; hb < 4; hb++) vf[t][hb] = vn[t][hb];
+        }
+      }
     }
-    if (more) {
-      store_tile(smem + (cur ^ 1) * STAGE, PB, tk, tid);
-      store_tile(smem + (cur ^ 1) * STAGE + KT * PB, PT, tv, tid);
-    }
+    wait_vm0();
     __syncthreads();
   }
 
-#pragma unroll
-  for (int mb = 0; mb < MB; mb++) {
-    const int qi = qw0 + mb * 32 + (lane & 31);
-    const float l = lrun[mb] + __shfl_xor(lrun[mb], 32);
+  {
+    const int qi = qw0 + (lane & 31);
+    const float l = lrun + __shfl_xor(lrun, 32);
     if (qi < S) {
-      store_acc_T(o + (tok0 + qi) * ld + head * HD, oacc[mb], 1.f / l, lane);
-      if (lane < 32) lse[((int64_t)b * H + head) * S + qi] = mrun[mb] * scale + logf(l);
+      store_acc_T(o + (tok0 + qi) * ld + head * HD, oacc, 1.f / l, lane);
+      if (lane < 32) lse[((int64_t)b * H + head) * S + qi] = mrun * scale + logf(l);
     }
   }
+  }  // pass
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -316,12 +398,16 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const uint16_t* __rest
   constexpr int BQ = 4 * MB * 32;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nqb = (S + BQ - 1) / BQ;
-  const int q0 = (nqb - 1 - (int)blockIdx.x) * BQ;
   const int head = blockIdx.y, b = blockIdx.z;
   const int64_t tok0 = (int64_t)b * S;
   const int64_t hoff = head * HD;
-  const int qw0 = q0 + wave * MB * 32;
   const float c = scale * LOG2E;
+  // one query block from the late end and its mirror image from the early end: equal work per workgroup
+  for (int pass = 0; pass < 2; pass++) {
+  const int qblk = pass == 0 ? nqb - 1 - (int)blockIdx.x : (int)blockIdx.x;
+  if (pass == 1 && qblk >= nqb - 1 - (int)blockIdx.x) break;
+  const int q0 = qblk * BQ;
+  const int qw0 = q0 + wave * MB * 32;
 
   // Q and dO rows of this wavefront stay in registers (B operands); every K / V fragment read from
   // LDS then feeds MB MFMAs.
@@ -430,6 +516,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const uint16_t* __rest
     const int qi = qw0 + mb * 32 + (lane & 31);
     if (qi < S) store_acc_T(dq + (tok0 + qi) * ld + hoff, acc[mb], scale, lane);
   }
+  }  // pass
 }
 constexpr int DQ_LDS = 2 * (KT * PB + KT * PT + KT * PB);
 
@@ -446,12 +533,18 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const uint16_t* __res
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int BN = 4 * NB * 32;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int n0 = blockIdx.x * BN;                          // early key blocks (most queries) first
+  const int nkb = (S + BN - 1) / BN;
   const int head = blockIdx.y, b = blockIdx.z;
   const int64_t tok0 = (int64_t)b * S;
   const int64_t hoff = head * HD;
-  const int nw0 = n0 + wave * NB * 32;
   const float c = scale * LOG2E;
+  // one key block from the early end (most queries) and its mirror image from the late end: equal
+  // work per workgroup
+  for (int pass = 0; pass < 2; pass++) {
+  const int kblk = pass == 0 ? (int)blockIdx.x : nkb - 1 - (int)blockIdx.x;
+  if (pass == 1 && kblk <= (int)blockIdx.x) break;
+  const int n0 = kblk * BN;
+  const int nw0 = n0 + wave * NB * 32;
 
   // K and V rows of this wavefront stay in registers (B operands); every Q / dO fragment read from
   // LDS then feeds NB MFMAs.
@@ -580,6 +673,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const uint16_t* __res
       store_acc_T(dv + (tok0 + ni) * ld + hoff, akv[1][nb], 1.f, lane);
     }
   }
+  }  // pass
 }
 constexpr int DKV_LDS = 2 * (2 * (KT * PB + KT * PT) + 2 * KT * 4);
 
@@ -601,7 +695,8 @@ hipError_t attention_fwd_bf16(const void* q, const void* k, const void* v, void*
     if (e != hipSuccess) return e;
     once = true;
   }
-  dim3 grid((S + BQ - 1) / BQ, H, B);
+  const int nqb = (S + BQ - 1) / BQ;
+  dim3 grid((nqb + 1) / 2, H, B);                        // each workgroup: one query block and its mirror
   hipLaunchKernelGGL(attn_fwd_kernel<MB>, grid, dim3(256), FWD_LDS, st, (const uint16_t*)q, (const uint16_t*)k,
                      (const uint16_t*)v, (uint16_t*)o, lse, ld, S, H, 1.f / sqrtf((float)hd));
   return hipGetLastError();
@@ -629,10 +724,10 @@ hipError_t attention_bwd_bf16(const void* q, const void* k, const void* v, const
   hipLaunchKernelGGL(attn_dot_kernel, dim3((unsigned)((items * 16 + 255) / 256)), dim3(256), 0, st,
                      (const uint16_t*)dout, (const uint16_t*)o, D, ld, S, H, items);
   const float scale = 1.f / sqrtf((float)hd);
-  hipLaunchKernelGGL(attn_bwd_dq_kernel<DQ_MB>, dim3((S + DQ_MB * 128 - 1) / (DQ_MB * 128), H, B), dim3(256), DQ_LDS, st, (const uint16_t*)q,
+  hipLaunchKernelGGL(attn_bwd_dq_kernel<DQ_MB>, dim3(((S + DQ_MB * 128 - 1) / (DQ_MB * 128) + 1) / 2, H, B), dim3(256), DQ_LDS, st, (const uint16_t*)q,
                      (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)dout, lse, D, (uint16_t*)dq, ld, S, H,
                      scale);
-  hipLaunchKernelGGL(attn_bwd_dkv_kernel<DKV_NB>, dim3((S + DKV_NB * 128 - 1) / (DKV_NB * 128), H, B), dim3(256), DKV_LDS, st, (const uint16_t*)q,
+  hipLaunchKernelGGL(attn_bwd_dkv_kernel<DKV_NB>, dim3(((S + DKV_NB * 128 - 1) / (DKV_NB * 128) + 1) / 2, H, B), dim3(256), DKV_LDS, st, (const uint16_t*)q,
                      (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)dout, lse, D, (uint16_t*)dk,
                      (uint16_t*)dv, ld, S, H, scale);
   return hipGetLastError();
