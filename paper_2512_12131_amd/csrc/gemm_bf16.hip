@@ -118,7 +118,7 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
   // ---- global -> LDS, without passing through registers ---------------------------------------
   // One buffer_load_dwordx4 ... lds per wavefront moves 8 tile rows x 128 bytes (1 KB, eight whole
   // cache lines): lane L's 16 bytes land at LDS base + 16 L, i.e. tile row L/8, physical chunk L%8.
-  // The 16-byte chunks of a row are stored XOR-swizzled by row%8, so each lane fetches the logical
+  // The 16-byte chunks of a row are stored XOR-swizzled by (row/2)%8, so each lane fetches the logical
   // chunk that belongs in its slot; MFMA operand reads (32 rows x one logical chunk) then spread over
   // all banks.  A lane whose chunk lies outside the matrix (row tail, k tail) uses an offset past the
   // resource size: the load returns zeros and zeros are what reaches LDS.
@@ -130,8 +130,14 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
   // k-contiguous form: 8 rows x 128 B per wavefront load; k-major form: 2 k-rows x 512 B (BM = 256
   // columns) or 4 k-rows x 256 B (128 columns).  In both, the 16-byte chunk index inside a row is
   // XOR-swizzled so that the operand reads spread over the banks.
+  // Swizzle of the k-contiguous form: physical chunk = logical chunk ^ ((row / 2) % 8).  An LDS row is
+  // 128 bytes, half of the 64 x 4-byte banks, so rows 2i and 2i+1 lie side by side in one bank line;
+  // with this term the 16 rows that one cycle of a 16-byte-per-lane read touches (16 lanes) fall on
+  // 16 different 16-byte bank groups.  The 1 KB group index g = wave + NW * i keeps its parity over i
+  // (NW is even), so one swizzle value per lane serves all of its loads.
+  static_assert(T::NW % 2 == 0 && (T::BM / 8) % 2 == 0, "row parity of a lane must not depend on the load index");
   const int lrow = KM ? 0 : lane >> 3;
-  const int lchunk = KM ? 0 : (lane & 7) ^ lrow;
+  const int lchunk = KM ? 0 : (lane & 7) ^ (((wave & 1) << 2) | (lrow >> 1));
   uint32_t goff[T::WLOADS];
   int kml_a = 0, kml_b = 0;          // KM: k-row (inside the slice, modulo the per-load stride) of this lane
 #pragma unroll
@@ -215,7 +221,7 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
       for (int v = 0; v < 16; v++) acc[i][j][v] = 0.f;
 
   // MFMA operand addressing: row = lane%32 of a 32-row block, logical chunk kk*2 + lane/32
-  const int frow = lane & 31, fk = lane >> 5, fsw = frow & 7;
+  const int frow = lane & 31, fk = lane >> 5, fsw = (frow >> 1) & 7;
   bf16x8 af[2][T::FM], bf[2][T::FN];
   auto load_frags = [&](int buf, int kt, int kk) {
     if constexpr (!KM) {
