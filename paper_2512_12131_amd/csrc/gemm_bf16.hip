@@ -494,17 +494,22 @@ int gemm_bf16_rowpart_slabs(int N) {
 }
 
 int gemm_bf16_pick_splitk(int M, int N, int K, int batch) {
-  // One workgroup per CU is resident at a time (LDS), so the launch should fill the 256 CUs in as few
-  // full rounds as possible with as few splits as possible (every split costs an fp32 partial tile).
+  // One workgroup per CU is resident at a time (LDS), so a launch runs in ceil(workgroups / 256)
+  // rounds, each as long as one workgroup: its k-slices plus a fixed cost (pipeline fill, the fp32
+  // partial tile it writes, its share of the fold) worth about 8 slices.  Pick the split count with
+  // the smallest estimate; ties go to fewer splits (less partial traffic).
   const int bm = 256, bn = use_big_tile(N) ? 256 : 128;
   const long tiles = (long)((M + bm - 1) / bm) * ((N + bn - 1) / bn) * batch;
-  int s = (int)((256 + tiles - 1) / tiles);
-  if (tiles * s > 256 && tiles * (s - 1) >= 224 && s > 1) s -= 1;   // 7/8 of the CUs busy beats a second round
-  const int maxs = (K + 8 * BK - 1) / (8 * BK);   // at least 8 slices per split
-  if (s > maxs) s = maxs;
-  if (s > 64) s = 64;
-  if (s < 1) s = 1;
-  return s;
+  const int nk = (K + BK - 1) / BK;
+  const int maxs = nk >= 16 ? (nk / 8 < 64 ? nk / 8 : 64) : 1;   // at least 8 slices per split
+  int best = 1;
+  long best_cost = -1;
+  for (int s = 1; s <= maxs; s++) {
+    const long rounds = (tiles * s + 255) / 256;
+    const long cost = rounds * ((nk + s - 1) / s + 8) * 16 + s;   // "+ s": the tie-break
+    if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = s; }
+  }
+  return best;
 }
 
 // ---- optional timing of the GEMM launches (for the benchmark's roofline figure) -----------------
