@@ -133,33 +133,41 @@ __device__ __forceinline__ void store_acc_T(uint16_t* out_row, const f32x16 (&ac
 // ----------------------------------------------------------------------------------------------
 constexpr int TILE_BYTES = KT * HD * 2;
 constexpr uint32_t DMA_OOB = 0x80000000u;
-enum { SWZ_ROW16 = 0, SWZ_ROW4 = 1 };
+enum { SWZ_ROW16 = 0, SWZ_ROW4 = 1, SWZ_BOTH = 2 };
+//   SWZ_BOTH   chunk ^ ((row % 4) * 4 + (row / 4) % 4)   serves both read patterns of a tile that is
+//                                        needed row-wise and transposed: 16 consecutive rows see 16
+//                                        different terms, 4 consecutive rows 4 different 64-byte groups
 #define LRB_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rsrc(const uint16_t* base) {
   return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, 0x7fffffff, 0x00020000);
 }
 
-// Per-lane byte offsets (row * ld + logical chunk) of the 4 wavefront loads that a wavefront of a
-// 4-wavefront workgroup contributes to one tile.
-template <int SWZ>
-__device__ __forceinline__ void dma_lane_offsets(uint32_t (&off)[4], int (&row)[4], int64_t ld, int wave, int lane) {
+// Per-lane byte offsets (row * ld + logical chunk) of the 16 / NW wavefront loads that a wavefront of
+// an NW-wavefront workgroup contributes to one tile.
+template <int SWZ, int NL>
+__device__ __forceinline__ void dma_lane_offsets(uint32_t (&off)[NL], int (&row)[NL], int64_t ld, int wave, int lane) {
+  constexpr int NW = 16 / NL;
 #pragma unroll
-  for (int i = 0; i < 4; i++) {
-    const int r = (i * 4 + wave) * 4 + (lane >> 4);
+  for (int i = 0; i < NL; i++) {
+    const int r = (i * NW + wave) * 4 + (lane >> 4);
     const int pc = lane & 15;
-    const int lc = SWZ == SWZ_ROW16 ? (pc ^ (r & 15)) : (pc ^ ((r & 3) << 2));
+    const int lc = SWZ == SWZ_ROW16 ? (pc ^ (r & 15))
+                 : SWZ == SWZ_ROW4 ? (pc ^ ((r & 3) << 2))
+                                   : (pc ^ (((r & 3) << 2) | ((r >> 2) & 3)));
     row[i] = r;
     off[i] = (uint32_t)(r * (int)ld + lc * 8) * 2u;
   }
 }
-__device__ __forceinline__ void dma_tile(__amdgpu_buffer_rsrc_t rs, unsigned char* tile, const uint32_t (&off)[4],
-                                         const int (&row)[4], int row0, int nrows, int64_t ld, int wave) {
+template <int NL>
+__device__ __forceinline__ void dma_tile(__amdgpu_buffer_rsrc_t rs, unsigned char* tile, const uint32_t (&off)[NL],
+                                         const int (&row)[NL], int row0, int nrows, int64_t ld, int wave) {
+  constexpr int NW = 16 / NL;
   const uint32_t base = (uint32_t)row0 * (uint32_t)ld * 2u;
 #pragma unroll
-  for (int i = 0; i < 4; i++) {
+  for (int i = 0; i < NL; i++) {
     const uint32_t o = (row0 + row[i]) < nrows ? base + off[i] : DMA_OOB;
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, LRB_LDS_PTR(tile + (i * 4 + wave) * 1024), 16, (int)o, 0, 0, 0);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, LRB_LDS_PTR(tile + (i * NW + wave) * 1024), 16, (int)o, 0, 0, 0);
   }
 }
 // s_waitcnt vmcnt(0) alone (gfx9 encoding), and lgkmcnt(0) alone
@@ -181,6 +189,26 @@ __device__ __forceinline__ bf16x8 swz_tr_frag(const unsigned char* tile, int k0,
   const unsigned char* p1 = p0 + 8 * 256;
   s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0));
   s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p1));
+  typedef short s16x8 __attribute__((ext_vector_type(8)));
+  s16x8 r = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  return __builtin_bit_cast(bf16x8, r);
+}
+
+// The same two operand reads for a SWZ_BOTH tile (r0 and k0 multiples of 16, c0 a multiple of 32).
+__device__ __forceinline__ bf16x8 both_row_frag(const unsigned char* tile, int r0, int ks, int lane) {
+  const int l31 = lane & 31;
+  const int f = ((l31 & 3) << 2) | ((l31 >> 2) & 3);
+  return lds_b128(tile + (r0 + l31) * 256 + (((ks * 2 + (lane >> 5)) ^ f) << 4));
+}
+__device__ __forceinline__ bf16x8 both_tr_frag(const unsigned char* tile, int k0, int c0, int lane) {
+  const int g = lane >> 4, s = lane & 15;
+  const int rl = (g >> 1) * 4 + (s >> 2);
+  const int f0 = ((s >> 2) << 2) | (g >> 1);                    // rows k0 + rl; rows + 8 flip bit 1 of the term
+  const int chunk = (c0 >> 3) + (g & 1) * 2 + ((s & 3) >> 1);
+  const unsigned char* rowp = tile + (k0 + rl) * 256 + (s & 1) * 8;
+  s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(rowp + ((chunk ^ f0) << 4)));
+  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (s16x4 __attribute__((address_space(3)))*)(rowp + 8 * 256 + ((chunk ^ f0 ^ 2) << 4)));
   typedef short s16x8 __attribute__((ext_vector_type(8)));
   s16x8 r = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
   return __builtin_bit_cast(bf16x8, r);
@@ -208,8 +236,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const uint16_t* __rest
   const float c = scale * LOG2E;
   uint32_t offK[4], offV[4];
   int rowK[4], rowV[4];
-  dma_lane_offsets<SWZ_ROW16>(offK, rowK, ld, wave, lane);
-  dma_lane_offsets<SWZ_ROW4>(offV, rowV, ld, wave, lane);
+  dma_lane_offsets<SWZ_ROW16, 4>(offK, rowK, ld, wave, lane);
+  dma_lane_offsets<SWZ_ROW4, 4>(offV, rowV, ld, wave, lane);
   unsigned char* sK = smem;                              // 2 tiles
   unsigned char* sV = smem + 2 * TILE_BYTES;             // 2 tiles
 
@@ -355,10 +383,12 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const uint16_t* __rest
 }
 
 // ----------------------------------------------------------------------------------------------
-// D[b, head, q] = sum_h dO[q, h] * O[q, h] : 16 lanes per (token, head)
+// D[b, head, q] = sum_h dO[q, h] * O[q, h] : 16 lanes per (token, head); also lse2 = lse * log2(e)
 // ----------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void attn_dot_kernel(const uint16_t* __restrict__ dout, const uint16_t* __restrict__ o,
-                                                       float* __restrict__ D, int64_t ld, int S, int H, int64_t total) {
+                                                       const float* __restrict__ lse, float* __restrict__ D,
+                                                       float* __restrict__ lse2, int64_t ld, int S, int H,
+                                                       int64_t total) {
   const int64_t item = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 4;   // (token, head) pair
   const int sub = threadIdx.x & 15;
   float s = 0.f;
@@ -381,6 +411,7 @@ __global__ __launch_bounds__(256) void attn_dot_kernel(const uint16_t* __restric
   if (item < total && sub == 0) {
     const int64_t bidx = tok / S, qi = tok % S;
     D[(bidx * H + head) * S + qi] = s;
+    lse2[(bidx * H + head) * S + qi] = lse[(bidx * H + head) * S + qi] * LOG2E;   // exponent offset in base 2
   }
 }
 
@@ -523,11 +554,17 @@ constexpr int DQ_LDS = 2 * (KT * PB + KT * PT + KT * PB);
 // ----------------------------------------------------------------------------------------------
 // backward, dK and dV: workgroup owns 4 x 32 keys, streams 64-query tiles of Q and dO
 // ----------------------------------------------------------------------------------------------
+constexpr int DKV_STAGE = 2 * TILE_BYTES + 2 * KT * 4;     // Q tile, dO tile, lse2[64], D[64]
+constexpr int DKV_LDS = 2 * DKV_STAGE;
+
+// NB 32-key blocks per wavefront: every Q / dO operand read from LDS feeds NB MFMAs.  With NB = 1 the
+// four wavefronts together need 128 bytes of LDS operands per clock to keep the matrix pipes busy,
+// which is all the LDS delivers; NB = 2 halves that (the accumulators then fill the AGPR file).
 template <int NB>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                                                            const uint16_t* __restrict__ v,
                                                            const uint16_t* __restrict__ dout,
-                                                           const float* __restrict__ lse, const float* __restrict__ D,
+                                                           const float* __restrict__ lse2, const float* __restrict__ D,
                                                            uint16_t* __restrict__ dk, uint16_t* __restrict__ dv,
                                                            int64_t ld, int S, int H, float scale) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -538,6 +575,29 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const uint16_t* __res
   const int64_t tok0 = (int64_t)b * S;
   const int64_t hoff = head * HD;
   const float c = scale * LOG2E;
+  // Q and dO tiles are needed row-wise (S, dP) and transposed (dK^T, dV^T): one LDS copy each, in the
+  // swizzle that serves both reads, written by direct-to-LDS loads.
+  const __amdgpu_buffer_rsrc_t rsQ = tile_rsrc(q + tok0 * ld + hoff);
+  const __amdgpu_buffer_rsrc_t rsO = tile_rsrc(dout + tok0 * ld + hoff);
+  const __amdgpu_buffer_rsrc_t rsL = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)(lse2 + ((int64_t)b * H + head) * S), 0, (uint32_t)S * 4u, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsD = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)(D + ((int64_t)b * H + head) * S), 0, (uint32_t)S * 4u, 0x00020000);
+  uint32_t offT[4];
+  int rowT[4];
+  dma_lane_offsets<SWZ_BOTH, 4>(offT, rowT, ld, wave, lane);
+  // all loads of one 64-query tile: 4 + 4 tile loads per wavefront; wavefronts 0 and 1 also fetch the
+  // tile's 64 row scalars (out-of-range rows read as zeros: the resource ends at S)
+  auto dma_stage = [&](int st, int j) {
+    unsigned char* p = smem + st * DKV_STAGE;
+    dma_tile<4>(rsQ, p, offT, rowT, j * KT, S, ld, wave);
+    dma_tile<4>(rsO, p + TILE_BYTES, offT, rowT, j * KT, S, ld, wave);
+    if (wave == 0)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsL, LRB_LDS_PTR(p + 2 * TILE_BYTES), 4, (j * KT + lane) * 4, 0, 0, 0);
+    if (wave == 1)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsD, LRB_LDS_PTR(p + 2 * TILE_BYTES + KT * 4), 4, (j * KT + lane) * 4, 0, 0, 0);
+  };
+
   // one key block from the early end (most queries) and its mirror image from the late end: equal
   // work per workgroup
   for (int pass = 0; pass < 2; pass++) {
@@ -546,8 +606,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const uint16_t* __res
   const int n0 = kblk * BN;
   const int nw0 = n0 + wave * NB * 32;
 
-  // K and V rows of this wavefront stay in registers (B operands); every Q / dO fragment read from
-  // LDS then feeds NB MFMAs.
+  // K and V rows of this wavefront stay in registers (B operands).
   bf16x8 kf[NB][8], vf[NB][8];
   load_row_frags<NB>(kf, k + tok0 * ld + hoff, ld, nw0, S, lane);
   load_row_frags<NB>(vf, v + tok0 * ld + hoff, ld, nw0, S, lane);
@@ -562,52 +621,22 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const uint16_t* __res
 #pragma unroll
         for (int e = 0; e < 16; e++) akv[w][nb][hb][e] = 0.f;
 
-  // per stage: Q (b128), Q (transpose), dO (b128), dO (transpose), lse*log2e[64], D[64]
-  constexpr int STAGE = 2 * (KT * PB + KT * PT) + 2 * KT * 4;
-  const uint16_t* qb = q + tok0 * ld + hoff;
-  const uint16_t* dob = dout + tok0 * ld + hoff;
-  const float* lseb = lse + ((int64_t)b * H + head) * S;
-  const float* Db = D + ((int64_t)b * H + head) * S;
   const int jbeg = n0 / KT;                                // causal: first query tile that sees key n0
   const int jend = (S + KT - 1) / KT;
-
-  auto stage_ptrs = [&](int st, unsigned char*& qB, unsigned char*& qT, unsigned char*& dB, unsigned char*& dT,
-                        float*& sl, float*& sd) {
-    unsigned char* p = smem + st * STAGE;
-    qB = p; qT = qB + KT * PB; dB = qT + KT * PT; dT = dB + KT * PB;
-    sl = reinterpret_cast<float*>(dT + KT * PT); sd = sl + KT;
-  };
-  unsigned char *qB, *qT, *dB, *dT;
-  float *sl, *sd;
-  TileRegs tq = load_tile(qb, ld, jbeg * KT, S, tid), td = load_tile(dob, ld, jbeg * KT, S, tid);
-  float rl = 0.f, rd = 0.f;
-  if (tid < KT) {
-    const int qq = min(jbeg * KT + tid, S - 1);
-    rl = lseb[qq] * LOG2E;
-    rd = Db[qq];
-  }
-  stage_ptrs(0, qB, qT, dB, dT, sl, sd);
-  store_tile(qB, PB, tq, tid); store_tile(qT, PT, tq, tid);
-  store_tile(dB, PB, td, tid); store_tile(dT, PT, td, tid);
-  if (tid < KT) { sl[tid] = rl; sd[tid] = rd; }
+  dma_stage(0, jbeg);
+  wait_vm0();
   __syncthreads();
 
   for (int j = jbeg; j < jend; j++) {
     const int cur = (j - jbeg) & 1;
-    const bool more = j + 1 < jend;
-    if (more) {
-      tq = load_tile(qb, ld, (j + 1) * KT, S, tid);
-      td = load_tile(dob, ld, (j + 1) * KT, S, tid);
-      if (tid < KT) {
-        const int qq = min((j + 1) * KT + tid, S - 1);
-        rl = lseb[qq] * LOG2E;
-        rd = Db[qq];
-      }
-    }
-    stage_ptrs(cur, qB, qT, dB, dT, sl, sd);
+    if (j + 1 < jend) dma_stage(cur ^ 1, j + 1);           // lands while this tile is worked on
+    const unsigned char* sQ = smem + cur * DKV_STAGE;
+    const unsigned char* sO = sQ + TILE_BYTES;
+    const float* sl = reinterpret_cast<const float*>(sO + TILE_BYTES);
+    const float* sd = sl + KT;
     const int qt0 = j * KT;
-    // one 32-query block at a time (keeps the register footprint down); blocks entirely before this
-    // wavefront's keys are skipped, blocks entirely after them need no mask
+    // one 32-query block at a time; blocks entirely before this wavefront's keys are skipped, blocks
+    // entirely after them need no mask
 #pragma unroll 1
     for (int qb2 = 0; qb2 < 2; qb2++) {
       const int qb0 = qt0 + qb2 * 32;
@@ -619,13 +648,18 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const uint16_t* __res
         for (int e = 0; e < 16; e++) { st[nb][e] = 0.f; dp[nb][e] = 0.f; }
 #pragma unroll
       for (int ks = 0; ks < 8; ks++) {
-        const int off = (qb2 * 32 + (lane & 31)) * PB + (ks * 2 + (lane >> 5)) * 16;
-        const bf16x8 qfr = lds_b128(qB + off), dfr = lds_b128(dB + off);
+        const bf16x8 qfr = both_row_frag(sQ, qb2 * 32, ks, lane), dfr = both_row_frag(sO, qb2 * 32, ks, lane);
 #pragma unroll
         for (int nb = 0; nb < NB; nb++) {
           st[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qfr, kf[nb][ks], st[nb], 0, 0, 0);
           dp[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dfr, vf[nb][ks], dp[nb], 0, 0, 0);
         }
+      }
+      float4 slv[4], sdv[4];                               // rows 8 g + 4 (lane / 32) + 0..3, g = 0..3
+#pragma unroll
+      for (int g4 = 0; g4 < 4; g4++) {
+        slv[g4] = *reinterpret_cast<const float4*>(sl + qb2 * 32 + 8 * g4 + 4 * (lane >> 5));
+        sdv[g4] = *reinterpret_cast<const float4*>(sd + qb2 * 32 + 8 * g4 + 4 * (lane >> 5));
       }
       const bool need_mask = (qb0 < nw0 + NB * 32 - 1) || (qb0 + 32 > S);
 #pragma unroll
@@ -633,11 +667,15 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const uint16_t* __res
         const int ni = nw0 + nb * 32 + (lane & 31);
 #pragma unroll
         for (int e = 0; e < 16; e++) {
-          const int ql = qb2 * 32 + acc_row(e, lane);
-          float p = fast_exp2(fmaf(st[nb][e], c, -sl[ql]));
-          if (need_mask) p = (ni > qt0 + ql || qt0 + ql >= S) ? 0.f : p;
+          const float lv = e % 4 == 0 ? slv[e / 4].x : e % 4 == 1 ? slv[e / 4].y : e % 4 == 2 ? slv[e / 4].z : slv[e / 4].w;
+          const float dvv = e % 4 == 0 ? sdv[e / 4].x : e % 4 == 1 ? sdv[e / 4].y : e % 4 == 2 ? sdv[e / 4].z : sdv[e / 4].w;
+          float p = fast_exp2(fmaf(st[nb][e], c, -lv));
+          if (need_mask) {
+            const int qi = qb0 + acc_row(e, lane);
+            p = (ni > qi || qi >= S) ? 0.f : p;
+          }
           st[nb][e] = p;                                   // P
-          dp[nb][e] = p * (dp[nb][e] - sd[ql]);            // dS
+          dp[nb][e] = p * (dp[nb][e] - dvv);               // dS
         }
       }
 #pragma unroll
@@ -647,8 +685,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const uint16_t* __res
         for (int nb = 0; nb < NB; nb++) { pf[nb] = pack_acc_half(st[nb], t); dsf[nb] = pack_acc_half(dp[nb], t); }
 #pragma unroll
         for (int hb = 0; hb < 4; hb++) {
-          const bf16x8 dtf = lds_tr_frag(dT, qb2 * 32 + t * 16, hb * 32, lane);
-          const bf16x8 qtf = lds_tr_frag(qT, qb2 * 32 + t * 16, hb * 32, lane);
+          const bf16x8 dtf = both_tr_frag(sO, qb2 * 32 + t * 16, hb * 32, lane);
+          const bf16x8 qtf = both_tr_frag(sQ, qb2 * 32 + t * 16, hb * 32, lane);
 #pragma unroll
           for (int nb = 0; nb < NB; nb++) {
             akv[1][nb][hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dtf, pf[nb], akv[1][nb][hb], 0, 0, 0);
@@ -657,12 +695,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const uint16_t* __res
         }
       }
     }
-    if (more) {
-      stage_ptrs(cur ^ 1, qB, qT, dB, dT, sl, sd);
-      store_tile(qB, PB, tq, tid); store_tile(qT, PT, tq, tid);
-      store_tile(dB, PB, td, tid); store_tile(dT, PT, td, tid);
-      if (tid < KT) { sl[tid] = rl; sd[tid] = rd; }
-    }
+    wait_vm0();
     __syncthreads();
   }
 #pragma unroll
@@ -675,7 +708,6 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const uint16_t* __res
   }
   }  // pass
 }
-constexpr int DKV_LDS = 2 * (2 * (KT * PB + KT * PT) + 2 * KT * 4);
 
 template <class K>
 hipError_t set_lds(K kern, int bytes) {
@@ -687,6 +719,7 @@ hipError_t set_lds(K kern, int bytes) {
 hipError_t attention_fwd_bf16(const void* q, const void* k, const void* v, void* o, float* lse, int64_t ld, int B,
                               int S, int H, int hd, int causal, hipStream_t st) {
   if (hd != HD || !causal) return hipErrorNotSupported;
+  if ((int64_t)S * ld * 2 >= (int64_t)0x7fffffff) return hipErrorNotSupported;   // 32-bit buffer offsets per (batch, head)
   constexpr int MB = 1;
   constexpr int BQ = 4 * MB * 32;
   static bool once = false;
@@ -702,7 +735,8 @@ hipError_t attention_fwd_bf16(const void* q, const void* k, const void* v, void*
   return hipGetLastError();
 }
 
-size_t attention_bwd_ws_bytes(int B, int S, int H, int hd) { return (size_t)B * H * S * sizeof(float); }
+// D and the base-2 exponent offsets lse * log2(e), both [B, H, S] fp32
+size_t attention_bwd_ws_bytes(int B, int S, int H, int hd) { return 2 * (size_t)B * H * S * sizeof(float); }
 
 constexpr int DQ_MB = 2;    // 32-query blocks per wavefront in the dQ kernel
 constexpr int DKV_NB = 1;   // 32-key blocks per wavefront in the dK/dV kernel
@@ -711,6 +745,7 @@ hipError_t attention_bwd_bf16(const void* q, const void* k, const void* v, const
                               const float* lse, void* dq, void* dk, void* dv, int64_t ld, int B, int S, int H, int hd,
                               int causal, void* ws, hipStream_t st) {
   if (hd != HD || !causal) return hipErrorNotSupported;
+  if ((int64_t)S * ld * 2 >= (int64_t)0x7fffffff) return hipErrorNotSupported;   // 32-bit buffer offsets per (batch, head)
   static bool once = false;
   if (!once) {
     hipError_t e = set_lds(attn_bwd_dq_kernel<DQ_MB>, DQ_LDS);
@@ -721,14 +756,15 @@ hipError_t attention_bwd_bf16(const void* q, const void* k, const void* v, const
   }
   float* D = (float*)ws;
   const int64_t items = (int64_t)B * S * H;
+  float* lse2 = D + items;
   hipLaunchKernelGGL(attn_dot_kernel, dim3((unsigned)((items * 16 + 255) / 256)), dim3(256), 0, st,
-                     (const uint16_t*)dout, (const uint16_t*)o, D, ld, S, H, items);
+                     (const uint16_t*)dout, (const uint16_t*)o, lse, D, lse2, ld, S, H, items);
   const float scale = 1.f / sqrtf((float)hd);
   hipLaunchKernelGGL(attn_bwd_dq_kernel<DQ_MB>, dim3(((S + DQ_MB * 128 - 1) / (DQ_MB * 128) + 1) / 2, H, B), dim3(256), DQ_LDS, st, (const uint16_t*)q,
                      (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)dout, lse, D, (uint16_t*)dq, ld, S, H,
                      scale);
   hipLaunchKernelGGL(attn_bwd_dkv_kernel<DKV_NB>, dim3(((S + DKV_NB * 128 - 1) / (DKV_NB * 128) + 1) / 2, H, B), dim3(256), DKV_LDS, st, (const uint16_t*)q,
-                     (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)dout, lse, D, (uint16_t*)dk,
+                     (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)dout, lse2, D, (uint16_t*)dk,
                      (uint16_t*)dv, ld, S, H, scale);
   return hipGetLastError();
 }
