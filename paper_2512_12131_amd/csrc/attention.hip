@@ -422,7 +422,7 @@ template <int MB>
 __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                                                           const uint16_t* __restrict__ v,
                                                           const uint16_t* __restrict__ dout,
-                                                          const float* __restrict__ lse, const float* __restrict__ D,
+                                                          const float* __restrict__ lse2, const float* __restrict__ D,
                                                           uint16_t* __restrict__ dq, int64_t ld, int S, int H,
                                                           float scale) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -433,6 +433,13 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const uint16_t* __rest
   const int64_t tok0 = (int64_t)b * S;
   const int64_t hoff = head * HD;
   const float c = scale * LOG2E;
+  // K is needed row-wise (S^T) and transposed (dQ^T), V row-wise (dP^T): one LDS copy each, in the
+  // swizzle that serves both reads, written by direct-to-LDS loads.
+  const __amdgpu_buffer_rsrc_t rsK = tile_rsrc(k + tok0 * ld + hoff);
+  const __amdgpu_buffer_rsrc_t rsV = tile_rsrc(v + tok0 * ld + hoff);
+  uint32_t offT[4];
+  int rowT[4];
+  dma_lane_offsets<SWZ_BOTH, 4>(offT, rowT, ld, wave, lane);
   // one query block from the late end and its mirror image from the early end: equal work per workgroup
   for (int pass = 0; pass < 2; pass++) {
   const int qblk = pass == 0 ? nqb - 1 - (int)blockIdx.x : (int)blockIdx.x;
@@ -445,12 +452,12 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const uint16_t* __rest
   bf16x8 qf[MB][8], dof[MB][8];
   load_row_frags<MB>(qf, q + tok0 * ld + hoff, ld, qw0, S, lane);
   load_row_frags<MB>(dof, dout + tok0 * ld + hoff, ld, qw0, S, lane);
-  float lse2[MB], Dq[MB];
+  float lsq[MB], Dq[MB];
 #pragma unroll
   for (int mb = 0; mb < MB; mb++) {
     const int qi = qw0 + mb * 32 + (lane & 31);
     const int64_t sidx = ((int64_t)b * H + head) * S + min(qi, S - 1);
-    lse2[mb] = lse[sidx] * LOG2E;
+    lsq[mb] = lse2[sidx];
     Dq[mb] = D[sidx];
   }
 
@@ -462,28 +469,22 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const uint16_t* __rest
 #pragma unroll
       for (int e = 0; e < 16; e++) acc[mb][hb][e] = 0.f;
 
-  // K is needed both row-wise (S^T) and transposed (dQ^T): keep two LDS copies with the two pitches.
-  constexpr int STAGE = KT * PB + KT * PT + KT * PB;     // K (b128), K (transpose read), V (b128)
+  constexpr int STAGE = 2 * TILE_BYTES;                  // K, V
   const int kv_end = min(S, q0 + BQ);
   const int ntiles = (kv_end + KT - 1) / KT;
-  const uint16_t* kb = k + tok0 * ld + hoff;
-  const uint16_t* vb = v + tok0 * ld + hoff;
-  TileRegs tk = load_tile(kb, ld, 0, S, tid), tv = load_tile(vb, ld, 0, S, tid);
-  store_tile(smem, PB, tk, tid);
-  store_tile(smem + KT * PB, PT, tk, tid);
-  store_tile(smem + KT * PB + KT * PT, PB, tv, tid);
+  dma_tile<4>(rsK, smem, offT, rowT, 0, S, ld, wave);
+  dma_tile<4>(rsV, smem + TILE_BYTES, offT, rowT, 0, S, ld, wave);
+  wait_vm0();
   __syncthreads();
 
   for (int j = 0; j < ntiles; j++) {
     const int cur = j & 1;
-    const bool more = j + 1 < ntiles;
-    if (more) {
-      tk = load_tile(kb, ld, (j + 1) * KT, S, tid);
-      tv = load_tile(vb, ld, (j + 1) * KT, S, tid);
+    if (j + 1 < ntiles) {                                // lands while this tile is worked on
+      dma_tile<4>(rsK, smem + (cur ^ 1) * STAGE, offT, rowT, (j + 1) * KT, S, ld, wave);
+      dma_tile<4>(rsV, smem + (cur ^ 1) * STAGE + TILE_BYTES, offT, rowT, (j + 1) * KT, S, ld, wave);
     }
-    const unsigned char* sKb = smem + cur * STAGE;
-    const unsigned char* sKt = sKb + KT * PB;
-    const unsigned char* sVb = sKt + KT * PT;
+    const unsigned char* sK = smem + cur * STAGE;
+    const unsigned char* sVb = sK + TILE_BYTES;
     const int key0 = j * KT;
     // one 32-key block at a time; blocks entirely after this wavefront's queries are skipped
 #pragma unroll 1
@@ -497,8 +498,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const uint16_t* __rest
         for (int e = 0; e < 16; e++) { st[mb][e] = 0.f; dp[mb][e] = 0.f; }
 #pragma unroll
       for (int ks = 0; ks < 8; ks++) {
-        const int off = (nb * 32 + (lane & 31)) * PB + (ks * 2 + (lane >> 5)) * 16;
-        const bf16x8 kfr = lds_b128(sKb + off), vfr = lds_b128(sVb + off);
+        const bf16x8 kfr = both_row_frag(sK, nb * 32, ks, lane), vfr = both_row_frag(sVb, nb * 32, ks, lane);
 #pragma unroll
         for (int mb = 0; mb < MB; mb++) {
           st[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr, qf[mb][ks], st[mb], 0, 0, 0);
@@ -512,7 +512,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const uint16_t* __rest
         const int qi = qw0 + mb * 32 + (lane & 31);
 #pragma unroll
         for (int e = 0; e < 16; e++) {
-          float p = fast_exp2(fmaf(st[mb][e], c, -lse2[mb]));
+          float p = fast_exp2(fmaf(st[mb][e], c, -lsq[mb]));
           if (need_mask) {
             const int key = kb0 + acc_row(e, lane);
             p = (key > qi || key >= S) ? 0.f : p;
@@ -527,19 +527,14 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const uint16_t* __rest
         for (int mb = 0; mb < MB; mb++) dsf[mb] = pack_acc_half(st[mb], t);
 #pragma unroll
         for (int hb = 0; hb < 4; hb++) {
-          const bf16x8 ktf = lds_tr_frag(sKt, nb * 32 + t * 16, hb * 32, lane);
+          const bf16x8 ktf = both_tr_frag(sK, nb * 32 + t * 16, hb * 32, lane);
 #pragma unroll
           for (int mb = 0; mb < MB; mb++)
             acc[mb][hb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ktf, dsf[mb], acc[mb][hb], 0, 0, 0);
         }
       }
     }
-    if (more) {
-      unsigned char* nx = smem + (cur ^ 1) * STAGE;
-      store_tile(nx, PB, tk, tid);
-      store_tile(nx + KT * PB, PT, tk, tid);
-      store_tile(nx + KT * PB + KT * PT, PB, tv, tid);
-    }
+    wait_vm0();
     __syncthreads();
   }
 #pragma unroll
@@ -549,7 +544,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const uint16_t* __rest
   }
   }  // pass
 }
-constexpr int DQ_LDS = 2 * (KT * PB + KT * PT + KT * PB);
+constexpr int DQ_LDS = 4 * TILE_BYTES;   // K and V, double buffered
 
 // ----------------------------------------------------------------------------------------------
 // backward, dK and dV: workgroup owns 4 x 32 keys, streams 64-query tiles of Q and dO
@@ -761,7 +756,7 @@ hipError_t attention_bwd_bf16(const void* q, const void* k, const void* v, const
                      (const uint16_t*)dout, (const uint16_t*)o, lse, D, lse2, ld, S, H, items);
   const float scale = 1.f / sqrtf((float)hd);
   hipLaunchKernelGGL(attn_bwd_dq_kernel<DQ_MB>, dim3(((S + DQ_MB * 128 - 1) / (DQ_MB * 128) + 1) / 2, H, B), dim3(256), DQ_LDS, st, (const uint16_t*)q,
-                     (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)dout, lse, D, (uint16_t*)dq, ld, S, H,
+                     (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)dout, lse2, D, (uint16_t*)dq, ld, S, H,
                      scale);
   hipLaunchKernelGGL(attn_bwd_dkv_kernel<DKV_NB>, dim3(((S + DKV_NB * 128 - 1) / (DKV_NB * 128) + 1) / 2, H, B), dim3(256), DKV_LDS, st, (const uint16_t*)q,
                      (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)dout, lse2, D, (uint16_t*)dk,
