@@ -13,6 +13,8 @@ template <>
 struct VecIO<float, 1> {
   static __device__ __forceinline__ void load(const void* p, int64_t off, float* v) { v[0] = ((const float*)p)[off]; }
   static __device__ __forceinline__ void store(void* p, int64_t off, const float* v) { ((float*)p)[off] = v[0]; }
+  static __device__ __forceinline__ void load_nt(const void* p, int64_t off, float* v) { load(p, off, v); }
+  static __device__ __forceinline__ void store_nt(void* p, int64_t off, const float* v) { store(p, off, v); }
 };
 template <>
 struct VecIO<float, 8> {
@@ -26,6 +28,7 @@ struct VecIO<float, 8> {
     *reinterpret_cast<float4*>((float*)p + off + 4) = make_float4(v[4], v[5], v[6], v[7]);
   }
 };
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 template <>
 struct VecIO<bf16_t, 8> {
   static __device__ __forceinline__ void load(const void* p, int64_t off, float* v) {
@@ -34,6 +37,16 @@ struct VecIO<bf16_t, 8> {
   }
   static __device__ __forceinline__ void store(void* p, int64_t off, const float* v) {
     *reinterpret_cast<uint4*>((uint16_t*)p + off) = pack8(v);
+  }
+  // streaming forms for data touched once: non-temporal, so it does not displace reusable lines
+  static __device__ __forceinline__ void load_nt(const void* p, int64_t off, float* v) {
+    const u32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>((const uint16_t*)p + off));
+    unpack8(make_uint4(t.x, t.y, t.z, t.w), v);
+  }
+  static __device__ __forceinline__ void store_nt(void* p, int64_t off, const float* v) {
+    const uint4 q = pack8(v);
+    const u32x4_t t = {q.x, q.y, q.z, q.w};
+    __builtin_nontemporal_store(t, reinterpret_cast<u32x4_t*>((uint16_t*)p + off));
   }
 };
 
