@@ -50,6 +50,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="block-7B", choices=list(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="also run a plain device copy of this many MiB (3 times), so that a hardware-counter "
+                         "run of this command can scale FETCH_SIZE / WRITE_SIZE by a kernel of known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives are part of it); use --gpus 1", file=sys.stderr)
@@ -134,16 +137,28 @@ def main():
     stream_kernels["lr_rms_stat"] = round(nbytes / t / 1e6, 1)
     t = time_ms(lambda: B.lr_swiglu_fwd(g, u))
     stream_kernels["lr_swiglu_fwd"] = round(3 * nbytes / t / 1e6, 1)
-    t = time_ms(lambda: B.lr_swiglu_bwd(g, u, g))
+    dm = torch.randn((Ts, fs), device=dev, dtype=torch.bfloat16)
+    t = time_ms(lambda: B.lr_swiglu_bwd(g, u, dm))             # reads g, u, dm; writes dg, du
     stream_kernels["lr_swiglu_bwd"] = round(5 * nbytes / t / 1e6, 1)
+    del dm
     xs = g[:, :4096].contiguous()
+    dxh = u[:, :4096].contiguous()
+    dres = g[:, 4096:8192].contiguous()
     gam = torch.ones((4096,), device=dev, dtype=torch.bfloat16)
     st_ = B.lr_rms_stat(xs)
-    t = time_ms(lambda: B.lr_rmsnorm_bwd(xs, gam, st_, eps, xs, xs))
-    stream_kernels["lr_rmsnorm_bwd"] = round(5 * Ts * 4096 * 2 / t / 1e6, 1)
-    del g, u, xs
+    t = time_ms(lambda: B.lr_rmsnorm_bwd(xs, gam, st_, eps, dxh, dres))   # reads x, dxhat, dres; writes dx
+    stream_kernels["lr_rmsnorm_bwd"] = round(4 * Ts * 4096 * 2 / t / 1e6, 1)
+    del g, u, xs, dxh, dres
     stream = {"unit": "GB/s", "peak": HBM_PEAK_GBS, "algorithmic_bytes_over_time": stream_kernels,
               "frac": {k: round(v / HBM_PEAK_GBS, 3) for k, v in stream_kernels.items()}}
+
+    if args.calib_copy_mib > 0:
+        src = torch.empty(args.calib_copy_mib << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     out = {
         "metric": "TFLOP/s + % MFMA bf16 peak, low-rank decoder block fwd+bwd (1 MI355X)",
