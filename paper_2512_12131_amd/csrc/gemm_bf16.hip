@@ -463,7 +463,7 @@ hipError_t launch(const GemmOp& op, hipStream_t st) {
   return hipGetLastError();
 }
 
-using TileBig = Tile<256, 256, 2, 4>;   // 8 waves, 128x64 per wave
+using TileBig = Tile<256, 256, 4, 2>;   // 8 waves, 64x128 per wave
 using TileMid = Tile<256, 128, 2, 2>;   // 4 waves, 128x64 per wave (narrow N, weight gradients)
 
 template <class T>
