@@ -214,6 +214,25 @@ __device__ __forceinline__ bf16x8 both_tr_frag(const unsigned char* tile, int k0
   return __builtin_bit_cast(bf16x8, r);
 }
 
+// The hardware deals consecutive workgroup ids to the 8 XCDs in rotation.  This maps the id back so
+// that each XCD works through a contiguous range of (batch, head, block) triples, block fastest: the
+// workgroups that stream the same head's K / V (or Q / dO) tiles then share one XCD's L2 instead of
+// every XCD fetching every head.
+struct WgCoord { int x, head, b; };
+__device__ __forceinline__ WgCoord wg_coord() {
+  const int nx = gridDim.x, H = gridDim.y;
+  const int total = nx * H * (int)gridDim.z;
+  const int lin = (int)blockIdx.x + nx * ((int)blockIdx.y + H * (int)blockIdx.z);
+  const int xcd = lin % 8, loc = lin / 8;
+  const int base = total / 8, rem = total % 8;
+  const int v = xcd * base + (xcd < rem ? xcd : rem) + loc;
+  WgCoord c;
+  c.x = v % nx;
+  c.head = (v / nx) % H;
+  c.b = v / (nx * H);
+  return c;
+}
+
 constexpr int FWD_LDS = 4 * TILE_BYTES;   // K and V, double buffered
 
 // ----------------------------------------------------------------------------------------------
@@ -228,7 +247,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const uint16_t* __rest
   constexpr int BQ = 4 * MB * 32;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nqb = (S + BQ - 1) / BQ;
-  const int head = blockIdx.y, b = blockIdx.z;
+  const WgCoord wg = wg_coord();
+  const int head = wg.head, b = wg.b;
   const int64_t tok0 = (int64_t)b * S;
   const uint16_t* qb = q + tok0 * ld + head * HD;
   const __amdgpu_buffer_rsrc_t rsK = tile_rsrc(k + tok0 * ld + head * HD);
@@ -246,8 +266,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const uint16_t* __rest
   // same amount of work (the hardware deals workgroups to the XCDs in strict rotation: unequal
   // workgroups leave most of the chip waiting for the XCD that drew the heavy ones).
   for (int pass = 0; pass < 2; pass++) {
-  const int qblk = pass == 0 ? nqb - 1 - (int)blockIdx.x : (int)blockIdx.x;
-  if (pass == 1 && qblk >= nqb - 1 - (int)blockIdx.x) break;   // odd block count: the middle block has no mirror
+  const int qblk = pass == 0 ? nqb - 1 - wg.x : wg.x;
+  if (pass == 1 && qblk >= nqb - 1 - wg.x) break;   // odd block count: the middle block has no mirror
   const int q0 = qblk * BQ;
   const int qw0 = q0 + wave * MB * 32;                   // first query of this wavefront
 
@@ -429,7 +449,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const uint16_t* __rest
   constexpr int BQ = 4 * MB * 32;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nqb = (S + BQ - 1) / BQ;
-  const int head = blockIdx.y, b = blockIdx.z;
+  const WgCoord wg = wg_coord();
+  const int head = wg.head, b = wg.b;
   const int64_t tok0 = (int64_t)b * S;
   const int64_t hoff = head * HD;
   const float c = scale * LOG2E;
@@ -442,8 +463,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const uint16_t* __rest
   dma_lane_offsets<SWZ_BOTH, 4>(offT, rowT, ld, wave, lane);
   // one query block from the late end and its mirror image from the early end: equal work per workgroup
   for (int pass = 0; pass < 2; pass++) {
-  const int qblk = pass == 0 ? nqb - 1 - (int)blockIdx.x : (int)blockIdx.x;
-  if (pass == 1 && qblk >= nqb - 1 - (int)blockIdx.x) break;
+  const int qblk = pass == 0 ? nqb - 1 - wg.x : wg.x;
+  if (pass == 1 && qblk >= nqb - 1 - wg.x) break;
   const int q0 = qblk * BQ;
   const int qw0 = q0 + wave * MB * 32;
 
@@ -566,7 +587,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const uint16_t* __res
   constexpr int BN = 4 * NB * 32;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nkb = (S + BN - 1) / BN;
-  const int head = blockIdx.y, b = blockIdx.z;
+  const WgCoord wg = wg_coord();
+  const int head = wg.head, b = wg.b;
   const int64_t tok0 = (int64_t)b * S;
   const int64_t hoff = head * HD;
   const float c = scale * LOG2E;
@@ -596,8 +618,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const uint16_t* __res
   // one key block from the early end (most queries) and its mirror image from the late end: equal
   // work per workgroup
   for (int pass = 0; pass < 2; pass++) {
-  const int kblk = pass == 0 ? (int)blockIdx.x : nkb - 1 - (int)blockIdx.x;
-  if (pass == 1 && kblk <= (int)blockIdx.x) break;
+  const int kblk = pass == 0 ? wg.x : nkb - 1 - wg.x;
+  if (pass == 1 && kblk <= wg.x) break;
   const int n0 = kblk * BN;
   const int nw0 = n0 + wave * NB * 32;
 
