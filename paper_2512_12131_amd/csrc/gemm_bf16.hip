@@ -77,13 +77,18 @@ __device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xc
 // deals round-robin to one XCD form a contiguous range of tiles, and (b) consecutive tiles of that
 // range form compact panels (PM tiles tall), keeping the A rows and B rows they share in that
 // XCD's L2.
-__device__ __forceinline__ void tile_of_block(int bid, int total, int tiles_m, int tiles_n, int& tm, int& tn) {
+// The range runs over the whole launch, (batch member, k split) slowest: an XCD then works on tiles of
+// one batch member and one k range at a time, which is what lets its workgroups share operand slices.
+__device__ __forceinline__ void tile_of_block(int bid, int total, int tiles_m, int tiles_n, int& tm, int& tn, int& bz) {
   const int xcd = bid % NXCD, loc = bid / NXCD;
   const int base = total / NXCD, rem = total % NXCD;
   const int nid = xcd * base + (xcd < rem ? xcd : rem) + loc;
+  const int tiles = tiles_m * tiles_n;
+  bz = nid / tiles;
+  const int tid_ = nid % tiles;
   constexpr int PM = 8;
   const int per_panel = PM * tiles_n;
-  const int panel = nid / per_panel, within = nid % per_panel;
+  const int panel = tid_ / per_panel, within = tid_ % per_panel;
   const int pm_eff = min(PM, tiles_m - panel * PM);
   tn = within / pm_eff;
   tm = panel * PM + within % pm_eff;
@@ -104,10 +109,9 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / T::WN, wn = wave % T::WN;
-  int tm, tn;
-  tile_of_block(blockIdx.x, gridDim.x, tiles_m, tiles_n, tm, tn);
+  int tm, tn, bz;
+  tile_of_block(blockIdx.x + gridDim.x * blockIdx.y, gridDim.x * gridDim.y, tiles_m, tiles_n, tm, tn, bz);
   const int m0 = tm * T::BM, n0 = tn * T::BN;
-  const int bz = blockIdx.y;
   const int b = bz / op.splitk, ks = bz % op.splitk;
   const int kbeg = ks * kper, kend = min(op.K, kbeg + kper);
   const int nk = kend > kbeg ? (kend - kbeg + BK - 1) / BK : 0;
