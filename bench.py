@@ -27,6 +27,11 @@ WORKLOADS = {
 }
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 HBM_PEAK_GBS = 8000.0
+# Bytes per GEMM launch between L2 and the memory side, measured offline with rocprofv3 --pmc
+# FETCH_SIZE and WRITE_SIZE runs of this benchmark, each scaled by what the same counter reads for a
+# plain 1 GiB copy (x2.000 and x1.000): profiles/gemm_bf16_block-7B_hbm_traffic.txt.  Counters cannot
+# be read from inside this process, so workloads without such a measurement report null.
+MEASURED_GEMM_TRAFFIC_BYTES = {"block-7B": 721.3e6}
 
 
 def block_flops(B, S, d, H, f, r):
@@ -108,7 +113,8 @@ def main():
     flops_per_launch = fl["gemm_exec"] / launches_per_step        # algorithmic FLOPs (2MNK) per launch
     achieved = flops_per_launch / (avg_launch_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
+                "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(args.workload), "traffic_unit": "bytes per launch (offline counters)",
                 "kernel": "gemm_bf16_kernel (bf16 MFMA GEMM, all instantiations)",
                 "launches_per_step": round(launches_per_step, 1), "avg_launch_us": round(avg_launch_ms * 1e3, 2),
                 "gemm_ms_per_step": round(gemm_ms / max(args.steps, 1), 3),

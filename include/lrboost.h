@@ -153,7 +153,9 @@ int lr_block_bwd(const lr_block_desc* desc, const lr_block_params* params, const
 
 /* ---- causal multi-head attention (the sharded-safe op between the chunks, Sec. 4.2) ---- */
 /* q, k, v, o: [B*S, H*hd] token-major, head h in columns h*hd..; lse[B, H, S] fp32.
- * bf16 only, hd = 128.                                                                    */
+ * bf16 only, hd = 128, and S * ld * 2 < 2^31 bytes (the kernels address one batch element with
+ * 32-bit buffer offsets); otherwise LR_EUNSUPPORTED.  The backward workspace holds two [B, H, S]
+ * fp32 arrays (sum_h dO*O and lse * log2(e)).                                               */
 int lr_attention_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
                      int64_t ld, int64_t B, int64_t S, int64_t H, int64_t hd, int causal,
                      int dt, void* stream);
