@@ -1,7 +1,7 @@
 // Causal multi-head attention, head_dim 128, bf16 in / fp32 softmax, for gfx950.
 //
-// Forward (one workgroup = 4 wavefronts x MB*32 queries of one (batch, head); K/V stream through
-// LDS in 64-key tiles, double buffered):
+// Forward (one workgroup = 4 wavefronts x 32 queries of one (batch, head), for one query block and
+// its causal mirror; K/V stream through LDS in 64-key tiles, double buffered):
 //   S^T = K Q^T      MFMA, A = K rows from LDS, B = Q rows kept in registers for the whole kernel
 //   online softmax   per query = per lane column of the S^T accumulators (one cross-half shuffle)
 //   O^T += V^T P^T   MFMA, B = P^T straight from the softmax registers, A = V^T through the LDS
@@ -15,7 +15,7 @@
 //                S^T, dP^T = V dO^T, dS^T = P^T*(dP^T - D), dQ^T += K^T dS^T
 //   dkv kernel - workgroup owns 128 keys, streams 64-query tiles from the diagonal on:
 //                S = Q K^T, dP = dO V^T, dV^T += dO^T P, dK^T += Q^T dS
-// with D[q] = sum_h dO[q,h] O[q,h] from a small preprocessing kernel.
+// with D[q] = sum_h dO[q,h] O[q,h] and lse * log2(e) from a small preprocessing kernel.
 #include "common.h"
 
 namespace lrb {
@@ -23,8 +23,6 @@ namespace {
 
 constexpr int HD = 128;
 constexpr int KT = 64;            // keys (or queries, in the dkv kernel) per streamed tile
-constexpr int PB = 272;           // LDS row pitch for tiles read with ds_read_b128 (rows 4 banks apart)
-constexpr int PT = 320;           // LDS row pitch for tiles read with the transpose read
 constexpr float LOG2E = 1.4426950408889634f;
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -33,25 +31,6 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 __device__ __forceinline__ bf16x8 lds_b128(const unsigned char* p) { return *reinterpret_cast<const bf16x8*>(p); }
-
-// A operand of a 32x32x16 MFMA whose 32 rows are 32 consecutive columns (c0..c0+31) of an LDS tile
-// stored [k][col] with row pitch PT, and whose 16 k slots are tile rows
-//   slot (half, e) -> k0 + (e/4)*8 + half*4 + e%4        (the accumulator-row permutation).
-// Inside each group of 16 lanes the transpose read hands lane i the i-th 16-bit column of the 4 x 16
-// block that the 16 lanes fetched as 4 rows x 4 lanes x 8 bytes.
-__device__ __forceinline__ bf16x8 lds_tr_frag(const unsigned char* tile, int k0, int c0, int lane) {
-  const int g = lane >> 4, s = lane & 15;
-  const int half = g >> 1;
-  const int col = c0 + (g & 1) * 16 + (s & 3) * 4;
-  const int row = k0 + half * 4 + (s >> 2);
-  const unsigned char* p0 = tile + row * PT + col * 2;
-  const unsigned char* p1 = p0 + 8 * PT;
-  s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0));
-  s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p1));
-  typedef short s16x8 __attribute__((ext_vector_type(8)));
-  s16x8 r = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-  return __builtin_bit_cast(bf16x8, r);
-}
 
 // 8 consecutive accumulator values (v = t*8 .. t*8+7) packed as the bf16 B operand of one k16 step.
 __device__ __forceinline__ bf16x8 pack_acc_half(const f32x16& a, int t) {
@@ -65,27 +44,6 @@ __device__ __forceinline__ bf16x8 pack_acc_half(const f32x16& a, int t) {
 
 // Row index of accumulator element v inside a 32-row block.
 __device__ __forceinline__ int acc_row(int v, int lane) { return 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3); }
-
-// Copies a [KT rows][128] bf16 tile (global row stride ld elements) into registers: 4 x 16 bytes per
-// thread; rows >= nrows read as zero.
-struct TileRegs { uint4 r[4]; };
-__device__ __forceinline__ TileRegs load_tile(const uint16_t* base, int64_t ld, int row0, int nrows, int tid) {
-  TileRegs t;
-#pragma unroll
-  for (int i = 0; i < 4; i++) {
-    const int c = tid + i * 256, row = c >> 4, kc = c & 15;
-    const bool ok = (row0 + row) < nrows;
-    t.r[i] = ok ? *reinterpret_cast<const uint4*>(base + (int64_t)(row0 + row) * ld + kc * 8) : make_uint4(0, 0, 0, 0);
-  }
-  return t;
-}
-__device__ __forceinline__ void store_tile(unsigned char* lds, int pitch, const TileRegs& t, int tid) {
-#pragma unroll
-  for (int i = 0; i < 4; i++) {
-    const int c = tid + i * 256, row = c >> 4, kc = c & 15;
-    *reinterpret_cast<uint4*>(lds + row * pitch + kc * 16) = t.r[i];
-  }
-}
 
 // Query-row fragments kept in registers: B operand (rows = queries) for all 8 k16 steps over h.
 template <int MB>
@@ -180,7 +138,10 @@ __device__ __forceinline__ bf16x8 swz_row_frag(const unsigned char* tile, int r0
   return lds_b128(tile + row * 256 + (((ks * 2 + (lane >> 5)) ^ (lane & 15)) << 4));
 }
 // Transposed A operand from a SWZ_ROW4 tile stored [k][col]: rows = columns c0..c0+31 (c0 a multiple
-// of 32), k slots = tile rows k0 + (e/4)*8 + half*4 + e%4 (k0 a multiple of 16); see lds_tr_frag.
+// of 32), k slots (half = lane / 32, e = 0..7) = tile rows k0 + (e/4)*8 + half*4 + e%4 (k0 a multiple
+// of 16), which is the row order of a 32x32 accumulator.  Inside each group of 16 lanes the transpose
+// read hands lane i the i-th 16-bit column of the 4 x 16 block that the 16 lanes fetched as 4 rows x
+// 4 lanes x 8 bytes.
 __device__ __forceinline__ bf16x8 swz_tr_frag(const unsigned char* tile, int k0, int c0, int lane) {
   const int g = lane >> 4, s = lane & 15;
   const int rl = (g >> 1) * 4 + (s >> 2);                       // row inside the 16-row group; rl % 4 = s / 4
