@@ -24,6 +24,9 @@ WORKLOADS = {
     "block-1B": (8, 2048, 2048, 16, 5461, 512),
     "block-7B-r128": (4, 4096, 4096, 32, 11008, 128),
     "block-tiny": (2, 256, 256, 2, 344, 64),
+    # one rank's share of the 7B block under bottleneck-aware tensor parallelism at TP = 8 (Sec. 4.1):
+    # d, heads and d_ff divided by 8, the rank-r tensors whole; the all-reduces between chunks are not run
+    "block-7B-btp8-shard": (4, 4096, 512, 4, 1376, 1024),
 }
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 HBM_PEAK_GBS = 8000.0
@@ -55,6 +58,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="block-7B", choices=list(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--ablation", action="store_true",
+                    help="add an 'ablation' object: grouped / batched projections and the statistic taken "
+                         "inside the GEMM against their separate forms (Table 3's compute rows, Sec. 5.3), "
+                         "and the cost of the rank-r checkpoint recompute (Table 5), at 4096 and 16384 tokens")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run a plain device copy of this many MiB (3 times), so that a hardware-counter "
                          "run of this command can scale FETCH_SIZE / WRITE_SIZE by a kernel of known traffic")
@@ -158,6 +165,64 @@ def main():
     stream = {"unit": "GB/s", "peak": HBM_PEAK_GBS, "algorithmic_bytes_over_time": stream_kernels,
               "frac": {k: round(v / HBM_PEAK_GBS, 3) for k, v in stream_kernels.items()}}
 
+    if args.ablation:
+        out_abl = {}
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(1)
+
+        def rnd(*shape, scale=1.0):
+            return (torch.randn(shape, device=dev, generator=gen) * scale).to(torch.bfloat16)
+
+        for Ta in (4096, 16384):
+            xa = rnd(Ta, d)
+            gam = torch.ones((d,), device=dev, dtype=torch.bfloat16)
+            wd_cat = rnd(3 * r, d, scale=d ** -0.5)
+            wu_st = rnd(3, d, r, scale=r ** -0.5)
+            dys = rnd(3, Ta, d)
+            # grouped down-projection + batched up-projections, statistic from the GEMM's A tiles
+            zc, st_, ys = B.lr_group_fwd(xa, gam, eps, B.LR_NORM_ONLINE, wd_cat, wu_st)
+            t_gf = time_ms(lambda: B.lr_group_fwd(xa, gam, eps, B.LR_NORM_ONLINE, wd_cat, wu_st))
+            t_gb = time_ms(lambda: B.lr_group_bwd(xa, gam, eps, B.LR_NORM_ONLINE, wd_cat, wu_st, zc, st_, dys))
+            # the same with the statistic from a separate pass over x
+            t_2f = time_ms(lambda: B.lr_group_fwd(xa, gam, eps, B.LR_NORM_TWO_PASS, wd_cat, wu_st))
+            # three separate low-rank layers on a pre-normalised input (norm kernels timed with them)
+            stx = B.lr_rms_stat(xa)
+            xh = B.lr_rmsnorm_apply(xa, gam, stx, eps)
+            zs = [B.lr_linear_fwd(xh, wd_cat[i * r:(i + 1) * r], wu_st[i])[0] for i in range(3)]
+
+            def sep_fwd():
+                s_ = B.lr_rms_stat(xa)
+                h_ = B.lr_rmsnorm_apply(xa, gam, s_, eps)
+                for i in range(3):
+                    B.lr_linear_fwd(h_, wd_cat[i * r:(i + 1) * r], wu_st[i])
+
+            def sep_bwd():
+                acc = None
+                for i in range(3):
+                    dxi = B.lr_linear_bwd(xh, wd_cat[i * r:(i + 1) * r], wu_st[i], zs[i], dys[i])[0]
+                    acc = dxi if acc is None else acc.add_(dxi)
+                B.lr_rmsnorm_bwd(xa, gam, stx, eps, acc)
+
+            t_sf, t_sb = time_ms(sep_fwd), time_ms(sep_bwd)
+            out_abl[f"T={Ta}"] = {"grouped_fwd_ms": round(t_gf, 4), "grouped_bwd_ms": round(t_gb, 4),
+                                  "grouped_two_pass_stat_fwd_ms": round(t_2f, 4),
+                                  "separate_fwd_ms": round(t_sf, 4), "separate_bwd_ms": round(t_sb, 4),
+                                  "fwd_speedup": round(t_sf / t_gf, 3), "bwd_speedup": round(t_sb / t_gb, 3)}
+            del xa, wd_cat, wu_st, dys, zc, ys, xh, zs
+        # rank-r checkpointing: memory kept per block against every d- and d_ff-wide activation, and the
+        # time of the re-forward it costs (forward minus the four down-projections that are not redone:
+        # their outputs are the checkpoints)
+        t_fwd = time_ms(lambda: B.lr_block_fwd(desc, params, x, ckpt=ck, ws=ws, y=y))
+        t_bwd = time_ms(lambda: B.lr_block_bwd(desc, params, x, dy, ck, grads=grads, accumulate=False, ws=ws, dx=dx))
+        kept = 7 * T * r * 2 + 2 * T * 4
+        full = (T * d * 2) * 8 + (T * f * 2) * 3 + 7 * T * r * 2 * 2   # xhat1,q,k,v,o,h1,xhat2,(y) + g,u,m + z and sigma(z)
+        out_abl["checkpoint"] = {"block_fwd_ms": round(t_fwd, 4), "block_bwd_ms": round(t_bwd, 4),
+                                 "kept_MB": round(kept / 1e6, 1), "store_everything_MB": round(full / 1e6, 1),
+                                 "delta_mem_MB": round((full - kept) / 1e6, 1)}
+        ablation = out_abl
+    else:
+        ablation = None
+
     if args.calib_copy_mib > 0:
         src = torch.empty(args.calib_copy_mib << 20, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
@@ -180,6 +245,8 @@ def main():
         "roofline": roofline,
         "hbm_bound_kernels": stream,
     }
+    if ablation is not None:
+        out["ablation"] = ablation
 
     if not args.no_cpu_baseline:
         # fp64 oracle on the host cores, bounded sample: forward + backward of the same block on the

@@ -55,6 +55,9 @@ SMALL = [
     (2, 192, 2, 344, 64),     # ragged against the 128-query / 64-key / 256-row tiles
     (1, 300, 1, 200, 32),
     (3, 128, 2, 512, 128),
+    # the shape of one rank's share under bottleneck-aware tensor parallelism (Sec. 4.1) at TP = 8 of
+    # the 7B model: d/8 = 512 model columns, 4 heads, d_ff/8 = 1376, every rank-r tensor whole (r > d)
+    (1, 320, 4, 1376, 1024),
 ]
 
 
