@@ -247,10 +247,19 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
       const unsigned char* sb = b_slot(kt) + krow * (T::BN * 2);
       typedef short s16x4 __attribute__((ext_vector_type(4)));
       typedef short s16x8 __attribute__((ext_vector_type(8)));
+      // The transpose reads are issued as inline assembly.  Through the builtin, the compiler cannot
+      // tell them from a read of the slot that the global->LDS loads in flight are writing, and puts a
+      // wait for ALL outstanding global loads in front of each group of reads (which throws away the
+      // two slices of load lead).  The price: the compiler does not wait for their results either, so
+      // every k16 step of this form ends with an explicit wait for the LDS counter behind a scheduling
+      // barrier (see the main loop).
       auto tr_pair = [&](const unsigned char* base, int pitch, int col, int swz) -> bf16x8 {
         const int off = (((col >> 3) ^ swz) << 4) + (col & 7) * 2;
-        s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(base + off));
-        s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(base + 8 * pitch + off));
+        const uint32_t a0 = (uint32_t)(uintptr_t)LRB_LDS_PTR(base + off);
+        const uint32_t a1 = (uint32_t)(uintptr_t)LRB_LDS_PTR(base + 8 * pitch + off);
+        s16x4 lo, hi;
+        asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo) : "v"(a0) : "memory");
+        asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(hi) : "v"(a1) : "memory");
         s16x8 r = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
         return __builtin_bit_cast(bf16x8, r);
       };
@@ -309,6 +318,10 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
   wait_vmcnt<T::WLOADS_A + HLB>();   // A(0), B(0) landed; A(1) and half of B(1) may fly
   __builtin_amdgcn_s_barrier();
   load_frags(0, 0, 0);
+  if constexpr (KM) {
+    wait_lgkmcnt0();
+    __builtin_amdgcn_sched_barrier(0);
+  }
   for (int kt = 0; kt < nk; kt++) {
     static_for<3>([&](auto KK) {
       constexpr int kk = decltype(KK)::value;
@@ -326,6 +339,10 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
         if (i * NL / (T::FM + T::FN) != (i + 1) * NL / (T::FM + T::FN))
           __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // VMEM read (global -> LDS)
       }
+      if constexpr (KM) {
+        __builtin_amdgcn_sched_barrier(0);
+        wait_lgkmcnt0();                   // the next step's operands (inline-assembly reads) have arrived
+      }
       __builtin_amdgcn_sched_barrier(0);
     });
     wait_vmcnt<T::WLOADS_A>();             // A(kt+1), B(kt+1) of this wavefront landed; A(kt+2) may fly
@@ -341,6 +358,10 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
       __builtin_amdgcn_sched_group_barrier(0x100, KM ? 2 : 1, 0);     // DS read
       if (i * HLB / (T::FM + T::FN) != (i + 1) * HLB / (T::FM + T::FN))
         __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // VMEM read (global -> LDS)
+    }
+    if constexpr (KM) {
+      __builtin_amdgcn_sched_barrier(0);
+      wait_lgkmcnt0();
     }
     __builtin_amdgcn_sched_barrier(0);
   }
