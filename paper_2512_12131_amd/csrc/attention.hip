@@ -97,8 +97,27 @@ enum { SWZ_ROW16 = 0, SWZ_ROW4 = 1, SWZ_BOTH = 2 };
 //                                        different terms, 4 consecutive rows 4 different 64-byte groups
 #define LRB_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rsrc(const uint16_t* base) {
-  return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, 0x7fffffff, 0x00020000);
+// Buffer resource as four scalar words: base address, stride 0, size in bytes, data format word.
+typedef uint32_t rsrc_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+  const uint64_t a = (uint64_t)(uintptr_t)base;
+  rsrc_t r = {(uint32_t)a, (uint32_t)(a >> 32) & 0xffffu, bytes, 0x00020000u};
+  return r;
+}
+__device__ __forceinline__ rsrc_t tile_rsrc(const uint16_t* base) { return make_rsrc(base, 0x7fffffffu); }
+
+// One global -> LDS load of BYTES (4 or 16) per lane: lane L's data lands at lds + BYTES * L.  Issued
+// as inline assembly on purpose: through the builtin the compiler treats every later LDS read as a
+// possible read of this load's destination and makes it wait for ALL global loads in flight, i.e. the
+// tile being worked on would wait for the next tile's loads.  Completion is tracked by hand instead
+// (wait_vm0 before the barrier that publishes a tile).  `lds` must be wavefront-uniform.
+template <int BYTES>
+__device__ __forceinline__ void lds_dma(rsrc_t rs, const unsigned char* lds, uint32_t voff) {
+  const uint32_t m0v = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)LRB_LDS_PTR(lds));
+  if constexpr (BYTES == 16)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(m0v), "v"(voff), "s"(rs) : "memory");
+  else
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds" ::"s"(m0v), "v"(voff), "s"(rs) : "memory");
 }
 
 // Per-lane byte offsets (row * ld + logical chunk) of the 16 / NW wavefront loads that a wavefront of
@@ -118,14 +137,14 @@ __device__ __forceinline__ void dma_lane_offsets(uint32_t (&off)[NL], int (&row)
   }
 }
 template <int NL>
-__device__ __forceinline__ void dma_tile(__amdgpu_buffer_rsrc_t rs, unsigned char* tile, const uint32_t (&off)[NL],
+__device__ __forceinline__ void dma_tile(rsrc_t rs, unsigned char* tile, const uint32_t (&off)[NL],
                                          const int (&row)[NL], int row0, int nrows, int64_t ld, int wave) {
   constexpr int NW = 16 / NL;
   const uint32_t base = (uint32_t)row0 * (uint32_t)ld * 2u;
 #pragma unroll
   for (int i = 0; i < NL; i++) {
     const uint32_t o = (row0 + row[i]) < nrows ? base + off[i] : DMA_OOB;
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, LRB_LDS_PTR(tile + (i * NW + wave) * 1024), 16, (int)o, 0, 0, 0);
+    lds_dma<16>(rs, tile + (i * NW + wave) * 1024, o);
   }
 }
 // s_waitcnt vmcnt(0) alone (gfx9 encoding), and lgkmcnt(0) alone
@@ -212,8 +231,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const uint16_t* __rest
   const int head = wg.head, b = wg.b;
   const int64_t tok0 = (int64_t)b * S;
   const uint16_t* qb = q + tok0 * ld + head * HD;
-  const __amdgpu_buffer_rsrc_t rsK = tile_rsrc(k + tok0 * ld + head * HD);
-  const __amdgpu_buffer_rsrc_t rsV = tile_rsrc(v + tok0 * ld + head * HD);
+  const rsrc_t rsK = tile_rsrc(k + tok0 * ld + head * HD);
+  const rsrc_t rsV = tile_rsrc(v + tok0 * ld + head * HD);
   const float c = scale * LOG2E;
   uint32_t offK[4], offV[4];
   int rowK[4], rowV[4];
@@ -417,8 +436,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const uint16_t* __rest
   const float c = scale * LOG2E;
   // K is needed row-wise (S^T) and transposed (dQ^T), V row-wise (dP^T): one LDS copy each, in the
   // swizzle that serves both reads, written by direct-to-LDS loads.
-  const __amdgpu_buffer_rsrc_t rsK = tile_rsrc(k + tok0 * ld + hoff);
-  const __amdgpu_buffer_rsrc_t rsV = tile_rsrc(v + tok0 * ld + hoff);
+  const rsrc_t rsK = tile_rsrc(k + tok0 * ld + hoff);
+  const rsrc_t rsV = tile_rsrc(v + tok0 * ld + hoff);
   uint32_t offT[4];
   int rowT[4];
   dma_lane_offsets<SWZ_BOTH, 4>(offT, rowT, ld, wave, lane);
@@ -555,12 +574,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const uint16_t* __res
   const float c = scale * LOG2E;
   // Q and dO tiles are needed row-wise (S, dP) and transposed (dK^T, dV^T): one LDS copy each, in the
   // swizzle that serves both reads, written by direct-to-LDS loads.
-  const __amdgpu_buffer_rsrc_t rsQ = tile_rsrc(q + tok0 * ld + hoff);
-  const __amdgpu_buffer_rsrc_t rsO = tile_rsrc(dout + tok0 * ld + hoff);
-  const __amdgpu_buffer_rsrc_t rsL = __builtin_amdgcn_make_buffer_rsrc(
-      (void*)(lse2 + ((int64_t)b * H + head) * S), 0, (uint32_t)S * 4u, 0x00020000);
-  const __amdgpu_buffer_rsrc_t rsD = __builtin_amdgcn_make_buffer_rsrc(
-      (void*)(D + ((int64_t)b * H + head) * S), 0, (uint32_t)S * 4u, 0x00020000);
+  const rsrc_t rsQ = tile_rsrc(q + tok0 * ld + hoff);
+  const rsrc_t rsO = tile_rsrc(dout + tok0 * ld + hoff);
+  const rsrc_t rsL = make_rsrc(lse2 + ((int64_t)b * H + head) * S, (uint32_t)S * 4u);
+  const rsrc_t rsD = make_rsrc(D + ((int64_t)b * H + head) * S, (uint32_t)S * 4u);
   uint32_t offT[4];
   int rowT[4];
   dma_lane_offsets<SWZ_BOTH, 4>(offT, rowT, ld, wave, lane);
@@ -571,9 +588,9 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const uint16_t* __res
     dma_tile<4>(rsQ, p, offT, rowT, j * KT, S, ld, wave);
     dma_tile<4>(rsO, p + TILE_BYTES, offT, rowT, j * KT, S, ld, wave);
     if (wave == 0)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsL, LRB_LDS_PTR(p + 2 * TILE_BYTES), 4, (j * KT + lane) * 4, 0, 0, 0);
+      lds_dma<4>(rsL, p + 2 * TILE_BYTES, (uint32_t)(j * KT + lane) * 4u);
     if (wave == 1)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsD, LRB_LDS_PTR(p + 2 * TILE_BYTES + KT * 4), 4, (j * KT + lane) * 4, 0, 0, 0);
+      lds_dma<4>(rsD, p + 2 * TILE_BYTES + KT * 4, (uint32_t)(j * KT + lane) * 4u);
   };
 
   // one key block from the early end (most queries) and its mirror image from the late end: equal
