@@ -51,6 +51,37 @@ def block_flops(B, S, d, H, f, r):
             "lin_fwd": lin_fwd, "attn_fwd": attn_fwd}
 
 
+def gemm_classes(B, S, d, H, f, r):
+    """Every GEMM launch class of one block step as (FLOPs, ideal bytes): 2MNK and one read of each
+    operand plus one write of the result (bf16; weight gradients leave as fp32)."""
+    T = B * S
+    out = []
+
+    def g(M, N, K, count=1, out_bytes=2):
+        out.append((count * 2.0 * M * N * K, count * (2.0 * (M * K + N * K) + out_bytes * M * N)))
+
+    # (input width, output width, group size) of the four grouped low-rank layers: qkv, o, gate/up, down
+    for d_in, d_out, G in ((d, d, 3), (d, d, 1), (d, f, 2), (f, d, 1)):
+        g(T, G * r, d_in)                 # forward: grouped down-projection
+        g(T, d_out, r, G)                 # forward: batched up-projections
+        g(T, r, d_out, G)                 # backward: data gradient through the up-projections
+        g(d_out, r, T, G, 4)              # backward: weight gradient of the up-projections
+        g(T, d_in, G * r)                 # backward: data gradient through the down-projection
+        g(G * r, d_in, T, 1, 4)           # backward: weight gradient of the down-projection
+    for d_out, G in ((d, 3), (d, 1), (f, 2)):
+        g(T, d_out, r, G)                 # re-forward from the rank-r checkpoints (all but the last layer)
+    return out
+
+
+def attainable_tflops(classes):
+    """FLOP-weighted bound of the GEMM launches: each class at min(MFMA peak, A.I. x HBM peak)."""
+    t = 0.0
+    for fl, by in classes:
+        bound = min(MFMA_BF16_PEAK_TFLOPS * 1e12, fl / by * HBM_PEAK_GBS * 1e9)
+        t += fl / bound
+    return sum(fl for fl, _ in classes) / t / 1e12
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -119,9 +150,15 @@ def main():
     avg_launch_ms = gemm_ms / max(gemm_launches, 1)
     flops_per_launch = fl["gemm_exec"] / launches_per_step        # algorithmic FLOPs (2MNK) per launch
     achieved = flops_per_launch / (avg_launch_ms * 1e-3) / 1e12
+    classes = gemm_classes(Bn, S, d, H, f, r)
+    assert abs(sum(c[0] for c in classes) - fl["gemm_exec"]) < 1e-6 * fl["gemm_exec"]
+    attainable = attainable_tflops(classes)
     roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
                 "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(args.workload), "traffic_unit": "bytes per launch (offline counters)",
+                # each launch class at min(MFMA peak, arithmetic intensity x HBM peak), FLOP-weighted: what
+                # the shapes of this workload allow (below the MFMA peak when the rank is small)
+                "attainable": round(attainable, 1), "frac_of_attainable": round(achieved / attainable, 4),
                 "kernel": "gemm_bf16_kernel (bf16 MFMA GEMM, all instantiations)",
                 "launches_per_step": round(launches_per_step, 1), "avg_launch_us": round(avg_launch_ms * 1e3, 2),
                 "gemm_ms_per_step": round(gemm_ms / max(args.steps, 1), 3),
