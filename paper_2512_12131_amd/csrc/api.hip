@@ -348,6 +348,7 @@ bool block_desc_ok(const lr_block_desc* ds, Blk& b, int* why) {
   if (ds->batch * ds->seq > 0x7fffffffLL || ds->ffn_ld > 0x7fffffffLL || 3 * ds->rank > 0x7fffffffLL) return false;
   *why = LR_EUNSUPPORTED;
   if (ds->dt != LR_BF16 || ds->head_dim != 128 || ds->causal != 1) return false;
+  if (ds->seq * ds->d_model * 2 >= 0x7fffffffLL) return false;   // attention: 32-bit byte offsets per batch element
   *why = LR_EALIGN;
   if (ds->d_model % 8 || ds->ffn_ld % 8 || ds->rank % 8) return false;
   b.B = ds->batch; b.S = ds->seq; b.T = ds->batch * ds->seq; b.d = ds->d_model; b.H = ds->n_heads; b.hd = ds->head_dim;
@@ -731,6 +732,7 @@ static int check_attn(int64_t ld, int64_t B, int64_t S, int64_t H, int64_t hd, i
   if (B <= 0 || S <= 0 || H <= 0 || hd <= 0 || ld < H * hd) return LR_EINVAL;
   if (B * S > 0x7fffffffLL || B * H > 0x7fffffffLL) return LR_EINVAL;
   if (dt != LR_BF16 || hd != 128 || causal != 1) return LR_EUNSUPPORTED;
+  if (S * ld * 2 >= 0x7fffffffLL) return LR_EUNSUPPORTED;   // the kernels use 32-bit byte offsets per batch element
   if (ld % 8) return LR_EALIGN;
   return LR_OK;
 }

@@ -57,6 +57,13 @@ def test_argument_errors_are_detected_on_the_host():
     assert f(fake, 64, fake, fake, fake, fake, 64, 8, 64, 16, 64, 1, 1, null, 0, None) == -3
     # T = 0 is a valid no-op
     assert f(fake, 64, fake, fake, fake, fake, 64, 0, 64, 16, 64, 1, 1, null, 0, None) == 0
+    # attention: sizes the kernels cannot address (32-bit byte offsets inside one batch element), other head
+    # sizes and non-causal masks are refused before anything is launched
+    a = lib.lr_attention_fwd
+    assert a(fake, fake, fake, fake, fake, 4096, 1, 1 << 20, 32, 128, 1, 1, None) == -2
+    assert a(fake, fake, fake, fake, fake, 2048, 1, 128, 32, 64, 1, 1, None) == -2
+    assert a(fake, fake, fake, fake, fake, 4096, 1, 128, 32, 128, 0, 1, None) == -2
+    assert a(fake, fake, fake, fake, null, 4096, 1, 128, 32, 128, 1, 1, None) == -1
 
 
 def test_workspace_queries_scale_and_reject():
