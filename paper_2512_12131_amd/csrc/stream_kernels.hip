@@ -359,6 +359,39 @@ __global__ __launch_bounds__(256) void transpose_kernel(const E* in, int64_t ld_
   }
 }
 
+// 16-bit elements, all extents and pitches multiples of 8: global accesses are 16-byte vectors on both
+// sides (a 2-byte-per-lane access moves 128 bytes per wavefront instruction, a 16-byte one 1 KB); the
+// element shuffle happens between LDS and registers.  Tile: 64 input rows x 64 input columns.
+__global__ __launch_bounds__(256) void transpose16_vec_kernel(const uint16_t* in, int64_t ld_in, uint16_t* out,
+                                                              int64_t ld_out, int64_t rows, int64_t cols, int64_t pad_to) {
+  __shared__ uint16_t tile[64][64 + 8];   // pitch 144 bytes: 16-byte aligned rows, column walks spread over banks
+  const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
+  const int t = threadIdx.x;
+#pragma unroll
+  for (int k = 0; k < 2; k++) {           // 64 rows x 8 vectors
+    const int v = t + k * 256, i = v >> 3, cv = (v & 7) * 8;
+    const int64_t r = r0 + i, c = c0 + cv;
+    uint4 q = make_uint4(0, 0, 0, 0);
+    if (r < rows && c < cols) q = *reinterpret_cast<const uint4*>(in + r * ld_in + c);
+    *reinterpret_cast<uint4*>(&tile[i][cv]) = q;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < 2; k++) {           // 64 output rows (input columns) x 8 vectors of 8 input rows
+    const int v = t + k * 256, i = v >> 3, rv = (v & 7) * 8;
+    const int64_t c = c0 + i, r = r0 + rv;
+    if (c < cols && r < pad_to) {
+      uint16_t e[8];
+#pragma unroll
+      for (int j = 0; j < 8; j++) e[j] = tile[rv + j][i];   // rows past `rows` were staged as zeros
+      uint4 q;
+      q.x = e[0] | ((uint32_t)e[1] << 16); q.y = e[2] | ((uint32_t)e[3] << 16);
+      q.z = e[4] | ((uint32_t)e[5] << 16); q.w = e[6] | ((uint32_t)e[7] << 16);
+      *reinterpret_cast<uint4*>(out + c * ld_out + r) = q;
+    }
+  }
+}
+
 __global__ __launch_bounds__(256) void rowsum_parts_kernel(const float* part, int64_t ld, int nparts, float* out,
                                                            int64_t M) {
   const int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -559,6 +592,10 @@ hipError_t k_transpose(const void* in, int64_t ld_in, void* out, int64_t ld_out,
   dim3 grid((cols + 63) / 64, (pad_to + 63) / 64);
   if (dt == LR_F32)
     hipLaunchKernelGGL(transpose_kernel<float>, grid, dim3(256), 0, st, (const float*)in, ld_in, (float*)out, ld_out,
+                       rows, cols, pad_to);
+  else if (rows % 8 == 0 && cols % 8 == 0 && ld_in % 8 == 0 && ld_out % 8 == 0 && ((uintptr_t)in & 15) == 0 &&
+           ((uintptr_t)out & 15) == 0)
+    hipLaunchKernelGGL(transpose16_vec_kernel, grid, dim3(256), 0, st, (const uint16_t*)in, ld_in, (uint16_t*)out, ld_out,
                        rows, cols, pad_to);
   else
     hipLaunchKernelGGL(transpose_kernel<uint16_t>, grid, dim3(256), 0, st, (const uint16_t*)in, ld_in, (uint16_t*)out,
