@@ -71,64 +71,60 @@ __device__ __forceinline__ bool epi_reads_r2(const Epilogue&) {
   return KIND == EPI_NORMBWD || KIND == EPI_SWIGLU_BWD;
 }
 
-// v[NV]: accumulators of row m, columns n..n+NV-1 of batch b; r[NV], r2[NV]: the matching entries of
-// the auxiliary tiles (already loaded; ignored by kinds that do not use them).  rho / rowb: per-row
-// scalars resolved by the caller (rho = 1 when unused).  Applies the fused elementwise work in fp32,
-// rounds once, stores, and returns this thread's contribution to the row partial (0 if none).
+// The arithmetic of an epilogue kind on NV consecutive columns of one row.  v[NV]: accumulators in,
+// primary output out; v2[NV]: secondary output (EPI_DOWN with want2, EPI_SWIGLU_BWD); r[NV], r2[NV]:
+// the matching entries of the auxiliary tiles (zeros where a kind's tile is absent: adding them is
+// harmless).  rho / rowb: per-row scalars resolved by the caller (rho = 1 when unused).  fp32 throughout;
+// returns this thread's contribution to the row partial (0 if the kind has none).
+template <int NV, int KIND>
+__device__ __forceinline__ float epi_math(int act, float inv_d, bool want2, float* v, float* v2, float rho, float rowb,
+                                          const float* r, const float* r2) {
+  float part = 0.f;
+  if constexpr (KIND == EPI_DOWN) {
+#pragma unroll
+    for (int i = 0; i < NV; i++) v[i] *= rho;
+    if (want2) {
+#pragma unroll
+      for (int i = 0; i < NV; i++) v2[i] = act_f(v[i], act);
+    }
+  } else if constexpr (KIND == EPI_UP) {
+#pragma unroll
+    for (int i = 0; i < NV; i++) {
+      v[i] += r[i];
+      part += v[i] * v[i];
+    }
+  } else if constexpr (KIND == EPI_ACTGRAD) {
+#pragma unroll
+    for (int i = 0; i < NV; i++) {
+      v[i] = v[i] * act_prime_f(r[i], act) * rho;
+      part += v[i] * r[i];
+    }
+  } else if constexpr (KIND == EPI_NORMBWD) {
+    const float coef = rho * inv_d * rowb;
+#pragma unroll
+    for (int i = 0; i < NV; i++) v[i] = v[i] - coef * r2[i] + r[i];
+  } else if constexpr (KIND == EPI_SWIGLU_BWD) {
+#pragma unroll
+    for (int i = 0; i < NV; i++) {
+      const float dm = v[i];
+      v2[i] = dm * silu_f(r[i]);
+      v[i] = dm * r2[i] * silu_prime_f(r[i]);
+    }
+  }
+  return part;
+}
+
+// epi_math, then the stores through plain pointers (the fp32 kernel's epilogue).
 template <typename ST, int NV, int KIND>
 __device__ __forceinline__ float epi_compute(const Epilogue& e, void* C, int64_t ldc, int64_t sC, int b, int64_t m,
                                              int64_t n, float* v, float rho, float rowb, const float* r,
                                              const float* r2) {
   using IO = VecIO<ST, NV>;
-  float part = 0.f;
-  const int64_t coff = (int64_t)b * sC + m * ldc + n;
-  if constexpr (KIND == EPI_STORE) {
-    IO::store(C, coff, v);
-  } else if constexpr (KIND == EPI_DOWN) {
-#pragma unroll
-    for (int i = 0; i < NV; i++) v[i] *= rho;
-    IO::store(C, coff, v);
-    if (e.C2) {
-      float a[NV];
-#pragma unroll
-      for (int i = 0; i < NV; i++) a[i] = act_f(v[i], e.act);
-      IO::store(e.C2, (int64_t)b * e.sC2 + m * e.ldc2 + n, a);
-    }
-  } else if constexpr (KIND == EPI_UP) {
-    if (e.R) {
-#pragma unroll
-      for (int i = 0; i < NV; i++) v[i] += r[i];
-    }
-    IO::store(C, coff, v);
-#pragma unroll
-    for (int i = 0; i < NV; i++) part += v[i] * v[i];
-  } else if constexpr (KIND == EPI_ACTGRAD) {
-#pragma unroll
-    for (int i = 0; i < NV; i++) {
-      v[i] = v[i] * act_prime_f(r[i], e.act) * rho;
-      part += v[i] * r[i];
-    }
-    IO::store(C, coff, v);
-  } else if constexpr (KIND == EPI_NORMBWD) {
-    const float coef = rho * e.inv_d * rowb;
-#pragma unroll
-    for (int i = 0; i < NV; i++) v[i] = v[i] - coef * r2[i];
-    if (e.R) {
-#pragma unroll
-      for (int i = 0; i < NV; i++) v[i] += r[i];
-    }
-    IO::store(C, coff, v);
-  } else if constexpr (KIND == EPI_SWIGLU_BWD) {
-    float du[NV];
-#pragma unroll
-    for (int i = 0; i < NV; i++) {
-      const float dm = v[i];
-      du[i] = dm * silu_f(r[i]);
-      v[i] = dm * r2[i] * silu_prime_f(r[i]);
-    }
-    IO::store(C, coff, v);
-    IO::store(e.C2, (int64_t)b * e.sC2 + m * e.ldc2 + n, du);
-  }
+  float v2[NV];
+  const bool want2 = KIND == EPI_SWIGLU_BWD || (KIND == EPI_DOWN && e.C2 != nullptr);
+  const float part = epi_math<NV, KIND>(e.act, e.inv_d, want2, v, v2, rho, rowb, r, r2);
+  IO::store(C, (int64_t)b * sC + m * ldc + n, v);
+  if (want2) IO::store(e.C2, (int64_t)b * e.sC2 + m * e.ldc2 + n, v2);
   return part;
 }
 

@@ -377,9 +377,13 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
   }
 
   // ---- epilogue: accumulators -> LDS (per-wave region) -> row-contiguous 8-wide vectors ---------
-  // The wavefront's sub-tile leaves in FM x (32/RPP) passes of RPP rows.  The auxiliary tiles an
-  // epilogue reads (residual, z, x, g, u) are fetched PF passes ahead into a small register ring, so
-  // their latency is covered by the passes in between instead of being paid once per pass.
+  // The wavefront's sub-tile leaves in FM x (32/RPP) passes of RPP rows.  Everything the passes touch
+  // in global memory goes through buffer resources that start at the tile's first row and end after
+  // its last valid row: rows past M (and, by an out-of-range offset, columns past N) read as zeros and
+  // are dropped on store, an absent auxiliary tile is a resource of size zero.  The pass code is
+  // therefore free of branches, which is what lets the compiler count the loads in flight exactly: the
+  // auxiliary tiles an epilogue reads (residual, z, x, g, u) are fetched PF passes ahead into a small
+  // register ring, and each pass waits only for its own.
   const Epilogue& e = op.epi;
   float* sC = reinterpret_cast<float*>(smem) + wave * (32 * T::CS);
   constexpr int LPR = T::TN / 8;            // lanes per output row
@@ -387,19 +391,45 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
   constexpr int PPB = 32 / RPP;             // passes per 32-row block
   constexpr int NQ = T::FM * PPB;           // passes per wavefront
   constexpr int PF = 4;                     // prefetch distance, in passes
+  constexpr uint32_t EOOB = 0x80000000u;
   const int cg = lane % LPR, rsub = lane / LPR;
-  const int64_t gn = (int64_t)n0 + wn * T::TN + cg * 8;
-  const bool use_r = KIND != EPI_PARTIAL && epi_reads_r<KIND>(e), use_r2 = KIND != EPI_PARTIAL && epi_reads_r2<KIND>(e);
-  uint4 auxr[PF], auxr2[PF];
+  const int rows_valid = min(T::BM, op.M - m0);
+  const int coln = n0 + wn * T::TN + cg * 8;                         // first of this lane's 8 columns
+  const bool col_ok = coln < op.N;
+  auto tile_rsrc = [&](const void* base, int64_t batch_stride, int64_t ld, int esz) {
+    const char* p = base ? (const char*)base + ((int64_t)b * batch_stride + (int64_t)m0 * ld) * esz : nullptr;
+    return __builtin_amdgcn_make_buffer_rsrc((void*)p, 0, base ? (uint32_t)rows_valid * (uint32_t)ld * (uint32_t)esz : 0u,
+                                             0x00020000);
+  };
+  auto row_rsrc = [&](const float* base) {   // per-row fp32 scalars of the tile's rows
+    return __builtin_amdgcn_make_buffer_rsrc((void*)(base ? base + m0 : nullptr), 0, base ? (uint32_t)rows_valid * 4u : 0u,
+                                             0x00020000);
+  };
+  constexpr bool PARTIAL = KIND == EPI_PARTIAL;
+  const __amdgpu_buffer_rsrc_t rsC = PARTIAL ? tile_rsrc(op.C, 0, op.N, 4) : tile_rsrc(op.C, op.sC, op.ldc, 2);
+  const int64_t c_extra = PARTIAL ? (int64_t)bz * op.M * op.N * 4 : 0;   // fp32 partials: [bz][M][N]
+  const __amdgpu_buffer_rsrc_t rsCp = PARTIAL ? __builtin_amdgcn_make_buffer_rsrc(
+      (void*)((char*)op.C + c_extra + (int64_t)m0 * op.N * 4), 0, (uint32_t)rows_valid * (uint32_t)op.N * 4u, 0x00020000) : rsC;
+  const __amdgpu_buffer_rsrc_t rsC2 = tile_rsrc(PARTIAL ? nullptr : e.C2, e.sC2, e.ldc2, 2);
+  const bool use_r = !PARTIAL && epi_reads_r<KIND>(e), use_r2 = !PARTIAL && epi_reads_r2<KIND>(e);
+  const __amdgpu_buffer_rsrc_t rsR = tile_rsrc(use_r ? e.R : nullptr, e.sR, e.ldr, 2);
+  const __amdgpu_buffer_rsrc_t rsR2 = tile_rsrc(use_r2 ? e.R2 : nullptr, e.sR2, e.ldr2, 2);
+  const __amdgpu_buffer_rsrc_t rsRowA = row_rsrc((!PARTIAL && e.use_rho && !STAT_A) ? e.rowa : nullptr);
+  const __amdgpu_buffer_rsrc_t rsRowB = row_rsrc(!PARTIAL ? e.rowb : nullptr);
+  const int ldC = PARTIAL ? op.N * 4 : (int)op.ldc * 2;               // row pitches in bytes
+  const int ldC2 = (int)e.ldc2 * 2, ldR = (int)e.ldr * 2, ldR2 = (int)e.ldr2 * 2;
+  const uint32_t colC = col_ok ? (uint32_t)coln * (PARTIAL ? 4u : 2u) : EOOB, col2 = col_ok ? (uint32_t)coln * 2u : EOOB;
+  const bool want2 = KIND == EPI_SWIGLU_BWD || (KIND == EPI_DOWN && e.C2 != nullptr);
+  const bool use_rho = !PARTIAL && e.use_rho;
+  const int act = e.act;
+  const float inv_d = e.inv_d, eps = e.eps;
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  u32x4 auxr[PF], auxr2[PF];
   auto row_of = [&](int q) { return wm * T::TM + (q / PPB) * 32 + (q % PPB) * RPP + rsub; };   // row inside the tile
-  auto fetch = [&](int q, uint4& ar, uint4& ar2) {
-    const int64_t gm = (int64_t)m0 + row_of(q);
-    ar = make_uint4(0, 0, 0, 0);
-    ar2 = make_uint4(0, 0, 0, 0);
-    if (gm < op.M && gn < op.N) {
-      if (use_r) ar = *reinterpret_cast<const uint4*>((const uint16_t*)e.R + (int64_t)b * e.sR + gm * e.ldr + gn);
-      if (use_r2) ar2 = *reinterpret_cast<const uint4*>((const uint16_t*)e.R2 + (int64_t)b * e.sR2 + gm * e.ldr2 + gn);
-    }
+  auto fetch = [&](int q, u32x4& ar, u32x4& ar2) {
+    const int lm = row_of(q);
+    ar = __builtin_amdgcn_raw_buffer_load_b128(rsR, (int)((uint32_t)(lm * ldR) + col2), 0, 0);
+    ar2 = __builtin_amdgcn_raw_buffer_load_b128(rsR2, (int)((uint32_t)(lm * ldR2) + col2), 0, 0);
   };
   if (use_r || use_r2) {
     static_for<PF>([&](auto Q) {
@@ -424,7 +454,6 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
     }
     const int rl = p * RPP + rsub;
     const int lm = wm * T::TM + i * 32 + rl;      // row inside the block tile
-    const int64_t gm = (int64_t)m0 + lm;
     float v[8];
     {
       const float4 lo = *reinterpret_cast<const float4*>(sC + rl * T::CS + cg * 8);
@@ -432,27 +461,34 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
       v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w;
       v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
     }
-    const bool ok = gm < op.M && gn < op.N;
-    float part = 0.f;
-    if constexpr (KIND == EPI_PARTIAL) {
-      if (ok) {
-        float* cp = (float*)op.C + ((int64_t)bz * op.M + gm) * op.N + gn;
-        *reinterpret_cast<float4*>(cp) = make_float4(v[0], v[1], v[2], v[3]);
-        *reinterpret_cast<float4*>(cp + 4) = make_float4(v[4], v[5], v[6], v[7]);
-      }
+    if constexpr (PARTIAL) {
+      const uint32_t off = (uint32_t)(lm * ldC) + colC;
+      const u32x4 lo = {__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])};
+      const u32x4 hi = {__float_as_uint(v[4]), __float_as_uint(v[5]), __float_as_uint(v[6]), __float_as_uint(v[7])};
+      __builtin_amdgcn_raw_buffer_store_b128(lo, rsCp, (int)off, 0, 0);
+      __builtin_amdgcn_raw_buffer_store_b128(hi, rsCp, (int)(off + 16u), 0, 0);
     } else {
-      if (ok) {
-        float rho = 1.f, rowb = 0.f;
-        if (e.use_rho) {
-          float ss;
-          if constexpr (STAT_A) ss = sStat[lm]; else ss = e.rowa[gm];
-          rho = rho_of(e, ss);
-        }
-        if (e.rowb) rowb = e.rowb[gm];
-        float r[8], r2[8];
-        unpack8(auxr[q % PF], r);
-        unpack8(auxr2[q % PF], r2);
-        part = epi_compute<bf16_t, 8, KIND>(e, op.C, op.ldc, op.sC, b, gm, gn, v, rho, rowb, r, r2);
+      float rho = 1.f, rowb = 0.f;
+      if (use_rho) {
+        float ss;
+        if constexpr (STAT_A) ss = sStat[lm];
+        else ss = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsRowA, lm * 4, 0, 0));
+        rho = rsqrtf(ss * inv_d + eps);
+      }
+      if constexpr (KIND == EPI_NORMBWD) rowb = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsRowB, lm * 4, 0, 0));
+      float r[8], r2[8], v2[8];
+      unpack8(make_uint4(auxr[q % PF].x, auxr[q % PF].y, auxr[q % PF].z, auxr[q % PF].w), r);
+      unpack8(make_uint4(auxr2[q % PF].x, auxr2[q % PF].y, auxr2[q % PF].z, auxr2[q % PF].w), r2);
+      float part = epi_math<8, KIND>(act, inv_d, want2, v, v2, rho, rowb, r, r2);
+      {
+        const uint4 o = pack8(v);
+        const u32x4 ov = {o.x, o.y, o.z, o.w};
+        __builtin_amdgcn_raw_buffer_store_b128(ov, rsC, (int)((uint32_t)(lm * ldC) + colC), 0, 0);
+      }
+      if (want2) {
+        const uint4 o = pack8(v2);
+        const u32x4 ov = {o.x, o.y, o.z, o.w};
+        __builtin_amdgcn_raw_buffer_store_b128(ov, rsC2, (int)((uint32_t)(lm * ldC2) + col2), 0, 0);
       }
       if constexpr (q + PF < NQ) {
         if (use_r || use_r2) fetch(q + PF, auxr[q % PF], auxr2[q % PF]);
@@ -461,11 +497,13 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
         if (e.rowpart) {
 #pragma unroll
           for (int o = 1; o < LPR; o <<= 1) part += __shfl_xor(part, o);
+          const int64_t gm = (int64_t)m0 + lm;
           if (cg == 0 && gm < op.M)
             e.rowpart[gm * e.rowpart_ld + e.rowpart_off + b * (tiles_n * T::WN) + tn * T::WN + wn] = part;
         }
       }
       if constexpr (STAT_A) {
+        const int64_t gm = (int64_t)m0 + lm;
         if (e.stat_out && tn == 0 && wn == 0 && b == 0 && cg == 0 && gm < op.M) e.stat_out[gm] = sStat[lm];
       }
     }
