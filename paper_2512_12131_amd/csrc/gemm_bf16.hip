@@ -406,10 +406,11 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
                                              0x00020000);
   };
   constexpr bool PARTIAL = KIND == EPI_PARTIAL;
-  const __amdgpu_buffer_rsrc_t rsC = PARTIAL ? tile_rsrc(op.C, 0, op.N, 4) : tile_rsrc(op.C, op.sC, op.ldc, 2);
-  const int64_t c_extra = PARTIAL ? (int64_t)bz * op.M * op.N * 4 : 0;   // fp32 partials: [bz][M][N]
-  const __amdgpu_buffer_rsrc_t rsCp = PARTIAL ? __builtin_amdgcn_make_buffer_rsrc(
-      (void*)((char*)op.C + c_extra + (int64_t)m0 * op.N * 4), 0, (uint32_t)rows_valid * (uint32_t)op.N * 4u, 0x00020000) : rsC;
+  // C: bf16 [batch][M][ldc]; fp32 split-K partials: [batch * split][M][N]
+  const __amdgpu_buffer_rsrc_t rsC = PARTIAL
+      ? __builtin_amdgcn_make_buffer_rsrc((void*)((char*)op.C + ((int64_t)bz * op.M + m0) * op.N * 4), 0,
+                                          (uint32_t)rows_valid * (uint32_t)op.N * 4u, 0x00020000)
+      : tile_rsrc(op.C, op.sC, op.ldc, 2);
   const __amdgpu_buffer_rsrc_t rsC2 = tile_rsrc(PARTIAL ? nullptr : e.C2, e.sC2, e.ldc2, 2);
   const bool use_r = !PARTIAL && epi_reads_r<KIND>(e), use_r2 = !PARTIAL && epi_reads_r2<KIND>(e);
   const __amdgpu_buffer_rsrc_t rsR = tile_rsrc(use_r ? e.R : nullptr, e.sR, e.ldr, 2);
@@ -421,6 +422,17 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
   const uint32_t colC = col_ok ? (uint32_t)coln * (PARTIAL ? 4u : 2u) : EOOB, col2 = col_ok ? (uint32_t)coln * 2u : EOOB;
   const bool want2 = KIND == EPI_SWIGLU_BWD || (KIND == EPI_DOWN && e.C2 != nullptr);
   const bool use_rho = !PARTIAL && e.use_rho;
+  // row partials [M, rowpart_ld] and the statistic [M]: one lane per row writes, the others (and rows
+  // past M) are given an out-of-range offset
+  constexpr bool ROWPART = KIND == EPI_UP || KIND == EPI_ACTGRAD;
+  const __amdgpu_buffer_rsrc_t rsPart = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)((ROWPART && e.rowpart) ? e.rowpart + (int64_t)m0 * e.rowpart_ld : nullptr), 0,
+      (ROWPART && e.rowpart) ? (uint32_t)rows_valid * (uint32_t)e.rowpart_ld * 4u : 0u, 0x00020000);
+  const int ldPart = ROWPART ? (int)e.rowpart_ld * 4 : 0;
+  const uint32_t colPart = cg == 0 ? (uint32_t)(e.rowpart_off + b * (tiles_n * T::WN) + tn * T::WN + wn) * 4u : EOOB;
+  const bool write_stat = STAT_A && e.stat_out && tn == 0 && wn == 0 && b == 0;
+  const __amdgpu_buffer_rsrc_t rsStat = row_rsrc(write_stat ? e.stat_out : nullptr);
+  const uint32_t colStat = cg == 0 ? 0u : EOOB;
   const int act = e.act;
   const float inv_d = e.inv_d, eps = e.eps;
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -465,8 +477,8 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
       const uint32_t off = (uint32_t)(lm * ldC) + colC;
       const u32x4 lo = {__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])};
       const u32x4 hi = {__float_as_uint(v[4]), __float_as_uint(v[5]), __float_as_uint(v[6]), __float_as_uint(v[7])};
-      __builtin_amdgcn_raw_buffer_store_b128(lo, rsCp, (int)off, 0, 0);
-      __builtin_amdgcn_raw_buffer_store_b128(hi, rsCp, (int)(off + 16u), 0, 0);
+      __builtin_amdgcn_raw_buffer_store_b128(lo, rsC, (int)off, 0, 0);
+      __builtin_amdgcn_raw_buffer_store_b128(hi, rsC, (int)(off + 16u), 0, 0);
     } else {
       float rho = 1.f, rowb = 0.f;
       if (use_rho) {
@@ -493,19 +505,13 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
       if constexpr (q + PF < NQ) {
         if (use_r || use_r2) fetch(q + PF, auxr[q % PF], auxr2[q % PF]);
       }
-      if constexpr (KIND == EPI_UP || KIND == EPI_ACTGRAD) {
-        if (e.rowpart) {
+      if constexpr (ROWPART) {
 #pragma unroll
-          for (int o = 1; o < LPR; o <<= 1) part += __shfl_xor(part, o);
-          const int64_t gm = (int64_t)m0 + lm;
-          if (cg == 0 && gm < op.M)
-            e.rowpart[gm * e.rowpart_ld + e.rowpart_off + b * (tiles_n * T::WN) + tn * T::WN + wn] = part;
-        }
+        for (int o = 1; o < LPR; o <<= 1) part += __shfl_xor(part, o);
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(part), rsPart, (int)((uint32_t)(lm * ldPart) + colPart), 0, 0);
       }
-      if constexpr (STAT_A) {
-        const int64_t gm = (int64_t)m0 + lm;
-        if (e.stat_out && tn == 0 && wn == 0 && b == 0 && cg == 0 && gm < op.M) e.stat_out[gm] = sStat[lm];
-      }
+      if constexpr (STAT_A)
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(sStat[lm]), rsStat, (int)((uint32_t)(lm * 4) + colStat), 0, 0);
     }
   });
 }
