@@ -449,6 +449,18 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
       if constexpr (q < NQ) fetch(q, auxr[q], auxr2[q]);
     });
   }
+  // per-row scalars of all passes, requested before the first pass
+  float ssv[NQ], rbv[NQ];
+  static_for<NQ>([&](auto Q) {
+    constexpr int q = decltype(Q)::value;
+    ssv[q] = 0.f;
+    rbv[q] = 0.f;
+    if constexpr (!PARTIAL && !STAT_A) {
+      if (use_rho) ssv[q] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsRowA, row_of(q) * 4, 0, 0));
+    }
+    if constexpr (KIND == EPI_NORMBWD)
+      rbv[q] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsRowB, row_of(q) * 4, 0, 0));
+  });
   static_for<NQ>([&](auto Q) {
     constexpr int q = decltype(Q)::value;
     constexpr int i = q / PPB, p = q % PPB;
@@ -484,10 +496,10 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
       if (use_rho) {
         float ss;
         if constexpr (STAT_A) ss = sStat[lm];
-        else ss = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsRowA, lm * 4, 0, 0));
+        else ss = ssv[q];
         rho = rsqrtf(ss * inv_d + eps);
       }
-      if constexpr (KIND == EPI_NORMBWD) rowb = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsRowB, lm * 4, 0, 0));
+      if constexpr (KIND == EPI_NORMBWD) rowb = rbv[q];
       float r[8], r2[8], v2[8];
       unpack8(make_uint4(auxr[q % PF].x, auxr[q % PF].y, auxr[q % PF].z, auxr[q % PF].w), r);
       unpack8(make_uint4(auxr2[q % PF].x, auxr2[q % PF].y, auxr2[q % PF].z, auxr2[q % PF].w), r2);
