@@ -398,6 +398,24 @@ void single_up_bwd(Ctx& c, const Blk& b, const void* dout, int64_t N, const void
   gemm(c, da);
 }
 
+// The gate / up pair of the MLP: g = act_g . W_up_g^T, then u = act_u . W_up_u^T whose epilogue forms
+// m = SiLU(g) * u from its fp32 accumulators and the g tile just written (the SwiGLU gate never
+// runs as a pass of its own).  u itself is stored only where a buffer is given: the forward has no use
+// for it, the backward's re-forward does.
+void mlp_up_swiglu(Ctx& c, const Blk& b, const void* w_up_gu, const void* act, void* g, void* u, void* m) {
+  const size_t es = 2;
+  GemmOp up;
+  up.A = act; up.lda = 2 * b.r; up.B = w_up_gu; up.ldb = b.r; up.C = g; up.ldc = b.f;
+  up.M = (int)b.T; up.N = (int)b.f; up.K = (int)b.r;
+  up.epi.kind = EPI_STORE;
+  gemm(c, up);
+  up.A = (const char*)act + (size_t)b.r * es;
+  up.B = (const char*)w_up_gu + (size_t)b.f * b.r * es;
+  up.C = u;
+  up.epi.kind = EPI_SWIGLU_FWD; up.epi.R = g; up.epi.ldr = b.f; up.epi.C2 = m; up.epi.ldc2 = b.f;
+  gemm(c, up);
+}
+
 GrpArgs group_args(const Blk& b, int G, int64_t d_out) {
   GrpArgs g{};
   g.G = G; g.T = b.T; g.d_in = b.d; g.r = b.r; g.d_out = d_out; g.act = b.act; g.norm = b.norm; g.eps = b.eps;
@@ -414,7 +432,7 @@ void block_fwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x
   void* h1 = c.take((size_t)T * d * es);
   float* lse = (float*)c.take((size_t)b.B * b.H * b.S * sizeof(float));
   void* act = c.take((size_t)T * 3 * r * es);     // sigma(z) of whichever projection group is live
-  void* gu = c.take((size_t)2 * T * f * es);
+  void* gg = c.take((size_t)T * f * es);
   void* mm = c.take((size_t)T * f * es);
   // attention side
   GrpArgs a = group_args(b, 3, d);
@@ -428,9 +446,9 @@ void block_fwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x
   // MLP side
   GrpArgs m = group_args(b, 2, f);
   m.x = h1; m.gamma = p->gamma2; m.w_down_cat = p->w_dn_gu; m.w_up_stack = p->w_up_gu;
-  m.z_cat = ck ? ck->z_gu : nullptr; m.stat = ck ? ck->s2 : nullptr; m.stat_ready = 1; m.y_stack = gu; m.act_out = act;
-  group_fwd_seq(c, m);
-  LAUNCH(c, k_swiglu_fwd(gu, (char*)gu + (size_t)T * f * es, mm, f, T, f, LR_BF16, c.st));
+  m.z_cat = ck ? ck->z_gu : nullptr; m.stat = ck ? ck->s2 : nullptr; m.stat_ready = 1; m.act_out = act;
+  group_down_seq(c, m, act);
+  mlp_up_swiglu(c, b, p->w_up_gu, act, gg, nullptr, mm);
   single_down(c, b, mm, f, p->w_dn_d, ck ? ck->z_d : nullptr, act);
   single_up(c, b, act, p->w_up_d, d, h1, y, nullptr);
 }
@@ -478,8 +496,7 @@ void block_bwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x
   LAUNCH(c, k_act_fwd(ck->z_gu, 2 * r, act_g, 2 * r, T, 2 * r, b.act, LR_BF16, c.st));
   GrpArgs m = group_args(b, 2, f);
   m.x = h1; m.gamma = p->gamma2; m.w_down_cat = p->w_dn_gu; m.w_up_stack = p->w_up_gu; m.y_stack = big;
-  group_up_seq(c, m, act_g);
-  LAUNCH(c, k_swiglu_fwd(big, (char*)big + (size_t)T * f * es, mm, f, T, f, LR_BF16, c.st));
+  mlp_up_swiglu(c, b, p->w_up_gu, act_g, big, (char*)big + (size_t)T * f * es, mm);
   // down-D backward: dW_dn_d = dz_d^T . m ; dm = dz_d . W_dn_d with the SwiGLU reverse fused in
   wgrad(c, dz1, r, (int)r, mm, f, (int)f, T, g->w_dn_d, nullptr, nullptr, nullptr, accumulate);
   {

@@ -19,7 +19,8 @@ enum EpiKind : int {
   EPI_ACTGRAD = 3,  // v = acc * act'(R) * rho_m ; C = v ; rowpart = sum_n v * R      (R = z)
   EPI_NORMBWD = 4,  // v = acc - (rho_m/d) * rowb_m * R2 + R ; C = v     (R2 = x, R = residual grad)
   EPI_PARTIAL = 5,  // fp32 store of a split-K partial: Cpart[split][M][N]
-  EPI_SWIGLU_BWD = 6  // v = acc (= dm); C = v*R2*silu'(R) (dg), C2 = v*silu(R) (du); R=g, R2=u
+  EPI_SWIGLU_BWD = 6,  // v = acc (= dm); C = v*R2*silu'(R) (dg), C2 = v*silu(R) (du); R=g, R2=u
+  EPI_SWIGLU_FWD = 7   // v = acc (= u); C = v (skipped when C is null), C2 = silu(R)*v (m); R = g
 };
 
 struct Epilogue {

@@ -64,7 +64,7 @@ struct VecIO<bf16_t, 1> {
 template <int KIND>
 __device__ __forceinline__ bool epi_reads_r(const Epilogue& e) {
   if constexpr (KIND == EPI_UP || KIND == EPI_NORMBWD) return e.R != nullptr;
-  return KIND == EPI_ACTGRAD || KIND == EPI_SWIGLU_BWD;
+  return KIND == EPI_ACTGRAD || KIND == EPI_SWIGLU_BWD || KIND == EPI_SWIGLU_FWD;
 }
 template <int KIND>
 __device__ __forceinline__ bool epi_reads_r2(const Epilogue&) {
@@ -110,6 +110,9 @@ __device__ __forceinline__ float epi_math(int act, float inv_d, bool want2, floa
       v2[i] = dm * silu_f(r[i]);
       v[i] = dm * r2[i] * silu_prime_f(r[i]);
     }
+  } else if constexpr (KIND == EPI_SWIGLU_FWD) {
+#pragma unroll
+    for (int i = 0; i < NV; i++) v2[i] = silu_f(r[i]) * v[i];
   }
   return part;
 }
@@ -121,9 +124,9 @@ __device__ __forceinline__ float epi_compute(const Epilogue& e, void* C, int64_t
                                              const float* r2) {
   using IO = VecIO<ST, NV>;
   float v2[NV];
-  const bool want2 = KIND == EPI_SWIGLU_BWD || (KIND == EPI_DOWN && e.C2 != nullptr);
+  const bool want2 = KIND == EPI_SWIGLU_BWD || KIND == EPI_SWIGLU_FWD || (KIND == EPI_DOWN && e.C2 != nullptr);
   const float part = epi_math<NV, KIND>(e.act, e.inv_d, want2, v, v2, rho, rowb, r, r2);
-  IO::store(C, (int64_t)b * sC + m * ldc + n, v);
+  if (KIND != EPI_SWIGLU_FWD || C != nullptr) IO::store(C, (int64_t)b * sC + m * ldc + n, v);
   if (want2) IO::store(e.C2, (int64_t)b * e.sC2 + m * e.ldc2 + n, v2);
   return part;
 }

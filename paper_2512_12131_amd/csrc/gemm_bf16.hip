@@ -420,7 +420,7 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
   const int ldC = PARTIAL ? op.N * 4 : (int)op.ldc * 2;               // row pitches in bytes
   const int ldC2 = (int)e.ldc2 * 2, ldR = (int)e.ldr * 2, ldR2 = (int)e.ldr2 * 2;
   const uint32_t colC = col_ok ? (uint32_t)coln * (PARTIAL ? 4u : 2u) : EOOB, col2 = col_ok ? (uint32_t)coln * 2u : EOOB;
-  const bool want2 = KIND == EPI_SWIGLU_BWD || (KIND == EPI_DOWN && e.C2 != nullptr);
+  const bool want2 = KIND == EPI_SWIGLU_BWD || KIND == EPI_SWIGLU_FWD || (KIND == EPI_DOWN && e.C2 != nullptr);
   const bool use_rho = !PARTIAL && e.use_rho;
   // row partials [M, rowpart_ld] and the statistic [M]: one lane per row writes, the others (and rows
   // past M) are given an out-of-range offset
@@ -561,6 +561,7 @@ hipError_t dispatch(const GemmOp& op, hipStream_t st) {
     case EPI_NORMBWD: return launch<T, EPI_NORMBWD, false>(op, st);
     case EPI_PARTIAL: return launch<T, EPI_PARTIAL, false>(op, st);
     case EPI_SWIGLU_BWD: return launch<T, EPI_SWIGLU_BWD, false>(op, st);
+    case EPI_SWIGLU_FWD: return launch<T, EPI_SWIGLU_FWD, false>(op, st);
     default: return hipErrorInvalidValue;
   }
 }

@@ -102,6 +102,7 @@ hipError_t gemm_f32(const GemmOp& op, hipStream_t st) {
     CASE(EPI_NORMBWD)
     CASE(EPI_PARTIAL)
     CASE(EPI_SWIGLU_BWD)
+    CASE(EPI_SWIGLU_FWD)
 #undef CASE
     default: return hipErrorInvalidValue;
   }
