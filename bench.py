@@ -27,6 +27,14 @@ WORKLOADS = {
     # one rank's share of the 7B block under bottleneck-aware tensor parallelism at TP = 8 (Sec. 4.1):
     # d, heads and d_ff divided by 8, the rank-r tensors whole; the all-reduces between chunks are not run
     "block-7B-btp8-shard": (4, 4096, 512, 4, 1376, 1024),
+    # the other model sizes of the paper's configuration table (App. "Model configuration"; heads of
+    # 128 here, the head counts follow from d_model), batch 4 x seq 4096 as in Sec. 5.1
+    "block-3B": (4, 4096, 3072, 24, 8192, 768),
+    "block-13B": (4, 4096, 5120, 40, 13824, 1280),
+    "block-30B": (4, 4096, 8192, 64, 22016, 2048),
+    # sigma = identity: the SVD-style factorisation without the rank-r non-linearity (App. "Low-rank
+    # Training Algorithm")
+    "block-7B-svd": (4, 4096, 4096, 32, 11008, 1024, "identity"),
 }
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 HBM_PEAK_GBS = 8000.0
@@ -108,11 +116,12 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     dev = "cuda:0"
-    Bn, S, d, H, f, r = WORKLOADS[args.workload]
+    Bn, S, d, H, f, r = WORKLOADS[args.workload][:6]
+    act = B.LR_ACT_IDENTITY if WORKLOADS[args.workload][6:] == ("identity",) else B.LR_ACT_SILU
     f_ld = si.pad_ld(f, 8)
     eps = 1e-5
     case = si.block_case(Bn, S, d, H, 128, f, r, seed=0)
-    desc = B.make_block_desc(Bn, S, d, H, 128, f, f_ld, r, eps=eps)
+    desc = B.make_block_desc(Bn, S, d, H, 128, f, f_ld, r, eps=eps, act=act)
     params = {k: v.to(dev) for k, v in si.pack_block_params(case["params"], f, f_ld).items()}
     x, dy = case["x"].to(dev), case["dy"].to(dev)
     ck = B.alloc_block_ckpt(desc, dev)
@@ -274,7 +283,8 @@ def main():
         "ms_per_step": round(dt * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: low-rank decoder block fwd+bwd, batch {Bn}, seq {S}, d_model {d}, "
-                               f"{H} heads of 128, ffn {f}, rank {r}, rank-r checkpoint recompute",
+                               f"{H} heads of 128, ffn {f}, rank {r}, sigma {'identity' if act == B.LR_ACT_IDENTITY else 'SiLU'}, "
+                               f"rank-r checkpoint recompute",
                    "tokens": T, "executed_tflop": round(fl["exec"] / 1e12, 3),
                    "model_tflop": round(fl["model"] / 1e12, 3),
                    "frac_mfma_peak_executed": round(value / MFMA_BF16_PEAK_TFLOPS, 4),
@@ -294,8 +304,9 @@ def main():
         P = {k: si.f64(v) for k, v in case["params"].items()}
         X0, DY0 = si.f64(case["x"][:s_len]), si.f64(case["dy"][:s_len])
         t0 = time.perf_counter()
-        orc.block_fwd(X0, P, 1, s_len, H, 128, eps)
-        orc.block_bwd(X0, P, DY0, 1, s_len, H, 128, eps)
+        oact = orc.ACT_IDENTITY if act == B.LR_ACT_IDENTITY else orc.ACT_SILU
+        orc.block_fwd(X0, P, 1, s_len, H, 128, eps, act=oact)
+        orc.block_bwd(X0, P, DY0, 1, s_len, H, 128, eps, act=oact)
         ct = time.perf_counter() - t0
         cfl = block_flops(1, s_len, d, H, f, r)
         cpu_flops = cfl["model"] + cfl["lin_fwd"] + cfl["attn_fwd"]   # block_bwd runs its own forward again

@@ -26,9 +26,9 @@ def _oracle_params(p):
     return {k: si.f64(v) for k, v in p.items()}
 
 
-def _run_gpu(case, Bn, S, d, H, f, r, norm=B.LR_NORM_ONLINE, grad_dt=B.LR_F32):
+def _run_gpu(case, Bn, S, d, H, f, r, norm=B.LR_NORM_ONLINE, grad_dt=B.LR_F32, act=B.LR_ACT_SILU):
     f_ld = si.pad_ld(f, 8)
-    desc = B.make_block_desc(Bn, S, d, H, d // H, f, f_ld, r, eps=EPS, norm=norm, grad_dt=grad_dt)
+    desc = B.make_block_desc(Bn, S, d, H, d // H, f, f_ld, r, eps=EPS, norm=norm, grad_dt=grad_dt, act=act)
     packed = {k: v.to(DEV) for k, v in si.pack_block_params(case["params"], f, f_ld).items()}
     x, dy = case["x"].to(DEV), case["dy"].to(DEV)
     y, ck = B.lr_block_fwd(desc, packed, x)
@@ -108,6 +108,31 @@ def test_block_odd_ffn_padding():
     for name in ("wd_d", "wu_g", "wu_u"):
         check("d" + name, got[name], g_ref[name], torch.bfloat16, floor=FLW)
     assert float(grads["w_dn_d"][:, f:].abs().max()) == 0.0
+
+
+def test_block_identity_sigma():
+    """sigma = identity at rank r (the SVD-style variant, App. "Low-rank Training Algorithm"): every
+    output against the oracle run with the same choice."""
+    Bn, S, H, f, r = 2, 192, 2, 344, 64
+    d = 128 * H
+    print("block identity sigma", flush=True)
+    case = si.block_case(Bn, S, d, H, 128, f, r, seed=5)
+    desc, packed, y, ck, dx, grads, f_ld = _run_gpu(case, Bn, S, d, H, f, r, act=B.LR_ACT_IDENTITY)
+    P = _oracle_params(case["params"])
+    X, DY = si.f64(case["x"]), si.f64(case["dy"])
+    y_ref, c = orc.block_fwd(X, P, Bn, S, H, 128, EPS, act=orc.ACT_IDENTITY)
+    dx_ref, g_ref = orc.block_bwd(X, P, DY, Bn, S, H, 128, EPS, act=orc.ACT_IDENTITY)
+    # the choice matters: the SiLU block differs from this one far beyond the tolerance
+    y_silu, _ = orc.block_fwd(X, P, Bn, S, H, 128, EPS)
+    assert np.abs(y_silu - y_ref).max() > 0.1 * np.sqrt(np.mean(y_ref ** 2))
+    dt = torch.bfloat16
+    check("y", y, y_ref, dt, floor=FL)
+    check("z_gu", ck["z_gu"], np.concatenate([c["z_g"], c["z_u"]], 1), dt, floor=FL)
+    check("z_d", ck["z_d"], c["z_d"], dt, floor=FL)
+    check("dx", dx, dx_ref, dt, floor=FL)
+    got = _unpack_grads(grads, f, r)
+    for name, ref in g_ref.items():
+        check("d" + name, got[name], ref, dt, floor=FLW)
 
 
 def test_block_accumulate_and_determinism():
