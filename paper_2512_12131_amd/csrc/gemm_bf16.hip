@@ -390,7 +390,12 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
   constexpr int RPP = 64 / LPR;             // rows per pass
   constexpr int PPB = 32 / RPP;             // passes per 32-row block
   constexpr int NQ = T::FM * PPB;           // passes per wavefront
-  constexpr int PF = 4;                     // prefetch distance, in passes
+  // which auxiliary tiles a kind can read at all, and the prefetch distance in passes: kinds with one
+  // auxiliary tile keep eight of its 16-byte vectors in flight per lane, kinds with two keep four of each
+  constexpr bool HAS_R = KIND == EPI_UP || KIND == EPI_ACTGRAD || KIND == EPI_NORMBWD || KIND == EPI_SWIGLU_BWD ||
+                         KIND == EPI_SWIGLU_FWD;
+  constexpr bool HAS_R2 = KIND == EPI_NORMBWD || KIND == EPI_SWIGLU_BWD;
+  constexpr int PF = HAS_R2 ? 4 : 8;
   constexpr uint32_t EOOB = 0x80000000u;
   const int cg = lane % LPR, rsub = lane / LPR;
   const int rows_valid = min(T::BM, op.M - m0);
@@ -440,15 +445,15 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
   auto row_of = [&](int q) { return wm * T::TM + (q / PPB) * 32 + (q % PPB) * RPP + rsub; };   // row inside the tile
   auto fetch = [&](int q, u32x4& ar, u32x4& ar2) {
     const int lm = row_of(q);
-    ar = __builtin_amdgcn_raw_buffer_load_b128(rsR, (int)((uint32_t)(lm * ldR) + col2), 0, 0);
-    ar2 = __builtin_amdgcn_raw_buffer_load_b128(rsR2, (int)((uint32_t)(lm * ldR2) + col2), 0, 0);
+    if constexpr (HAS_R) ar = __builtin_amdgcn_raw_buffer_load_b128(rsR, (int)((uint32_t)(lm * ldR) + col2), 0, 0);
+    if constexpr (HAS_R2) ar2 = __builtin_amdgcn_raw_buffer_load_b128(rsR2, (int)((uint32_t)(lm * ldR2) + col2), 0, 0);
   };
-  if (use_r || use_r2) {
-    static_for<PF>([&](auto Q) {
-      constexpr int q = decltype(Q)::value;
-      if constexpr (q < NQ) fetch(q, auxr[q], auxr2[q]);
-    });
-  }
+  static_for<PF>([&](auto Q) {
+    constexpr int q = decltype(Q)::value;
+    auxr[q] = u32x4{0u, 0u, 0u, 0u};
+    auxr2[q] = u32x4{0u, 0u, 0u, 0u};
+    if constexpr (q < NQ) fetch(q, auxr[q], auxr2[q]);
+  });
   // per-row scalars of all passes, requested before the first pass
   float ssv[NQ], rbv[NQ];
   static_for<NQ>([&](auto Q) {
@@ -514,9 +519,7 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
         const u32x4 ov = {o.x, o.y, o.z, o.w};
         __builtin_amdgcn_raw_buffer_store_b128(ov, rsC2, (int)((uint32_t)(lm * ldC2) + col2), 0, 0);
       }
-      if constexpr (q + PF < NQ) {
-        if (use_r || use_r2) fetch(q + PF, auxr[q % PF], auxr2[q % PF]);
-      }
+      if constexpr (q + PF < NQ) fetch(q + PF, auxr[q % PF], auxr2[q % PF]);
       if constexpr (ROWPART) {
 #pragma unroll
         for (int o = 1; o < LPR; o <<= 1) part += __shfl_xor(part, o);

@@ -34,7 +34,7 @@ __global__ __launch_bounds__(256) void rms_stat_kernel(const void* x, int64_t ld
 #pragma unroll
     for (int j = 0; j < U; j++) {
       const int64_t c = c0 + (j * 64 + lane) * S::NV;
-      if (c < d) IO::load(x, row * ldx + c, v[j]);
+      if (c < d) IO::load_nt(x, row * ldx + c, v[j]);
     }
 #pragma unroll
     for (int j = 0; j < U; j++) {
@@ -158,89 +158,99 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const void* x, int64_t
   }
 }
 
-// bf16, d <= 512 * NIT: a wavefront holds a whole row of x and of dxhat in registers (packed, as
-// loaded), so every tensor is read exactly once: reduce c, then write dx and add the row into the
-// lane's column partials of dgamma.  Same row ownership and partial layout as the kernel above.
+// bf16, d <= 512 * NIT: a wavefront holds a whole row of x, dxhat and the residual gradient in
+// registers (packed, as loaded), so every tensor is read exactly once: reduce c, then write dx and add
+// the row into the lane's column partials of dgamma.  Same partial layout as the kernel above; the rows
+// of a workgroup are interleaved with those of the others, so that the workgroups in flight together
+// sweep one contiguous window of each tensor.
+// All global accesses of the row loop go through buffer resources that span exactly one row (and
+// nothing, for an absent residual): columns past d read as zeros and are dropped on store without a
+// branch, so the loop body is straight-line code and all of a row's loads are in flight together.  (With a
+// bounds test per vector the compiler had put a full wait for memory between the vectors of the
+// second phase: 4.5 instead of the rate below.)
 template <int NIT>
 __global__ __launch_bounds__(256, 2) void rmsnorm_bwd_row_kernel(const uint16_t* x, int64_t ldx, const uint16_t* gamma,
                                                               const float* stat, float eps, const uint16_t* dxh,
                                                               int64_t lddxh, const uint16_t* dres, int64_t lddres,
                                                               uint16_t* dx, int64_t lddx, float* dgpart, int64_t T,
                                                               int64_t d) {
-  using IO = VecIO<bf16_t, 8>;
-  __shared__ float sred[4][64 * 8];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int64_t row0 = (int64_t)blockIdx.x * NB_RB;
+  // LDS: gamma (staged once per workgroup: re-reading it here costs no registers and, unlike a global
+  // re-read, does not queue behind the row's stores), then each wavefront's column partials of dgamma
+  // (kept here rather than in 64 registers per lane, which the row data needs)
+  extern __shared__ __align__(16) unsigned char rn_smem[];
+  uint4* sgam = reinterpret_cast<uint4*>(rn_smem);                           // [NIT * 64]
+  float4* sacc = reinterpret_cast<float4*>(rn_smem + NIT * 64 * 16);          // [4][NIT * 64][2]
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const float inv_d = 1.f / (float)d;
-  float acc[NIT][8];
-#pragma unroll
-  for (int it = 0; it < NIT; it++)
-#pragma unroll
-    for (int i = 0; i < 8; i++) acc[it][i] = 0.f;
-  // gamma (a few KB, cache resident) is re-read per row rather than held in registers
-  auto gamma_at = [&](int it) {
-    const int64_t col = (int64_t)(it * 64 + lane) * 8;
-    return col < d ? *reinterpret_cast<const uint4*>(gamma + col) : make_uint4(0, 0, 0, 0);
+  const uint32_t row_bytes = (uint32_t)d * 2u;
+  constexpr int NT_ = 2;   // cache policy of the streamed tensors: non-temporal
+  auto row_rsrc = [&](const uint16_t* base, int64_t row, int64_t ld) {
+    return __builtin_amdgcn_make_buffer_rsrc((void*)(base ? base + row * ld : nullptr), 0, base ? row_bytes : 0u,
+                                             0x00020000);
   };
-  for (int r = wave; r < NB_RB; r += 4) {
-    const int64_t row = row0 + r;
+  for (int e = threadIdx.x; e < NIT * 64; e += 256)
+    sgam[e] = (int64_t)e * 8 < d ? *reinterpret_cast<const uint4*>(gamma + (int64_t)e * 8) : make_uint4(0, 0, 0, 0);
+  float4* myacc = sacc + (wave * NIT * 64 + lane) * 2;      // + it * 128: this lane's 8 columns of slice it
+#pragma unroll
+  for (int it = 0; it < NIT; it++) {
+    myacc[it * 128] = make_float4(0.f, 0.f, 0.f, 0.f);
+    myacc[it * 128 + 1] = make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  __syncthreads();
+  auto u4 = [](const u32x4_t& t) { return make_uint4(t.x, t.y, t.z, t.w); };
+  for (int r = 0; r < NB_RB / 4; r++) {
+    const int64_t row = ((int64_t)r * gridDim.x + blockIdx.x) * 4 + wave;
     if (row >= T) break;
     const float rho = rsqrtf(stat[row] * inv_d + eps);
-    uint4 xq[NIT], dq[NIT];
+    const __amdgpu_buffer_rsrc_t rsX = row_rsrc(x, row, ldx), rsD = row_rsrc(dxh, row, lddxh),
+                                 rsR = row_rsrc(dres, row, lddres), rsO = row_rsrc(dx, row, lddx);
+    u32x4_t xq[NIT], dq[NIT], rq[NIT];
 #pragma unroll
     for (int it = 0; it < NIT; it++) {
-      const int64_t col = (int64_t)(it * 64 + lane) * 8;
-      xq[it] = make_uint4(0, 0, 0, 0);
-      dq[it] = make_uint4(0, 0, 0, 0);
-      if (col < d) {
-        xq[it] = *reinterpret_cast<const uint4*>(x + row * ldx + col);
-        dq[it] = *reinterpret_cast<const uint4*>(dxh + row * lddxh + col);
-      }
+      const int off = (it * 64 + lane) * 16;
+      xq[it] = __builtin_amdgcn_raw_buffer_load_b128(rsX, off, 0, NT_);
+      dq[it] = __builtin_amdgcn_raw_buffer_load_b128(rsD, off, 0, NT_);
     }
+#pragma unroll
+    for (int it = 0; it < NIT; it++) rq[it] = __builtin_amdgcn_raw_buffer_load_b128(rsR, (it * 64 + lane) * 16, 0, NT_);
     float s = 0.f;
 #pragma unroll
     for (int it = 0; it < NIT; it++) {
       float xv[8], gv[8], dv[8];
-      unpack8(xq[it], xv); unpack8(gamma_at(it), gv); unpack8(dq[it], dv);
+      unpack8(u4(xq[it]), xv); unpack8(sgam[it * 64 + lane], gv); unpack8(u4(dq[it]), dv);
 #pragma unroll
       for (int i = 0; i < 8; i++) s = fmaf(dv[i] * gv[i], xv[i] * rho, s);
+      // keeps the compiler from fetching and unpacking every slice's gamma at once (registers)
+      if (it % 2 == 1) __builtin_amdgcn_sched_barrier(0);
     }
     const float c = wave_sum(s) * inv_d;
 #pragma unroll
     for (int it = 0; it < NIT; it++) {
-      const int64_t col = (int64_t)(it * 64 + lane) * 8;
-      if (col < d) {
-        float xv[8], gv[8], dv[8], o[8];
-        unpack8(xq[it], xv); unpack8(gamma_at(it), gv); unpack8(dq[it], dv);
+      float xv[8], gv[8], dv[8], rv[8], o[8];
+      if (it % 2 == 0) __builtin_amdgcn_sched_barrier(0);
+      unpack8(u4(xq[it]), xv); unpack8(sgam[it * 64 + lane], gv); unpack8(u4(dq[it]), dv); unpack8(u4(rq[it]), rv);
+      float4 a0 = myacc[it * 128], a1 = myacc[it * 128 + 1];
+      float a[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
 #pragma unroll
-        for (int i = 0; i < 8; i++) {
-          const float n = xv[i] * rho;
-          o[i] = (dv[i] * gv[i] - n * c) * rho;
-          acc[it][i] = fmaf(dv[i], n, acc[it][i]);
-        }
-        if (dres) {
-          float rv[8];
-          IO::load_nt(dres, row * lddres + col, rv);
-#pragma unroll
-          for (int i = 0; i < 8; i++) o[i] += rv[i];
-        }
-        IO::store_nt(dx, row * lddx + col, o);
+      for (int i = 0; i < 8; i++) {
+        const float n = xv[i] * rho;
+        o[i] = (dv[i] * gv[i] - n * c) * rho + rv[i];
+        a[i] = fmaf(dv[i], n, a[i]);
       }
+      myacc[it * 128] = make_float4(a[0], a[1], a[2], a[3]);
+      myacc[it * 128 + 1] = make_float4(a[4], a[5], a[6], a[7]);
+      const uint4 ov = pack8(o);
+      __builtin_amdgcn_raw_buffer_store_b128(u32x4_t{ov.x, ov.y, ov.z, ov.w}, rsO, (it * 64 + lane) * 16, 0, NT_);
     }
   }
-  // add the four wavefronts' column partials, one 512-column slice at a time
-#pragma unroll
-  for (int it = 0; it < NIT; it++) {
-#pragma unroll
-    for (int i = 0; i < 8; i++) sred[wave][lane * 8 + i] = acc[it][i];
-    __syncthreads();
-    for (int e = threadIdx.x; e < 64 * 8; e += 256) {
-      const int64_t col = (int64_t)it * 512 + e;
-      if (col < d) dgpart[(int64_t)blockIdx.x * d + col] = sred[0][e] + sred[1][e] + sred[2][e] + sred[3][e];
-    }
-    __syncthreads();
+  // add the four wavefronts' column partials
+  __syncthreads();
+  const float* fa = reinterpret_cast<const float*>(sacc);
+  for (int e = threadIdx.x; e < NIT * 512; e += 256) {
+    if (e < d) dgpart[(int64_t)blockIdx.x * d + e] = fa[e] + fa[NIT * 512 + e] + fa[2 * NIT * 512 + e] + fa[3 * NIT * 512 + e];
   }
 }
+constexpr int RN_ROW_LDS = 8 * 64 * 16 + 4 * 8 * 512 * 4;   // rmsnorm_bwd_row_kernel<8>: gamma + four partial sets
 
 // ---- elementwise on [T, n] with leading dimensions -------------------------------------------
 // Each workgroup owns one contiguous run of EW_U x 256 vectors and issues all of its loads before the
@@ -559,9 +569,16 @@ hipError_t k_rmsnorm_bwd(const void* x, int64_t ldx, const void* gamma, const fl
                          float* dgamma_part, int64_t T, int64_t d, int dt, hipStream_t st) {
   if (T <= 0) return hipSuccess;
   if (dt == LR_BF16 && d <= 4096) {   // a row fits a wavefront's registers: single pass over every tensor
-    hipLaunchKernelGGL(rmsnorm_bwd_row_kernel<8>, dim3(k_rmsnorm_bwd_parts(T)), dim3(256), 0, st, (const uint16_t*)x, ldx,
-                       (const uint16_t*)gamma, stat, eps, (const uint16_t*)dxhat, lddxh, (const uint16_t*)dres, lddres,
-                       (uint16_t*)dx, lddx, dgamma_part, T, d);
+    static bool attr_set = false;   // one-time opt-in to more than 64 KB of dynamic LDS
+    if (!attr_set) {
+      hipError_t err = hipFuncSetAttribute((const void*)rmsnorm_bwd_row_kernel<8>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, RN_ROW_LDS);
+      if (err != hipSuccess) return err;
+      attr_set = true;
+    }
+    hipLaunchKernelGGL(rmsnorm_bwd_row_kernel<8>, dim3(k_rmsnorm_bwd_parts(T)), dim3(256), RN_ROW_LDS, st,
+                       (const uint16_t*)x, ldx, (const uint16_t*)gamma, stat, eps, (const uint16_t*)dxhat, lddxh,
+                       (const uint16_t*)dres, lddres, (uint16_t*)dx, lddx, dgamma_part, T, d);
     return hipGetLastError();
   }
   DISPATCH_DT(dt, rmsnorm_bwd_kernel, dim3(k_rmsnorm_bwd_parts(T)), dim3(256), st, x, ldx, gamma, stat, eps, dxhat,
