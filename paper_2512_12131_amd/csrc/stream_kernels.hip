@@ -346,6 +346,98 @@ __global__ __launch_bounds__(256) void swiglu_bwd_kernel(const void* g, const vo
   }
 }
 
+// ---- the same three maps for dense bf16 tensors (row pitch = row length), the form the block uses ------
+// The tensor is one flat array; a workgroup owns the 256 * U vectors from byte blockIdx.x * CHUNK on and
+// reaches them through a buffer resource that starts there and ends at the chunk's or the tensor's end,
+// whichever comes first: the tail needs no bounds test, the body is straight-line code, and all loads of
+// a lane are in flight before the first is used.  (With a test per vector the compiler waits for each
+// vector's load inside its branch, one memory round trip after the other.)
+constexpr int DENSE_U = 4, DENSE_U3 = 4;   // vectors per lane: one / two inputs, three inputs (measured best)
+constexpr int NT_POLICY = 2;   // buffer cache policy: non-temporal
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t chunk_rsrc(const void* p, int64_t total_bytes, int64_t chunk_bytes) {
+  const int64_t start = (int64_t)blockIdx.x * chunk_bytes;
+  const int64_t left = total_bytes - start;
+  return __builtin_amdgcn_make_buffer_rsrc((void*)((const char*)p + start), 0,
+                                           (uint32_t)(left < chunk_bytes ? left : chunk_bytes), 0x00020000);
+}
+__device__ __forceinline__ void unpack8v(const u32x4_t& t, float* v) { unpack8(make_uint4(t.x, t.y, t.z, t.w), v); }
+__device__ __forceinline__ u32x4_t pack8v(const float* v) {
+  const uint4 q = pack8(v);
+  return u32x4_t{q.x, q.y, q.z, q.w};
+}
+
+template <int U>
+__global__ __launch_bounds__(256) void act_fwd_dense_kernel(const void* z, void* a, int64_t total_bytes, int act) {
+  constexpr int64_t CHUNK = 256 * U * 16;
+  const __amdgpu_buffer_rsrc_t rz = chunk_rsrc(z, total_bytes, CHUNK), ra = chunk_rsrc(a, total_bytes, CHUNK);
+  u32x4_t q[U];
+#pragma unroll
+  for (int j = 0; j < U; j++) q[j] = __builtin_amdgcn_raw_buffer_load_b128(rz, (j * 256 + (int)threadIdx.x) * 16, 0, NT_POLICY);
+#pragma unroll
+  for (int j = 0; j < U; j++) {
+    float v[8];
+    unpack8v(q[j], v);
+#pragma unroll
+    for (int k = 0; k < 8; k++) v[k] = act_f(v[k], act);
+    __builtin_amdgcn_raw_buffer_store_b128(pack8v(v), ra, (j * 256 + (int)threadIdx.x) * 16, 0, NT_POLICY);
+  }
+}
+
+template <int U>
+__global__ __launch_bounds__(256) void swiglu_fwd_dense_kernel(const void* g, const void* u, void* m, int64_t total_bytes) {
+  constexpr int64_t CHUNK = 256 * U * 16;
+  const __amdgpu_buffer_rsrc_t rg = chunk_rsrc(g, total_bytes, CHUNK), ru = chunk_rsrc(u, total_bytes, CHUNK),
+                               rm = chunk_rsrc(m, total_bytes, CHUNK);
+  u32x4_t gq[U], uq[U];
+#pragma unroll
+  for (int j = 0; j < U; j++) {
+    const int off = (j * 256 + (int)threadIdx.x) * 16;
+    gq[j] = __builtin_amdgcn_raw_buffer_load_b128(rg, off, 0, NT_POLICY);
+    uq[j] = __builtin_amdgcn_raw_buffer_load_b128(ru, off, 0, NT_POLICY);
+  }
+#pragma unroll
+  for (int j = 0; j < U; j++) {
+    float gv[8], uv[8];
+    unpack8v(gq[j], gv);
+    unpack8v(uq[j], uv);
+#pragma unroll
+    for (int k = 0; k < 8; k++) gv[k] = silu_f(gv[k]) * uv[k];
+    __builtin_amdgcn_raw_buffer_store_b128(pack8v(gv), rm, (j * 256 + (int)threadIdx.x) * 16, 0, NT_POLICY);
+  }
+}
+
+template <int U>
+__global__ __launch_bounds__(256) void swiglu_bwd_dense_kernel(const void* g, const void* u, const void* dm, void* dg,
+                                                               void* du, int64_t total_bytes) {
+  constexpr int64_t CHUNK = 256 * U * 16;
+  const __amdgpu_buffer_rsrc_t rg = chunk_rsrc(g, total_bytes, CHUNK), ru = chunk_rsrc(u, total_bytes, CHUNK),
+                               rd = chunk_rsrc(dm, total_bytes, CHUNK), rdg = chunk_rsrc(dg, total_bytes, CHUNK),
+                               rdu = chunk_rsrc(du, total_bytes, CHUNK);
+  u32x4_t gq[U], uq[U], dq[U];
+#pragma unroll
+  for (int j = 0; j < U; j++) {
+    const int off = (j * 256 + (int)threadIdx.x) * 16;
+    gq[j] = __builtin_amdgcn_raw_buffer_load_b128(rg, off, 0, NT_POLICY);
+    uq[j] = __builtin_amdgcn_raw_buffer_load_b128(ru, off, 0, NT_POLICY);
+    dq[j] = __builtin_amdgcn_raw_buffer_load_b128(rd, off, 0, NT_POLICY);
+  }
+#pragma unroll
+  for (int j = 0; j < U; j++) {
+    float gv[8], uv[8], dv[8], o1[8], o2[8];
+    unpack8v(gq[j], gv);
+    unpack8v(uq[j], uv);
+    unpack8v(dq[j], dv);
+#pragma unroll
+    for (int k = 0; k < 8; k++) {
+      o1[k] = dv[k] * uv[k] * silu_prime_f(gv[k]);
+      o2[k] = dv[k] * silu_f(gv[k]);
+    }
+    const int off = (j * 256 + (int)threadIdx.x) * 16;
+    __builtin_amdgcn_raw_buffer_store_b128(pack8v(o1), rdg, off, 0, NT_POLICY);
+    __builtin_amdgcn_raw_buffer_store_b128(pack8v(o2), rdu, off, 0, NT_POLICY);
+  }
+}
+
 // ---- transpose: out[c, r] = in[r, c]; 64x64 tiles through LDS.  Output columns rows..pad_to-1
 // are written as zeros, so a transposed activation can serve as a k-contiguous GEMM operand whose
 // k extent is rounded up to the 16-byte vector.
@@ -587,18 +679,33 @@ hipError_t k_rmsnorm_bwd(const void* x, int64_t ldx, const void* gamma, const fl
 hipError_t k_act_fwd(const void* z, int64_t ldz, void* a, int64_t lda, int64_t T, int64_t n, int act, int dt,
                      hipStream_t st) {
   if (T <= 0 || n <= 0) return hipSuccess;
+  if (dt == LR_BF16 && ldz == n && lda == n) {
+    const int64_t bytes = T * n * 2;
+    hipLaunchKernelGGL(act_fwd_dense_kernel<DENSE_U>, dim3(grid_chunks(bytes / 16, 256 * DENSE_U)), dim3(256), 0, st, z, a, bytes, act);
+    return hipGetLastError();
+  }
   const int nv = dt == LR_BF16 ? 8 : 1;
   DISPATCH_DT(dt, act_fwd_kernel, dim3(grid_chunks(T * (n / nv), 256 * EW_U)), dim3(256), st, z, ldz, a, lda, T, n, act);
 }
 hipError_t k_swiglu_fwd(const void* g, const void* u, void* m, int64_t ld, int64_t T, int64_t f, int dt,
                         hipStream_t st) {
   if (T <= 0 || f <= 0) return hipSuccess;
+  if (dt == LR_BF16 && ld == f) {
+    const int64_t bytes = T * f * 2;
+    hipLaunchKernelGGL(swiglu_fwd_dense_kernel<DENSE_U>, dim3(grid_chunks(bytes / 16, 256 * DENSE_U)), dim3(256), 0, st, g, u, m, bytes);
+    return hipGetLastError();
+  }
   const int nv = dt == LR_BF16 ? 8 : 1;
   DISPATCH_DT(dt, swiglu_fwd_kernel, dim3(grid_chunks(T * (f / nv), 256 * EW_U)), dim3(256), st, g, u, m, ld, T, f);
 }
 hipError_t k_swiglu_bwd(const void* g, const void* u, const void* dm, void* dg, void* du, int64_t ld, int64_t T,
                         int64_t f, int dt, hipStream_t st) {
   if (T <= 0 || f <= 0) return hipSuccess;
+  if (dt == LR_BF16 && ld == f) {
+    const int64_t bytes = T * f * 2;
+    hipLaunchKernelGGL(swiglu_bwd_dense_kernel<DENSE_U3>, dim3(grid_chunks(bytes / 16, 256 * DENSE_U3)), dim3(256), 0, st, g, u, dm, dg, du, bytes);
+    return hipGetLastError();
+  }
   const int nv = dt == LR_BF16 ? 8 : 1;
   DISPATCH_DT(dt, swiglu_bwd_kernel, dim3(grid_chunks(T * (f / nv), 256 * EW_U3)), dim3(256), st, g, u, dm, dg, du, ld, T, f);
 }
