@@ -546,7 +546,9 @@ __global__ __launch_bounds__(256) void scale_cols_kernel(const void* w, const vo
 // 64-vector column strip: its 4 wavefronts take rows r, r+4, ... and add their column sums through LDS.
 constexpr int WF_RB = 32;  // rows per dgamma partial
 
-template <int DT, typename OT, bool DG>
+// NS > 0: the number of split-K partials is known at compile time, so their loads are issued
+// together instead of one dependent round trip per partial; NS = 0 takes any count.
+template <int DT, typename OT, bool DG, int NS>
 __global__ __launch_bounds__(256) void wgrad_finish_kernel(const float* part, int nsplit, int64_t rows, int64_t cols,
                                                            void* dw, const void* colscale, const void* wdg,
                                                            float* dgpart, int accumulate) {
@@ -563,12 +565,24 @@ __global__ __launch_bounds__(256) void wgrad_finish_kernel(const float* part, in
   for (int i = 0; i < NV; i++) { cs[i] = 1.f; dg[i] = 0.f; }
   auto one = [&](int64_t r, int64_t c) {
     float s[NV];
-    PIO::load(part, r * cols + c, s);
-    for (int sp = 1; sp < nsplit; sp++) {
-      float t[NV];
-      PIO::load(part, (int64_t)sp * count + r * cols + c, t);
+    if constexpr (NS > 0) {
+      float t[NS][NV];
 #pragma unroll
-      for (int i = 0; i < NV; i++) s[i] += t[i];
+      for (int sp = 0; sp < NS; sp++) PIO::load(part, (int64_t)sp * count + r * cols + c, t[sp]);
+#pragma unroll
+      for (int i = 0; i < NV; i++) s[i] = t[0][i];
+#pragma unroll
+      for (int sp = 1; sp < NS; sp++)
+#pragma unroll
+        for (int i = 0; i < NV; i++) s[i] += t[sp][i];
+    } else {
+      PIO::load(part, r * cols + c, s);
+      for (int sp = 1; sp < nsplit; sp++) {
+        float t[NV];
+        PIO::load(part, (int64_t)sp * count + r * cols + c, t);
+#pragma unroll
+        for (int i = 0; i < NV; i++) s[i] += t[i];
+      }
     }
     if constexpr (DG) {
       float wv[NV];
@@ -751,19 +765,30 @@ hipError_t k_wgrad_finish(const float* part, int nsplit, int64_t rows, int64_t c
   const bool dg = w_for_dgamma != nullptr && dgamma_part != nullptr;
   dim3 grid = dg ? dim3((unsigned)((cols / nv + 63) / 64), (unsigned)((rows + WF_RB - 1) / WF_RB))
                  : dim3((unsigned)((rows * (cols / nv) + 255) / 256));
-#define LRB_WF(DT_, OT_)                                                                                         \
+#define LRB_WF2(DT_, OT_, NS_)                                                                                   \
   do {                                                                                                           \
     if (dg)                                                                                                      \
-      hipLaunchKernelGGL((wgrad_finish_kernel<DT_, OT_, true>), grid, dim3(256), 0, st, part, nsplit, rows, cols, dw, \
+      hipLaunchKernelGGL((wgrad_finish_kernel<DT_, OT_, true, NS_>), grid, dim3(256), 0, st, part, nsplit, rows, cols, dw, \
                          colscale, w_for_dgamma, dgamma_part, accumulate);                                      \
     else                                                                                                         \
-      hipLaunchKernelGGL((wgrad_finish_kernel<DT_, OT_, false>), grid, dim3(256), 0, st, part, nsplit, rows, cols, dw, \
+      hipLaunchKernelGGL((wgrad_finish_kernel<DT_, OT_, false, NS_>), grid, dim3(256), 0, st, part, nsplit, rows, cols, dw, \
                          colscale, w_for_dgamma, dgamma_part, accumulate);                                      \
+  } while (0)
+#define LRB_WF(DT_, OT_)                                                                                         \
+  do {                                                                                                           \
+    switch (nsplit) {                                                                                            \
+      case 2: LRB_WF2(DT_, OT_, 2); break;                                                                       \
+      case 3: LRB_WF2(DT_, OT_, 3); break;                                                                       \
+      case 4: LRB_WF2(DT_, OT_, 4); break;                                                                       \
+      case 8: LRB_WF2(DT_, OT_, 8); break;                                                                       \
+      default: LRB_WF2(DT_, OT_, 0); break;                                                                      \
+    }                                                                                                            \
   } while (0)
   if (dt == LR_F32) LRB_WF(LR_F32, float);
   else if (out_dt == LR_F32) LRB_WF(LR_BF16, float);
   else LRB_WF(LR_BF16, bf16_t);
 #undef LRB_WF
+#undef LRB_WF2
   return hipGetLastError();
 }
 hipError_t k_colsum_parts(const float* part, int64_t nparts, int64_t cols, void* out, int accumulate, int out_dt,
