@@ -37,7 +37,9 @@ struct Tile {
   static constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
   static constexpr int WLOADS = (BM + BN) / 8 / NW;   // 1 KB wavefront loads (8 rows x 128 B) per wavefront per stage
   static constexpr int WLOADS_A = BM / 8 / NW;        // the first WLOADS_A of them fetch A rows, the rest B rows
-  static constexpr int CS = TN + 8;  // fp32 row stride of the epilogue staging tile
+  // fp32 row stride of the epilogue staging tile: = 4 (mod 64), so the 16 rows that one cycle of a
+  // 16-byte-per-lane write touches fall on 16 different groups of four banks
+  static constexpr int CS = TN + 4;
   static constexpr int EPI_BYTES = NW * 32 * CS * 4;
   static constexpr int STAT_BYTES = BM * 4;
   static constexpr int MAIN_BYTES = NSA * A_BYTES + NSB * B_BYTES;
@@ -277,7 +279,7 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
     for (int i = 0; i < T::FM; i++)
 #pragma unroll
       for (int j = 0; j < T::FN; j++)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i], bf[buf][j], acc[i][j], 0, 0, 0);
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[buf][j], af[buf][i], acc[i][j], 0, 0, 0);
   };
   float ssq = 0.f;   // STAT_A: thread t accumulates the sum of squares of tile row t from the LDS copy
   auto stat_row = [&](int kt, int half) {
@@ -472,11 +474,13 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
     if constexpr (p == 0) {
       static_for<T::FN>([&](auto J) {
         constexpr int j = decltype(J)::value;
+        // the accumulators hold the transposed 32x32 block (the MFMA is issued with its operands
+        // exchanged): lane -> row lane%32, registers 4g..4g+3 -> columns 8g + 4*(lane/32) + 0..3, so a lane
+        // stages four consecutive columns with one 16-byte write
 #pragma unroll
-        for (int v = 0; v < 16; v++) {
-          int rl = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-          sC[rl * T::CS + j * 32 + (lane & 31)] = acc[i][j][v];
-        }
+        for (int g = 0; g < 4; g++)
+          *reinterpret_cast<float4*>(sC + (lane & 31) * T::CS + j * 32 + 8 * g + 4 * (lane >> 5)) =
+              make_float4(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]);
       });
       // No barrier: the staging region belongs to this wavefront alone and a wavefront's LDS
       // operations complete in order.
