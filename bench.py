@@ -53,8 +53,9 @@ def block_flops(B, S, d, H, f, r):
     model = 3.0 * lin_fwd + 3.5 * attn_fwd                       # bwd: 2x linear, 2.5x attention
     recompute_lin = 2.0 * T * r * (4 * d + 2 * f)                # six of the seven up-projections
     gemm_exec = 3.0 * lin_fwd + recompute_lin
-    # attention as executed here: fwd, re-fwd, and a two-kernel backward (3 + 4 GEMM units of the 2 in fwd)
-    attn_exec = attn_fwd * (1.0 + 1.0 + 3.5)
+    # attention as executed here: fwd, re-fwd, and a backward of 5 GEMM units against the 2 of the forward
+    # (S, dP, dV, dK in one kernel that also leaves dS; dQ as one GEMM over it)
+    attn_exec = attn_fwd * (1.0 + 1.0 + 2.5)
     return {"model": model, "gemm_exec": gemm_exec, "attn_exec": attn_exec, "exec": gemm_exec + attn_exec,
             "lin_fwd": lin_fwd, "attn_fwd": attn_fwd}
 

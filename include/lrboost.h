@@ -155,7 +155,10 @@ int lr_block_bwd(const lr_block_desc* desc, const lr_block_params* params, const
 /* q, k, v, o: [B*S, H*hd] token-major, head h in columns h*hd..; lse[B, H, S] fp32.
  * bf16 only, hd = 128, and S * ld * 2 < 2^31 bytes (the kernels address one batch element with
  * 32-bit buffer offsets); otherwise LR_EUNSUPPORTED.  The backward workspace holds two [B, H, S]
- * fp32 arrays (sum_h dO*O and lse * log2(e)).                                               */
+ * fp32 arrays (sum_h dO*O and lse * log2(e)) and, when S is a multiple of 8 and it stays under
+ * 24 GiB, the score gradient scale * dS^T as bf16 [B, H, S, S] (4.3 GB at B 4, H 32, S 4096):
+ * the key / value gradient kernel writes it and the query gradient is one GEMM over it, which
+ * saves recomputing the scores a second time.  Other shapes take the recomputing form.        */
 int lr_attention_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
                      int64_t ld, int64_t B, int64_t S, int64_t H, int64_t hd, int causal,
                      int dt, void* stream);

@@ -149,6 +149,12 @@ __device__ __forceinline__ void dma_tile(rsrc_t rs, unsigned char* tile, const u
 }
 // s_waitcnt vmcnt(0) alone (gfx9 encoding), and lgkmcnt(0) alone
 __device__ __forceinline__ void wait_vm0() { __builtin_amdgcn_s_waitcnt(0x0f70); }
+// s_waitcnt vmcnt(N) alone, N < 64: bits 3:0 and 15:14 hold vmcnt, the other counters stay at "no wait"
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14));
+}
 
 // A operand (32 rows = tile rows r0 + lane%32, k slots = logical chunk ks*2 + lane/32) from a
 // SWZ_ROW16 tile.  r0 is a multiple of 16, so the swizzle term depends on the lane only.
@@ -556,13 +562,18 @@ constexpr int DKV_LDS = 2 * DKV_STAGE;
 // NB 32-key blocks per wavefront: every Q / dO operand read from LDS feeds NB MFMAs.  With NB = 1 the
 // four wavefronts together need 128 bytes of LDS operands per clock to keep the matrix pipes busy,
 // which is all the LDS delivers; NB = 2 halves that (the accumulators then fill the AGPR file).
-template <int NB>
+// WRITE_DS: the kernel also leaves scale * dS^T, as bf16 [key][query] per (batch, head), in `dst`; the
+// query gradient is then one k-major GEMM dQ = (scale dS^T)^T K over it, instead of a second kernel
+// that forms S, dP and dS all over again.  Everything a row tile of that GEMM reads is written here:
+// key k's row holds every query from 256 * floor(k / 256) on, zeros where the query precedes the key.
+template <int NB, bool WRITE_DS>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                                                            const uint16_t* __restrict__ v,
                                                            const uint16_t* __restrict__ dout,
                                                            const float* __restrict__ lse2, const float* __restrict__ D,
                                                            uint16_t* __restrict__ dk, uint16_t* __restrict__ dv,
-                                                           int64_t ld, int S, int H, float scale) {
+                                                           uint16_t* __restrict__ dst, int64_t ld, int S, int H,
+                                                           float scale) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int BN = 4 * NB * 32;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -595,11 +606,36 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const uint16_t* __res
 
   // one key block from the early end (most queries) and its mirror image from the late end: equal
   // work per workgroup
+  // dS^T of this (batch, head): S rows of S bf16.  A packed k16 fragment holds, for the lane's key row,
+  // queries 4h..4h+3 and 8+4h..8+4h+3 (h = lane / 32); lanes l and l + 32 exchange one half each, after
+  // which a lane owns 8 consecutive queries and stores them with one 16-byte access.  Rows past S fall
+  // outside the resource, queries past S (a multiple of 8) are given an offset that does.
+  const __amdgpu_buffer_rsrc_t rsS = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)(WRITE_DS ? dst + ((int64_t)b * H + head) * S * S : nullptr), 0, WRITE_DS ? (uint32_t)S * (uint32_t)S * 2u : 0u,
+      0x00020000);
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  auto store_ds = [&](const bf16x8& f, int key, int q16) {
+    const uint4 w = __builtin_bit_cast(uint4, f);
+    // swap(a, b): lanes 32..63 of a <-> lanes 0..31 of b
+    const auto sx = __builtin_amdgcn_permlane32_swap(w.x, w.z, false, false);
+    const auto sy = __builtin_amdgcn_permlane32_swap(w.y, w.w, false, false);
+    const int q0 = q16 + 8 * (lane >> 5);
+    const uint32_t o = q0 < S ? (uint32_t)key * (uint32_t)S * 2u + (uint32_t)q0 * 2u : DMA_OOB;
+    __builtin_amdgcn_raw_buffer_store_b128(u32x4{sx[0], sy[0], sx[1], sy[1]}, rsS, (int)o, 0, 0);
+  };
+  const bf16x8 zero_frag = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
+
   for (int pass = 0; pass < 2; pass++) {
   const int kblk = pass == 0 ? wg.x : nkb - 1 - wg.x;
   if (pass == 1 && kblk <= wg.x) break;
   const int n0 = kblk * BN;
   const int nw0 = n0 + wave * NB * 32;
+  if constexpr (WRITE_DS) {
+    // queries between the start of the enclosing 256-row tile and this key block: zeros
+    for (int qz = (n0 / 256) * 256; qz < n0; qz += 16)
+#pragma unroll
+      for (int nb = 0; nb < NB; nb++) store_ds(zero_frag, nw0 + nb * 32 + (lane & 31), qz);
+  }
 
   // K and V rows of this wavefront stay in registers (B operands).
   bf16x8 kf[NB][8], vf[NB][8];
@@ -635,7 +671,15 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const uint16_t* __res
 #pragma unroll 1
     for (int qb2 = 0; qb2 < 2; qb2++) {
       const int qb0 = qt0 + qb2 * 32;
-      if (qb0 + 31 < nw0 || qb0 >= S) continue;
+      if (qb0 + 31 < nw0 || qb0 >= S) {
+        if constexpr (WRITE_DS) {   // not computed, but a row tile of the dQ GEMM reads it: zeros
+#pragma unroll
+          for (int t = 0; t < 2; t++)
+#pragma unroll
+            for (int nb = 0; nb < NB; nb++) store_ds(zero_frag, nw0 + nb * 32 + (lane & 31), qb0 + t * 16);
+        }
+        continue;
+      }
       f32x16 st[NB], dp[NB];                               // rows = queries, column = key
 #pragma unroll
       for (int nb = 0; nb < NB; nb++)
@@ -670,7 +714,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const uint16_t* __res
             p = (ni > qi || qi >= S) ? 0.f : p;
           }
           st[nb][e] = p;                                   // P
-          dp[nb][e] = p * (dp[nb][e] - dvv);               // dS
+          if constexpr (WRITE_DS) dp[nb][e] = (p * scale) * (dp[nb][e] - dvv);   // scale * dS
+          else dp[nb][e] = p * (dp[nb][e] - dvv);          // dS
         }
       }
 #pragma unroll
@@ -678,6 +723,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const uint16_t* __res
         bf16x8 pf[NB], dsf[NB];
 #pragma unroll
         for (int nb = 0; nb < NB; nb++) { pf[nb] = pack_acc_half(st[nb], t); dsf[nb] = pack_acc_half(dp[nb], t); }
+        if constexpr (WRITE_DS) {
+#pragma unroll
+          for (int nb = 0; nb < NB; nb++) store_ds(dsf[nb], nw0 + nb * 32 + (lane & 31), qb0 + t * 16);
+        }
 #pragma unroll
         for (int hb = 0; hb < 4; hb++) {
           const bf16x8 dtf = both_tr_frag(sO, qb2 * 32 + t * 16, hb * 32, lane);
@@ -690,14 +739,18 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const uint16_t* __res
         }
       }
     }
-    wait_vm0();
+    // The next tile's loads were issued before this tile's dS^T stores (4 * NB per wavefront, issued on
+    // every path) and memory operations retire in order: waiting until at most that many are
+    // outstanding covers the loads without waiting for the stores to be acknowledged.
+    if constexpr (WRITE_DS) wait_vm<4 * NB>();
+    else wait_vm0();
     __syncthreads();
   }
 #pragma unroll
   for (int nb = 0; nb < NB; nb++) {
     const int ni = nw0 + nb * 32 + (lane & 31);
     if (ni < S) {
-      store_acc_T(dk + (tok0 + ni) * ld + hoff, akv[0][nb], scale, lane);
+      store_acc_T(dk + (tok0 + ni) * ld + hoff, akv[0][nb], WRITE_DS ? 1.f : scale, lane);
       store_acc_T(dv + (tok0 + ni) * ld + hoff, akv[1][nb], 1.f, lane);
     }
   }
@@ -730,8 +783,19 @@ hipError_t attention_fwd_bf16(const void* q, const void* k, const void* v, void*
   return hipGetLastError();
 }
 
-// D and the base-2 exponent offsets lse * log2(e), both [B, H, S] fp32
-size_t attention_bwd_ws_bytes(int B, int S, int H, int hd) { return 2 * (size_t)B * H * S * sizeof(float); }
+// The backward runs in one of two forms.  With the score gradient kept (S a multiple of 8, and
+// B * H * S^2 bf16 values within the cap below): the dK / dV kernel also writes scale * dS^T and dQ is
+// one k-major GEMM over it, 5 GEMM units in all.  Otherwise: a second kernel recomputes S, dP and dS for
+// dQ, 7 units and no large workspace.
+constexpr size_t DS_WS_CAP = (size_t)24 << 30;
+static bool keep_ds(int B, int S, int H) {
+  return S % 8 == 0 && (int64_t)S * S * 2 < (int64_t)0x7fffffff && (size_t)B * H * S * S * 2 <= DS_WS_CAP;
+}
+// D and the base-2 exponent offsets lse * log2(e), both [B, H, S] fp32; then dS^T [B, H, S, S] bf16
+size_t attention_bwd_ws_bytes(int B, int S, int H, int hd) {
+  const size_t small = (2 * (size_t)B * H * S * sizeof(float) + 255) / 256 * 256;
+  return small + (keep_ds(B, S, H) ? (size_t)B * H * S * S * 2 : 0);
+}
 
 constexpr int DQ_MB = 2;    // 32-query blocks per wavefront in the dQ kernel
 constexpr int DKV_NB = 1;   // 32-key blocks per wavefront in the dK/dV kernel
@@ -745,7 +809,9 @@ hipError_t attention_bwd_bf16(const void* q, const void* k, const void* v, const
   if (!once) {
     hipError_t e = set_lds(attn_bwd_dq_kernel<DQ_MB>, DQ_LDS);
     if (e != hipSuccess) return e;
-    e = set_lds(attn_bwd_dkv_kernel<DKV_NB>, DKV_LDS);
+    e = set_lds(attn_bwd_dkv_kernel<DKV_NB, false>, DKV_LDS);
+    if (e != hipSuccess) return e;
+    e = set_lds(attn_bwd_dkv_kernel<DKV_NB, true>, DKV_LDS);
     if (e != hipSuccess) return e;
     once = true;
   }
@@ -755,12 +821,30 @@ hipError_t attention_bwd_bf16(const void* q, const void* k, const void* v, const
   hipLaunchKernelGGL(attn_dot_kernel, dim3((unsigned)((items * 16 + 255) / 256)), dim3(256), 0, st,
                      (const uint16_t*)dout, (const uint16_t*)o, lse, D, lse2, ld, S, H, items);
   const float scale = 1.f / sqrtf((float)hd);
+  const dim3 kv_grid(((S + DKV_NB * 128 - 1) / (DKV_NB * 128) + 1) / 2, H, B);
+  if (keep_ds(B, S, H)) {
+    uint16_t* dst = (uint16_t*)((char*)ws + (2 * (size_t)items * sizeof(float) + 255) / 256 * 256);
+    hipLaunchKernelGGL((attn_bwd_dkv_kernel<DKV_NB, true>), kv_grid, dim3(256), DKV_LDS, st, (const uint16_t*)q,
+                       (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)dout, lse2, D, (uint16_t*)dk,
+                       (uint16_t*)dv, dst, ld, S, H, scale);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    // dQ[q, :] = sum_key (scale dS^T)[key, q] * K[key, :], per (batch, head): both operands k-major, the
+    // key range of a row tile cut at its last query
+    GemmOp op;
+    op.A = dst; op.lda = S; op.transA = 1; op.sA = (int64_t)S * S; op.sAo = (int64_t)H * S * S;
+    op.B = k; op.ldb = ld; op.transB = 1; op.sB = HD; op.sBo = (int64_t)S * ld;
+    op.C = dq; op.ldc = ld; op.sC = HD; op.sCo = (int64_t)S * ld;
+    op.M = S; op.N = HD; op.K = S; op.batch = B * H; op.batch_inner = H; op.causal_k = 1;
+    op.epi.kind = EPI_STORE;
+    return gemm_bf16_untimed(op, st);
+  }
   hipLaunchKernelGGL(attn_bwd_dq_kernel<DQ_MB>, dim3(((S + DQ_MB * 128 - 1) / (DQ_MB * 128) + 1) / 2, H, B), dim3(256), DQ_LDS, st, (const uint16_t*)q,
                      (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)dout, lse2, D, (uint16_t*)dq, ld, S, H,
                      scale);
-  hipLaunchKernelGGL(attn_bwd_dkv_kernel<DKV_NB>, dim3(((S + DKV_NB * 128 - 1) / (DKV_NB * 128) + 1) / 2, H, B), dim3(256), DKV_LDS, st, (const uint16_t*)q,
+  hipLaunchKernelGGL((attn_bwd_dkv_kernel<DKV_NB, false>), kv_grid, dim3(256), DKV_LDS, st, (const uint16_t*)q,
                      (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)dout, lse2, D, (uint16_t*)dk,
-                     (uint16_t*)dv, ld, S, H, scale);
+                     (uint16_t*)dv, (uint16_t*)nullptr, ld, S, H, scale);
   return hipGetLastError();
 }
 

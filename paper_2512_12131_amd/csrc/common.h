@@ -52,6 +52,13 @@ struct GemmOp {
   int transA = 0, transB = 0;  // 0: operand(i,k) at p[i*ld + k]; 1: at p[k*ld + i]
   int M = 0, N = 0, K = 0, batch = 1;
   int splitk = 1;              // > 1: EPI_PARTIAL into fp32 C[batch][split][M][N] (ldc = N)
+  // Two-level batches (bf16 kernel, A, B and C only): batch index = outer * batch_inner + inner, the
+  // operand of that entry starts at outer * s?o + inner * s?.  batch_inner = 0: one level.
+  int batch_inner = 0;
+  int64_t sAo = 0, sBo = 0, sCo = 0;
+  // k-major bf16 form only: the rows m0.. of a row tile use k < m0 + (tile height) only, i.e. A is
+  // known to be zero where k > m (the causal structure of an attention gradient)
+  int causal_k = 0;
   Epilogue epi;
 };
 
@@ -60,6 +67,8 @@ int gemm_bf16_rowpart_slabs(int N);
 // Chooses a split-K factor for a weight-gradient GEMM with K = T.
 int gemm_bf16_pick_splitk(int M, int N, int K, int batch);
 hipError_t gemm_bf16(const GemmOp& op, hipStream_t st);
+// the same launch, never counted by the benchmark timer below (launches that are not projection GEMMs)
+hipError_t gemm_bf16_untimed(const GemmOp& op, hipStream_t st);
 // true when gemm_bf16 can run `op` with both operands k-major (no transposed copies needed)
 bool gemm_bf16_kmajor_ok(const GemmOp& op);
 hipError_t gemm_f32(const GemmOp& op, hipStream_t st);

@@ -106,8 +106,8 @@ __device__ __forceinline__ void tile_of_block(int bid, int total, int tiles_m, i
 //             with the LDS transpose read, so no transposed copy of an activation is ever written.
 template <class T, int KIND, bool STAT_A, bool KM>
 __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, int tiles_m, int tiles_n) {
-  static_assert(!KM || (KIND == EPI_PARTIAL && !STAT_A && T::BM == 256 && T::BN % 128 == 0),
-                "the k-major form only serves split-K weight gradients");
+  static_assert(!KM || ((KIND == EPI_PARTIAL || KIND == EPI_STORE) && !STAT_A && T::BM == 256 && T::BN % 128 == 0),
+                "the k-major form serves split-K weight gradients and plain stores");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   float* sStat = reinterpret_cast<float*>(smem + T::STAT_OFF);
 
@@ -117,11 +117,15 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
   tile_of_block(blockIdx.x + gridDim.x * blockIdx.y, gridDim.x * gridDim.y, tiles_m, tiles_n, tm, tn, bz);
   const int m0 = tm * T::BM, n0 = tn * T::BN;
   const int b = bz / op.splitk, ks = bz % op.splitk;
-  const int kbeg = ks * kper, kend = min(op.K, kbeg + kper);
+  const int kbeg = ks * kper;
+  int kend = min(op.K, kbeg + kper);
+  if (KM && op.causal_k) kend = min(kend, m0 + T::BM);
+  // element offsets of this batch entry's operands
+  const int bo = op.batch_inner > 0 ? b / op.batch_inner : 0, bi = op.batch_inner > 0 ? b % op.batch_inner : b;
   const int nk = kend > kbeg ? (kend - kbeg + BK - 1) / BK : 0;
 
-  const uint16_t* A = (const uint16_t*)op.A + (int64_t)b * op.sA;
-  const uint16_t* B = (const uint16_t*)op.B + (int64_t)b * op.sB;
+  const uint16_t* A = (const uint16_t*)op.A + (int64_t)bi * op.sA + (int64_t)bo * op.sAo;
+  const uint16_t* B = (const uint16_t*)op.B + (int64_t)bi * op.sB + (int64_t)bo * op.sBo;
 
   // ---- global -> LDS, without passing through registers ---------------------------------------
   // One buffer_load_dwordx4 ... lds per wavefront moves 8 tile rows x 128 bytes (1 KB, eight whole
@@ -403,8 +407,8 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
   const int rows_valid = min(T::BM, op.M - m0);
   const int coln = n0 + wn * T::TN + cg * 8;                         // first of this lane's 8 columns
   const bool col_ok = coln < op.N;
-  auto tile_rsrc = [&](const void* base, int64_t batch_stride, int64_t ld, int esz) {
-    const char* p = base ? (const char*)base + ((int64_t)b * batch_stride + (int64_t)m0 * ld) * esz : nullptr;
+  auto tile_rsrc = [&](const void* base, int64_t batch_off, int64_t ld, int esz) {
+    const char* p = base ? (const char*)base + (batch_off + (int64_t)m0 * ld) * esz : nullptr;
     return __builtin_amdgcn_make_buffer_rsrc((void*)p, 0, base ? (uint32_t)rows_valid * (uint32_t)ld * (uint32_t)esz : 0u,
                                              0x00020000);
   };
@@ -417,11 +421,11 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
   const __amdgpu_buffer_rsrc_t rsC = PARTIAL
       ? __builtin_amdgcn_make_buffer_rsrc((void*)((char*)op.C + ((int64_t)bz * op.M + m0) * op.N * 4), 0,
                                           (uint32_t)rows_valid * (uint32_t)op.N * 4u, 0x00020000)
-      : tile_rsrc(op.C, op.sC, op.ldc, 2);
-  const __amdgpu_buffer_rsrc_t rsC2 = tile_rsrc(PARTIAL ? nullptr : e.C2, e.sC2, e.ldc2, 2);
+      : tile_rsrc(op.C, (int64_t)bi * op.sC + (int64_t)bo * op.sCo, op.ldc, 2);
+  const __amdgpu_buffer_rsrc_t rsC2 = tile_rsrc(PARTIAL ? nullptr : e.C2, (int64_t)b * e.sC2, e.ldc2, 2);
   const bool use_r = !PARTIAL && epi_reads_r<KIND>(e), use_r2 = !PARTIAL && epi_reads_r2<KIND>(e);
-  const __amdgpu_buffer_rsrc_t rsR = tile_rsrc(use_r ? e.R : nullptr, e.sR, e.ldr, 2);
-  const __amdgpu_buffer_rsrc_t rsR2 = tile_rsrc(use_r2 ? e.R2 : nullptr, e.sR2, e.ldr2, 2);
+  const __amdgpu_buffer_rsrc_t rsR = tile_rsrc(use_r ? e.R : nullptr, (int64_t)b * e.sR, e.ldr, 2);
+  const __amdgpu_buffer_rsrc_t rsR2 = tile_rsrc(use_r2 ? e.R2 : nullptr, (int64_t)b * e.sR2, e.ldr2, 2);
   const __amdgpu_buffer_rsrc_t rsRowA = row_rsrc((!PARTIAL && e.use_rho && !STAT_A) ? e.rowa : nullptr);
   const __amdgpu_buffer_rsrc_t rsRowB = row_rsrc(!PARTIAL ? e.rowb : nullptr);
   const int ldC = PARTIAL ? op.N * 4 : (int)op.ldc * 2;               // row pitches in bytes
@@ -641,7 +645,6 @@ int gemm_timer_end(double* total_ms, int* launches) {
   return 0;
 }
 
-static hipError_t gemm_bf16_untimed(const GemmOp& op, hipStream_t st);
 
 hipError_t gemm_bf16(const GemmOp& op, hipStream_t st) {
   if (!g_timer.on || g_timer.used + 2 > g_timer.ev.size() || op.M <= 0 || op.N <= 0 || op.batch <= 0)
@@ -655,14 +658,20 @@ hipError_t gemm_bf16(const GemmOp& op, hipStream_t st) {
 
 bool gemm_bf16_kmajor_ok(const GemmOp& op) {
   // both operands k-major, fp32 partial output, offsets within the 2 GB a buffer resource addresses
-  return op.transA && op.transB && op.batch == 1 && op.epi.kind == EPI_PARTIAL && op.M % 8 == 0 && op.N % 8 == 0 &&
+  const bool wgrad = op.batch == 1 && op.epi.kind == EPI_PARTIAL;
+  const bool plain = op.splitk == 1 && op.epi.kind == EPI_STORE;
+  return op.transA && op.transB && (wgrad || plain) && op.M % 8 == 0 && op.N % 8 == 0 &&
          (int64_t)op.K * op.lda * 2 < 0x7fffffffLL && (int64_t)op.K * op.ldb * 2 < 0x7fffffffLL;
 }
 
-static hipError_t gemm_bf16_untimed(const GemmOp& op, hipStream_t st) {
+hipError_t gemm_bf16_untimed(const GemmOp& op, hipStream_t st) {
   if (op.M <= 0 || op.N <= 0 || op.batch <= 0) return hipSuccess;
   if (op.transA && op.transB) {
     if (!gemm_bf16_kmajor_ok(op)) return hipErrorInvalidValue;
+    if (op.epi.kind == EPI_STORE && op.splitk == 1) {
+      if (use_big_tile(op.N)) return launch<TileBig, EPI_STORE, false, true>(op, st);
+      return launch<TileMid, EPI_STORE, false, true>(op, st);
+    }
     if (use_big_tile(op.N)) return launch<TileBig, EPI_PARTIAL, false, true>(op, st);
     return launch<TileMid, EPI_PARTIAL, false, true>(op, st);
   }

@@ -15,7 +15,7 @@ from paper_2512_12131_amd import binding as B
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
-CASES = [(1, 1, 1), (2, 64, 2), (2, 200, 3), (1, 333, 2), (2, 512, 2), (1, 1100, 1)]   # B, S, H (hd = 128)
+CASES = [(1, 1, 1), (2, 64, 2), (2, 200, 3), (1, 333, 2), (2, 512, 2), (1, 1100, 1), (2, 776, 2), (1, 1096, 1)]   # B, S, H (hd = 128)
 
 
 @pytest.mark.parametrize("Bn,S,H", CASES)
