@@ -151,7 +151,10 @@ __device__ __forceinline__ uint4 pack8(const float* v) {
   q.z = pack_bf16x2(v[4], v[5]); q.w = pack_bf16x2(v[6], v[7]);
   return q;
 }
-__device__ __forceinline__ float logistic_f(float z) { return 1.f / (1.f + __expf(-z)); }
+// 1 / (1 + e^-z) with the hardware reciprocal (1 ulp) instead of an IEEE division, which costs ten
+// instructions per element: in the GEMM epilogues that apply sigma or the SwiGLU gate these divisions
+// were 40 % of all instructions.
+__device__ __forceinline__ float logistic_f(float z) { return __builtin_amdgcn_rcpf(1.f + __expf(-z)); }
 __device__ __forceinline__ float silu_f(float z) { return z * logistic_f(z); }
 __device__ __forceinline__ float silu_prime_f(float z) {
   float s = logistic_f(z);

@@ -77,6 +77,23 @@ __device__ __forceinline__ void wait_vmcnt() {
 }
 __device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xc07f); }
 
+// Sum over aligned groups of N = 8 or 16 consecutive lanes, every lane receiving the total, with
+// data-parallel-primitive moves (register file only): neighbours inside a quad, then the mirror image
+// inside 8 lanes, then inside 16.  (A butterfly of __shfl_xor goes through the LDS crossbar: four
+// dependent round trips per row partial.)
+template <int N>
+__device__ __forceinline__ float lane_group_sum(float x) {
+  static_assert(N == 8 || N == 16, "lane group size");
+  auto dpp = [](float v, auto CTRL) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), decltype(CTRL)::value, 0xf, 0xf, false));
+  };
+  x += dpp(x, std::integral_constant<int, 0xB1>{});    // quad_perm [1,0,3,2]
+  x += dpp(x, std::integral_constant<int, 0x4E>{});    // quad_perm [2,3,0,1]
+  x += dpp(x, std::integral_constant<int, 0x141>{});   // row_half_mirror: lane i <-> 7 - i
+  if constexpr (N == 16) x += dpp(x, std::integral_constant<int, 0x140>{});   // row_mirror: lane i <-> 15 - i
+  return x;
+}
+
 // Maps the linear workgroup id to an output tile so that (a) the workgroups that the hardware
 // deals round-robin to one XCD form a contiguous range of tiles, and (b) consecutive tiles of that
 // range form compact panels (PM tiles tall), keeping the A rows and B rows they share in that
@@ -529,8 +546,7 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
       }
       if constexpr (q + PF < NQ) fetch(q + PF, auxr[q % PF], auxr2[q % PF]);
       if constexpr (ROWPART) {
-#pragma unroll
-        for (int o = 1; o < LPR; o <<= 1) part += __shfl_xor(part, o);
+        part = lane_group_sum<LPR>(part);
         __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(part), rsPart, (int)((uint32_t)(lm * ldPart) + colPart), 0, 0);
       }
       if constexpr (STAT_A)
