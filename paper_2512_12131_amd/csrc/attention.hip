@@ -231,6 +231,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const uint16_t* __rest
   static_assert(MB == 1, "one 32-query block per wavefront");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int BQ = 4 * MB * 32;
+  // (here the wavefront index stays a vector value: as a scalar it costs this kernel 13 more spilled registers)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nqb = (S + BQ - 1) / BQ;
   const WgCoord wg = wg_coord();
@@ -433,7 +434,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const uint16_t* __rest
                                                           float scale) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int BQ = 4 * MB * 32;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // the wavefront index as a scalar: everything derived from it (LDS slots, tile rows) is scalar arithmetic
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int nqb = (S + BQ - 1) / BQ;
   const WgCoord wg = wg_coord();
   const int head = wg.head, b = wg.b;
@@ -576,7 +578,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const uint16_t* __res
                                                            float scale) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int BN = 4 * NB * 32;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // the wavefront index as a scalar: everything derived from it (LDS slots, tile rows) is scalar arithmetic
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int nkb = (S + BN - 1) / BN;
   const WgCoord wg = wg_coord();
   const int head = wg.head, b = wg.b;
