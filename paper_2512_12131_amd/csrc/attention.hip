@@ -516,18 +516,26 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const uint16_t* __rest
       }
       // dS^T = P^T * (dP^T - D), masked on the diagonal / tail blocks only
       const bool need_mask = (kb0 + 31 > qw0) || (kb0 + 32 > S);
+      auto elements = [&](auto MASKED) {   // one wavefront-uniform branch around two copies of the loop
 #pragma unroll
-      for (int mb = 0; mb < MB; mb++) {
-        const int qi = qw0 + mb * 32 + (lane & 31);
+        for (int mb = 0; mb < MB; mb++) {
+          const int qi = qw0 + mb * 32 + (lane & 31);
 #pragma unroll
-        for (int e = 0; e < 16; e++) {
-          float p = fast_exp2(fmaf(st[mb][e], c, -lsq[mb]));
-          if (need_mask) {
-            const int key = kb0 + acc_row(e, lane);
-            p = (key > qi || key >= S) ? 0.f : p;
+          for (int e = 0; e < 16; e++) {
+            float p = fast_exp2(fmaf(st[mb][e], c, -lsq[mb]));
+            if constexpr (decltype(MASKED)::value) {
+              const int key = kb0 + acc_row(e, lane);
+              p = (key > qi || key >= S) ? 0.f : p;
+            }
+            st[mb][e] = p * (dp[mb][e] - Dq[mb]);
           }
-          st[mb][e] = p * (dp[mb][e] - Dq[mb]);
         }
+      };
+      if (need_mask) {
+        asm volatile("" ::: "memory");
+        elements(std::true_type{});
+      } else {
+        elements(std::false_type{});
       }
 #pragma unroll
       for (int t = 0; t < 2; t++) {
@@ -704,22 +712,32 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const uint16_t* __res
         sdv[g4] = *reinterpret_cast<const float4*>(sd + qb2 * 32 + 8 * g4 + 4 * (lane >> 5));
       }
       const bool need_mask = (qb0 < nw0 + NB * 32 - 1) || (qb0 + 32 > S);
+      // the element loop exists twice, with and without the mask, under one wavefront-uniform branch
+      // (left to the compiler, the test was repeated per element and split the loop into 16 blocks)
+      auto elements = [&](auto MASKED) {
 #pragma unroll
-      for (int nb = 0; nb < NB; nb++) {
-        const int ni = nw0 + nb * 32 + (lane & 31);
+        for (int nb = 0; nb < NB; nb++) {
+          const int ni = nw0 + nb * 32 + (lane & 31);
 #pragma unroll
-        for (int e = 0; e < 16; e++) {
-          const float lv = e % 4 == 0 ? slv[e / 4].x : e % 4 == 1 ? slv[e / 4].y : e % 4 == 2 ? slv[e / 4].z : slv[e / 4].w;
-          const float dvv = e % 4 == 0 ? sdv[e / 4].x : e % 4 == 1 ? sdv[e / 4].y : e % 4 == 2 ? sdv[e / 4].z : sdv[e / 4].w;
-          float p = fast_exp2(fmaf(st[nb][e], c, -lv));
-          if (need_mask) {
-            const int qi = qb0 + acc_row(e, lane);
-            p = (ni > qi || qi >= S) ? 0.f : p;
+          for (int e = 0; e < 16; e++) {
+            const float lv = e % 4 == 0 ? slv[e / 4].x : e % 4 == 1 ? slv[e / 4].y : e % 4 == 2 ? slv[e / 4].z : slv[e / 4].w;
+            const float dvv = e % 4 == 0 ? sdv[e / 4].x : e % 4 == 1 ? sdv[e / 4].y : e % 4 == 2 ? sdv[e / 4].z : sdv[e / 4].w;
+            float p = fast_exp2(fmaf(st[nb][e], c, -lv));
+            if constexpr (decltype(MASKED)::value) {
+              const int qi = qb0 + acc_row(e, lane);
+              p = (ni > qi || qi >= S) ? 0.f : p;
+            }
+            st[nb][e] = p;                                   // P
+            if constexpr (WRITE_DS) dp[nb][e] = (p * scale) * (dp[nb][e] - dvv);   // scale * dS
+            else dp[nb][e] = p * (dp[nb][e] - dvv);          // dS
           }
-          st[nb][e] = p;                                   // P
-          if constexpr (WRITE_DS) dp[nb][e] = (p * scale) * (dp[nb][e] - dvv);   // scale * dS
-          else dp[nb][e] = p * (dp[nb][e] - dvv);          // dS
         }
+      };
+      if (need_mask) {
+        asm volatile("" ::: "memory");
+        elements(std::true_type{});
+      } else {
+        elements(std::false_type{});
       }
 #pragma unroll
       for (int t = 0; t < 2; t++) {
