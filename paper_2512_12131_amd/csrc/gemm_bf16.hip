@@ -250,7 +250,28 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
   // MFMA operand addressing: row = lane%32 of a 32-row block, logical chunk kk*2 + lane/32
   const int frow = lane & 31, fk = lane >> 5, fsw = (frow >> 1) & 7;
   bf16x8 af[2][T::FM], bf[2][T::FN];
-  auto load_frags = [&](int buf, int kt, int kk) {
+  // k-major form, transpose reads.  Inside each group of 16 lanes, lane s supplies the address of 4
+  // consecutive columns of k-row (s/4) and receives column s of the 4 x 16 block; two reads (k-rows +0 and
+  // +8) give the 8 k slots of a lane: slot (half, e) -> k = kk*16 + (e/4)*8 + half*4 + e%4, the same
+  // assignment for both operands.  The lane-dependent part of every fragment address (k-row inside a
+  // k16 step, swizzled column chunk) does not change over the main loop and is computed once; the slot
+  // of the slice is added per fragment, the k16 step and the +8 rows ride in the instruction's offset.
+  uint32_t troffA[KM ? T::FM : 1], troffB[KM ? T::FN : 1];
+  if constexpr (KM) {
+    const int g = lane >> 4, sl = lane & 15;
+    const int krow0 = (g >> 1) * 4 + (sl >> 2);
+    const int ksw = (krow0 & 7) << 2;                     // (krow0 + 8 n) & 7 is the same
+    const int cin = (g & 1) * 16 + (sl & 3) * 4;          // column inside the 32-column block
+    auto lane_off = [&](int pitch, int col, int swz) {
+      return (uint32_t)(krow0 * pitch + ((((col >> 3) ^ swz) << 4) + (col & 7) * 2));
+    };
+#pragma unroll
+    for (int i = 0; i < T::FM; i++) troffA[i] = lane_off(T::BM * 2, wm * T::TM + i * 32 + cin, ksw);
+#pragma unroll
+    for (int j2 = 0; j2 < T::FN; j2++) troffB[j2] = lane_off(T::BN * 2, wn * T::TN + j2 * 32 + cin, ksw & (T::BN / 8 - 1));
+  }
+  auto load_frags = [&](int buf, int kt, auto KKc) {
+    constexpr int kk = decltype(KKc)::value;
     if constexpr (!KM) {
       const unsigned char* sa = a_slot(kt) + (wm * T::TM + frow) * 128;
       const unsigned char* sb = b_slot(kt) + (wn * T::TN + frow) * 128;
@@ -260,16 +281,6 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
 #pragma unroll
       for (int j = 0; j < T::FN; j++) bf[buf][j] = *reinterpret_cast<const bf16x8*>(sb + j * 32 * 128 + coff);
     } else {
-      // Transpose reads.  Inside each group of 16 lanes, lane s supplies the address of 4 consecutive
-      // columns of k-row (s/4) and receives column s of the 4 x 16 block; two reads (k-rows +0 and +8)
-      // give the 8 k slots of a lane: slot (half, e) -> k = kk*16 + (e/4)*8 + half*4 + e%4, the same
-      // assignment for both operands.
-      const int g = lane >> 4, sl = lane & 15;
-      const int krow = kk * 16 + (g >> 1) * 4 + (sl >> 2);
-      const int ksw = (krow & 7) << 2;                      // (krow + 8) & 7 is the same
-      const int cin = (g & 1) * 16 + (sl & 3) * 4;          // column inside the 32-column block
-      const unsigned char* sa = a_slot(kt) + krow * (T::BM * 2);
-      const unsigned char* sb = b_slot(kt) + krow * (T::BN * 2);
       typedef short s16x4 __attribute__((ext_vector_type(4)));
       typedef short s16x8 __attribute__((ext_vector_type(8)));
       // The transpose reads are issued as inline assembly.  Through the builtin, the compiler cannot
@@ -278,21 +289,21 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
       // two slices of load lead).  The price: the compiler does not wait for their results either, so
       // every k16 step of this form ends with an explicit wait for the LDS counter behind a scheduling
       // barrier (see the main loop).
-      auto tr_pair = [&](const unsigned char* base, int pitch, int col, int swz) -> bf16x8 {
-        const int off = (((col >> 3) ^ swz) << 4) + (col & 7) * 2;
-        const uint32_t a0 = (uint32_t)(uintptr_t)LRB_LDS_PTR(base + off);
-        const uint32_t a1 = (uint32_t)(uintptr_t)LRB_LDS_PTR(base + 8 * pitch + off);
+      const uint32_t slotA = (uint32_t)(uintptr_t)LRB_LDS_PTR(a_slot(kt));
+      const uint32_t slotB = (uint32_t)(uintptr_t)LRB_LDS_PTR(b_slot(kt));
+      auto tr_pair = [&](uint32_t addr, auto PITCH) -> bf16x8 {
+        constexpr int o0 = kk * 16 * decltype(PITCH)::value, o1 = o0 + 8 * decltype(PITCH)::value;
+        static_assert(o1 < 65536, "LDS instruction offset field");
         s16x4 lo, hi;
-        asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo) : "v"(a0) : "memory");
-        asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(hi) : "v"(a1) : "memory");
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(addr), "n"(o0) : "memory");
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(addr), "n"(o1) : "memory");
         s16x8 r = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
         return __builtin_bit_cast(bf16x8, r);
       };
 #pragma unroll
-      for (int i = 0; i < T::FM; i++) af[buf][i] = tr_pair(sa, T::BM * 2, wm * T::TM + i * 32 + cin, ksw);
+      for (int i = 0; i < T::FM; i++) af[buf][i] = tr_pair(slotA + troffA[i], std::integral_constant<int, T::BM * 2>{});
 #pragma unroll
-      for (int j = 0; j < T::FN; j++)
-        bf[buf][j] = tr_pair(sb, T::BN * 2, wn * T::TN + j * 32 + cin, ksw & (T::BN / 8 - 1));
+      for (int j = 0; j < T::FN; j++) bf[buf][j] = tr_pair(slotB + troffB[j], std::integral_constant<int, T::BN * 2>{});
     }
   };
   auto mfma_step = [&](int buf) {
@@ -342,7 +353,7 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
   issue_ab(1, OPB, Half0{});
   wait_vmcnt<T::WLOADS_A + HLB>();   // A(0), B(0) landed; A(1) and half of B(1) may fly
   __builtin_amdgcn_s_barrier();
-  load_frags(0, 0, 0);
+  load_frags(0, 0, std::integral_constant<int, 0>{});
   if constexpr (KM) {
     wait_lgkmcnt0();
     __builtin_amdgcn_sched_barrier(0);
@@ -350,7 +361,7 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
   for (int kt = 0; kt < nk; kt++) {
     static_for<3>([&](auto KK) {
       constexpr int kk = decltype(KK)::value;
-      load_frags((kk + 1) & 1, kt, kk + 1);
+      load_frags((kk + 1) & 1, kt, std::integral_constant<int, kk + 1>{});
       if constexpr (kk == 0) issue_ab(kt + 1, OPB, Half1{});
       if constexpr (kk == 1) issue_ab(kt + 2, OPA, Half0{});
       if constexpr (kk == 2) issue_ab(kt + 2, OPA, Half1{});
@@ -375,7 +386,7 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
     issue_ab(kt + 2, OPB, Half0{});
-    load_frags(0, kt + 1, 0);
+    load_frags(0, kt + 1, std::integral_constant<int, 0>{});
     mfma_step(1);
 #pragma unroll
     for (int i = 0; i < T::FM + T::FN; i++) {
