@@ -231,8 +231,10 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const uint16_t* __rest
   static_assert(MB == 1, "one 32-query block per wavefront");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int BQ = 4 * MB * 32;
-  // (here the wavefront index stays a vector value: as a scalar it costs this kernel 13 more spilled registers)
+  // (here the wavefront index stays a vector value: as a scalar it costs this kernel 13 more spilled
+  // registers; only the LDS destinations of the global->LDS loads use a scalar copy)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
   const int nqb = (S + BQ - 1) / BQ;
   const WgCoord wg = wg_coord();
   const int head = wg.head, b = wg.b;
@@ -271,16 +273,16 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const uint16_t* __rest
   const int kv_end = min(S, q0 + BQ);                    // causal: keys up to the block's last query
   const int ntiles = (kv_end + KT - 1) / KT;
 
-  dma_tile(rsK, sK, offK, rowK, 0, S, ld, wave);
-  dma_tile(rsV, sV, offV, rowV, 0, S, ld, wave);
+  dma_tile(rsK, sK, offK, rowK, 0, S, ld, wave_s);
+  dma_tile(rsV, sV, offV, rowV, 0, S, ld, wave_s);
   wait_vm0();
   __syncthreads();
 
   for (int j = 0; j < ntiles; j++) {
     const int cur = j & 1;
     if (j + 1 < ntiles) {                                // next tiles land while this one is worked on
-      dma_tile(rsK, sK + (cur ^ 1) * TILE_BYTES, offK, rowK, (j + 1) * KT, S, ld, wave);
-      dma_tile(rsV, sV + (cur ^ 1) * TILE_BYTES, offV, rowV, (j + 1) * KT, S, ld, wave);
+      dma_tile(rsK, sK + (cur ^ 1) * TILE_BYTES, offK, rowK, (j + 1) * KT, S, ld, wave_s);
+      dma_tile(rsV, sV + (cur ^ 1) * TILE_BYTES, offV, rowV, (j + 1) * KT, S, ld, wave_s);
     }
     const int key0 = j * KT;
     const unsigned char* sKc = sK + cur * TILE_BYTES;
