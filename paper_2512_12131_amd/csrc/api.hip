@@ -184,8 +184,12 @@ void group_down_seq(Ctx& c, const GrpArgs& a, void* act) {
     dn.epi.use_rho = 1; dn.epi.inv_d = 1.f / (float)a.d_in; dn.epi.eps = a.eps;
     if (a.stat_ready) {
       dn.epi.rowa = a.stat;
-    } else if (c.dt == LR_BF16) {
-      dn.epi.stat_from_a = 1; dn.epi.stat_out = a.stat;   // sum of squares gathered from the A tiles
+    } else if (c.dt == LR_BF16 && GR <= 512) {
+      // sum of squares gathered from the A tiles inside the GEMM.  Every column tile of a row panel
+      // repeats the gather, so this pays only while the output is one or two tiles wide; beyond that a
+      // separate pass over x (Alg. 1 line 1 as its own step) is faster (0.80 against 0.89 ms for the
+      // Q/K/V group of the 7B shape).
+      dn.epi.stat_from_a = 1; dn.epi.stat_out = a.stat;
     } else {
       LAUNCH(c, k_rms_stat(a.x, a.ldx, a.stat, a.T, a.d_in, c.dt, c.st));
       dn.epi.rowa = a.stat;
