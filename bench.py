@@ -35,6 +35,10 @@ WORKLOADS = {
     # sigma = identity: the SVD-style factorisation without the rank-r non-linearity (App. "Low-rank
     # Training Algorithm")
     "block-7B-svd": (4, 4096, 4096, 32, 11008, 1024, "identity"),
+    # the LaX variant (App. "LaX variant (residual low-rank)"): identity gate, every layer adds the rank-r
+    # activation of the layer below before its up-projection; timed as a middle block of a stack (it
+    # receives h_prev and dz_next and returns dh_prev)
+    "block-7B-lax": (4, 4096, 4096, 32, 11008, 1024, "lax"),
 }
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 HBM_PEAK_GBS = 8000.0
@@ -118,7 +122,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     dev = "cuda:0"
     Bn, S, d, H, f, r = WORKLOADS[args.workload][:6]
-    act = B.LR_ACT_IDENTITY if WORKLOADS[args.workload][6:] == ("identity",) else B.LR_ACT_SILU
+    variant = WORKLOADS[args.workload][6] if len(WORKLOADS[args.workload]) > 6 else "silu"
+    act = B.LR_ACT_IDENTITY if variant in ("identity", "lax") else B.LR_ACT_SILU
     f_ld = si.pad_ld(f, 8)
     eps = 1e-5
     case = si.block_case(Bn, S, d, H, 128, f, r, seed=0)
@@ -131,9 +136,20 @@ def main():
     ws = torch.empty(max(B.lr_block_workspace_bytes(desc, 0), B.lr_block_workspace_bytes(desc, 1)),
                      dtype=torch.uint8, device=dev)
 
-    def step():
-        B.lr_block_fwd(desc, params, x, ckpt=ck, ws=ws, y=y)
-        B.lr_block_bwd(desc, params, x, dy, ck, grads=grads, accumulate=False, ws=ws, dx=dx)
+    if variant == "lax":
+        shapes = {"qkv": 3 * r, "o": r, "gu": 2 * r, "d": r}
+        h_prev = {n: si.gaussian(0, "h_prev_" + n, (Bn * S, w), std=0.5, dtype=torch.bfloat16).to(dev)
+                  for n, w in shapes.items()}
+        dz_next = {n: si.gaussian(0, "dz_next_" + n, (Bn * S, w), dtype=torch.bfloat16).to(dev) for n, w in shapes.items()}
+
+        def step():
+            B.lr_block_lax_fwd(desc, params, x, h_prev=h_prev, ckpt=ck, ws=ws, y=y)
+            B.lr_block_lax_bwd(desc, params, x, dy, ck, h_prev=h_prev, dz_next=dz_next, grads=grads,
+                               accumulate=False, ws=ws, dx=dx)
+    else:
+        def step():
+            B.lr_block_fwd(desc, params, x, ckpt=ck, ws=ws, y=y)
+            B.lr_block_bwd(desc, params, x, dy, ck, grads=grads, accumulate=False, ws=ws, dx=dx)
 
     for _ in range(args.warmup):
         step()
@@ -284,7 +300,8 @@ def main():
         "ms_per_step": round(dt * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: low-rank decoder block fwd+bwd, batch {Bn}, seq {S}, d_model {d}, "
-                               f"{H} heads of 128, ffn {f}, rank {r}, sigma {'identity' if act == B.LR_ACT_IDENTITY else 'SiLU'}, "
+                               f"{H} heads of 128, ffn {f}, rank {r}, sigma {'identity' if act == B.LR_ACT_IDENTITY else 'SiLU'}"
+                               f"{' + rank-r residual from the layer below (LaX)' if variant == 'lax' else ''}, "
                                f"rank-r checkpoint recompute",
                    "tokens": T, "executed_tflop": round(fl["exec"] / 1e12, 3),
                    "model_tflop": round(fl["model"] / 1e12, 3),
@@ -304,10 +321,22 @@ def main():
         s_len = S   # all of batch element 0: about 10 s of fp64 work at the 7B shape
         P = {k: si.f64(v) for k, v in case["params"].items()}
         X0, DY0 = si.f64(case["x"][:s_len]), si.f64(case["dy"][:s_len])
+        if variant == "lax":
+            from oracle import lax_oracle as lorc
+            parts = {"qkv": "qkv", "o": "o", "gu": "gu", "d": "d"}
+            hp, dzn = {}, {}
+            for part, names in parts.items():
+                for i, n in enumerate(names):
+                    hp[n] = si.f64(h_prev[part][:s_len, i * r:(i + 1) * r].cpu())
+                    dzn[n] = si.f64(dz_next[part][:s_len, i * r:(i + 1) * r].cpu())
         t0 = time.perf_counter()
-        oact = orc.ACT_IDENTITY if act == B.LR_ACT_IDENTITY else orc.ACT_SILU
-        orc.block_fwd(X0, P, 1, s_len, H, 128, eps, act=oact)
-        orc.block_bwd(X0, P, DY0, 1, s_len, H, 128, eps, act=oact)
+        if variant == "lax":
+            lorc.block_fwd(X0, P, hp, 1, s_len, H, 128, eps)
+            lorc.block_bwd(X0, P, hp, DY0, dzn, 1, s_len, H, 128, eps)
+        else:
+            oact = orc.ACT_IDENTITY if act == B.LR_ACT_IDENTITY else orc.ACT_SILU
+            orc.block_fwd(X0, P, 1, s_len, H, 128, eps, act=oact)
+            orc.block_bwd(X0, P, DY0, 1, s_len, H, 128, eps, act=oact)
         ct = time.perf_counter() - t0
         cfl = block_flops(1, s_len, d, H, f, r)
         cpu_flops = cfl["model"] + cfl["lin_fwd"] + cfl["attn_fwd"]   # block_bwd runs its own forward again

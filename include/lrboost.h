@@ -151,6 +151,30 @@ int lr_block_bwd(const lr_block_desc* desc, const lr_block_params* params, const
                  const lr_block_params* grads, int accumulate, void* ws, size_t ws_bytes,
                  void* stream);
 
+/* ---- the LaX variant of the block (App. "LaX variant (residual low-rank)") ----------------
+ * Identity gate at rank r, and every bottleneck layer adds the rank-r activation h_{i-1} of the
+ * same projection in the decoder layer below before its up-projection: y_i = B_i (h_i + h_{i-1}),
+ * h_i = A_i x_i.  A block's own h_i are its checkpoints z_* (lr_block_ckpt), which the caller
+ * hands to the block above as h_prev_*.  In the backward, dz_next_* is the block above's
+ * gradient w.r.t. this block's z_* (its dh_prev_*), and dh_prev_* receives this block's gradient
+ * w.r.t. its h_prev_*.  Layouts as the checkpoints: qkv [T, 3r], o [T, r], gu [T, 2r], d [T, r],
+ * bf16, dense.  Each pointer may be NULL: an absent h_prev / dz_next counts as zeros (first /
+ * last block of a stack), an absent dh_prev is not written.  desc->act must be
+ * LR_ACT_IDENTITY (else LR_EUNSUPPORTED); everything else as lr_block_fwd / lr_block_bwd,
+ * same workspace sizes.                                                                     */
+typedef struct {
+  const void *h_prev_qkv, *h_prev_o, *h_prev_gu, *h_prev_d;       /* forward and backward inputs  */
+  const void *dz_next_qkv, *dz_next_o, *dz_next_gu, *dz_next_d;   /* backward inputs              */
+  void *dh_prev_qkv, *dh_prev_o, *dh_prev_gu, *dh_prev_d;         /* backward outputs             */
+} lr_block_lax;
+int lr_block_lax_fwd(const lr_block_desc* desc, const lr_block_params* params, const void* x,
+                     void* y, const lr_block_ckpt* ckpt, const lr_block_lax* lax, void* ws,
+                     size_t ws_bytes, void* stream);
+int lr_block_lax_bwd(const lr_block_desc* desc, const lr_block_params* params, const void* x,
+                     const void* dy, const lr_block_ckpt* ckpt, void* dx,
+                     const lr_block_params* grads, int accumulate, const lr_block_lax* lax,
+                     void* ws, size_t ws_bytes, void* stream);
+
 /* ---- causal multi-head attention (the sharded-safe op between the chunks, Sec. 4.2) ---- */
 /* q, k, v, o: [B*S, H*hd] token-major, head h in columns h*hd..; lse[B, H, S] fp32.
  * bf16 only, hd = 128, and S * ld * 2 < 2^31 bytes (the kernels address one batch element with

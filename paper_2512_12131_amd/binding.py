@@ -43,7 +43,12 @@ class BlockCkpt(C.Structure):
     _fields_ = [(n, _vp) for n in ("z_qkv", "z_o", "z_gu", "z_d", "s1", "s2")]
 
 
+class BlockLax(C.Structure):
+    _fields_ = [(k + "_" + n, _vp) for k in ("h_prev", "dz_next", "dh_prev") for n in ("qkv", "o", "gu", "d")]
+
+
 PARAM_NAMES = tuple(n for n, _ in BlockParams._fields_)
+LAX_PARTS = ("qkv", "o", "gu", "d")
 
 _SIGS = {
     "lr_version": (_int, []),
@@ -63,6 +68,10 @@ _SIGS = {
                             _vp]),
     "lr_block_bwd": (_int, [C.POINTER(BlockDesc), C.POINTER(BlockParams), _vp, _vp, C.POINTER(BlockCkpt), _vp,
                             C.POINTER(BlockParams), _int, _vp, _sz, _vp]),
+    "lr_block_lax_fwd": (_int, [C.POINTER(BlockDesc), C.POINTER(BlockParams), _vp, _vp, C.POINTER(BlockCkpt),
+                                C.POINTER(BlockLax), _vp, _sz, _vp]),
+    "lr_block_lax_bwd": (_int, [C.POINTER(BlockDesc), C.POINTER(BlockParams), _vp, _vp, C.POINTER(BlockCkpt), _vp,
+                                C.POINTER(BlockParams), _int, C.POINTER(BlockLax), _vp, _sz, _vp]),
     "lr_attention_fwd": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _int, _int, _vp]),
     "lr_attention_bwd_workspace_bytes": (_sz, [_i64, _i64, _i64, _i64]),
     "lr_attention_bwd": (_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _int, _int,
@@ -275,6 +284,56 @@ def lr_block_bwd(desc, params: dict, x, dy, ckpt: dict, grads: dict = None, accu
     _check(lib().lr_block_bwd(C.byref(desc), C.byref(ps), _p(x), _p(dy), C.byref(cs), _p(dx), C.byref(gs),
                               int(accumulate), _p(ws), ws.numel(), _stream()), "lr_block_bwd")
     return dx, grads
+
+
+# ---- block, LaX variant ----------------------------------------------------------------------
+def _lax_struct(h_prev=None, dz_next=None, dh_prev=None):
+    """Each argument: None or a dict keyed "qkv", "o", "gu", "d" of device tensors (missing keys = NULL)."""
+    vals = []
+    for d in (h_prev, dz_next, dh_prev):
+        for n in LAX_PARTS:
+            t = None if d is None else d.get(n)
+            vals.append(C.c_void_p(None if t is None else t.data_ptr()))
+    return BlockLax(*vals)
+
+
+def lr_block_lax_fwd(desc, params: dict, x, h_prev: dict = None, ckpt: dict = None, ws=None, y=None):
+    """Returns (y, ckpt); ckpt["z_qkv"], ["z_o"], ["z_gu"], ["z_d"] are the h_prev of the block above."""
+    if ckpt is None:
+        ckpt = alloc_block_ckpt(desc, x.device)
+    if y is None:
+        y = torch.empty_like(x)
+    nb = lr_block_workspace_bytes(desc, 0)
+    if nb == 0:
+        raise LrError("lr_block_workspace_bytes: invalid or unsupported block descriptor")
+    if ws is None:
+        ws = _ws(nb, x.device)
+    ps, cs, lx = _params_struct(params), _ckpt_struct(ckpt), _lax_struct(h_prev)
+    _check(lib().lr_block_lax_fwd(C.byref(desc), C.byref(ps), _p(x), _p(y), C.byref(cs), C.byref(lx), _p(ws),
+                                  ws.numel(), _stream()), "lr_block_lax_fwd")
+    return y, ckpt
+
+
+def lr_block_lax_bwd(desc, params: dict, x, dy, ckpt: dict, h_prev: dict = None, dz_next: dict = None,
+                     want_dh_prev=True, grads: dict = None, accumulate=False, ws=None, dx=None):
+    """Returns (dx, grads, dh_prev) with dh_prev keyed "qkv", "o", "gu", "d" (None if not wanted)."""
+    if grads is None:
+        grads = {n: torch.empty_like(params[n], dtype=_tdt(desc.grad_dt)) for n in PARAM_NAMES}
+    if dx is None:
+        dx = torch.empty_like(x)
+    dh = None
+    if want_dh_prev:
+        dh = {n: torch.empty_like(ckpt["z_" + n]) for n in LAX_PARTS}
+    nb = lr_block_workspace_bytes(desc, 1)
+    if nb == 0:
+        raise LrError("lr_block_workspace_bytes: invalid or unsupported block descriptor")
+    if ws is None:
+        ws = _ws(nb, x.device)
+    ps, cs, gs = _params_struct(params), _ckpt_struct(ckpt), _params_struct(grads)
+    lx = _lax_struct(h_prev, dz_next, dh)
+    _check(lib().lr_block_lax_bwd(C.byref(desc), C.byref(ps), _p(x), _p(dy), C.byref(cs), _p(dx), C.byref(gs),
+                                  int(accumulate), C.byref(lx), _p(ws), ws.numel(), _stream()), "lr_block_lax_bwd")
+    return dx, grads, dh
 
 
 # ---- attention -----------------------------------------------------------------------------

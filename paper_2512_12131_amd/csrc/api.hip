@@ -163,6 +163,12 @@ struct GrpArgs {
   const void* dres;          // optional residual gradient added into dx (block use)
   int64_t lddres;
   void* act_out;             // optional: where sigma(z_cat) goes (else workspace)
+  // LaX variant (identity gate): h_prev [T, G*r] is added to z_cat before the up-projections; in the
+  // backward dz_next [T, G*r] is the layer above's gradient w.r.t. z_cat and dh_prev [T, G*r] receives
+  // the gradient w.r.t. h_prev.  `lax` selects the variant; each pointer may still be null (= zeros / unused).
+  int lax;
+  const void *h_prev, *dz_next;
+  void* dh_prev;
   int stat_ready;            // stat[] already holds sum_j x^2 (gathered by the GEMM that produced x)
   int64_t ldx, ldy, y_bs, lddy, dy_bs, lddx, T, d_in, r, d_out;
   int G, act, norm, accumulate;
@@ -177,6 +183,7 @@ void group_down_seq(Ctx& c, const GrpArgs& a, void* act) {
   dn.A = a.x; dn.lda = a.ldx; dn.B = a.w_down_cat; dn.ldb = a.d_in; dn.C = a.z_cat; dn.ldc = GR;
   dn.M = (int)a.T; dn.N = (int)GR; dn.K = (int)a.d_in;
   dn.epi.kind = EPI_DOWN; dn.epi.act = a.act; dn.epi.C2 = act; dn.epi.ldc2 = GR;
+  if (a.lax) { dn.epi.kind = EPI_DOWN_LAX; dn.epi.R = a.h_prev; dn.epi.ldr = GR; }
   if (a.norm == LR_NORM_ONLINE) {
     void* wg = c.take((size_t)GR * a.d_in * es);   // w_down_cat with gamma folded into its columns
     LAUNCH(c, k_scale_cols(a.w_down_cat, a.gamma, wg, GR, a.d_in, c.dt, c.st));
@@ -242,6 +249,11 @@ void group_bwd_seq(Ctx& c, const GrpArgs& a, const void* act) {
   da.C = dp; da.ldc = GR; da.sC = a.r;
   da.M = (int)a.T; da.N = (int)a.r; da.K = (int)a.d_out; da.batch = a.G;
   da.epi.kind = EPI_ACTGRAD; da.epi.act = a.act; da.epi.R = a.zc; da.epi.ldr = GR; da.epi.sR = a.r;
+  if (a.lax) {
+    da.epi.kind = EPI_LAXGRAD;
+    da.epi.R2 = a.dz_next; da.epi.ldr2 = GR; da.epi.sR2 = a.r;
+    da.epi.C2 = a.dh_prev; da.epi.ldc2 = GR; da.epi.sC2 = a.r;
+  }
   if (normed) {
     da.epi.use_rho = 1; da.epi.rowa = a.statc; da.epi.inv_d = 1.f / (float)a.d_in; da.epi.eps = a.eps;
   }
@@ -363,11 +375,14 @@ bool block_desc_ok(const lr_block_desc* ds, Blk& b, int* why) {
 }
 
 // z = in . w_dn^T (no norm), act = sigma(z)
-void single_down(Ctx& c, const Blk& b, const void* in, int64_t K, const void* w_dn, void* z, void* act) {
+// (LaX: act = z + h_prev, identity gate)
+void single_down(Ctx& c, const Blk& b, const void* in, int64_t K, const void* w_dn, void* z, void* act, int lax = 0,
+                 const void* h_prev = nullptr) {
   GemmOp dn;
   dn.A = in; dn.lda = K; dn.B = w_dn; dn.ldb = K; dn.C = z; dn.ldc = b.r;
   dn.M = (int)b.T; dn.N = (int)b.r; dn.K = (int)K;
   dn.epi.kind = EPI_DOWN; dn.epi.act = b.act; dn.epi.C2 = act; dn.epi.ldc2 = b.r;
+  if (lax) { dn.epi.kind = EPI_DOWN_LAX; dn.epi.R = h_prev; dn.epi.ldr = b.r; }
   gemm(c, dn);
 }
 
@@ -392,13 +407,19 @@ void single_up(Ctx& c, const Blk& b, const void* act, const void* w_up, int64_t 
 }
 
 // Backward through an un-grouped up-projection: dw_up (+)= dout^T . act ; dz = (dout . w_up) * sigma'(z)
+// (LaX: dz = dout . w_up + dz_next, and dh_prev = dout . w_up)
 void single_up_bwd(Ctx& c, const Blk& b, const void* dout, int64_t N, const void* act, const void* z, const void* w_up,
-                   void* dw_up, void* dz, int accumulate) {
+                   void* dw_up, void* dz, int accumulate, int lax = 0, const void* dz_next = nullptr,
+                   void* dh_prev = nullptr) {
   wgrad(c, dout, N, (int)N, act, b.r, (int)b.r, b.T, dw_up, nullptr, nullptr, nullptr, accumulate);
   GemmOp da;
   da.A = dout; da.lda = N; da.B = w_up; da.ldb = b.r; da.transB = 1; da.C = dz; da.ldc = b.r;
   da.M = (int)b.T; da.N = (int)b.r; da.K = (int)N;
   da.epi.kind = EPI_ACTGRAD; da.epi.act = b.act; da.epi.R = z; da.epi.ldr = b.r;
+  if (lax) {
+    da.epi.kind = EPI_LAXGRAD; da.epi.R = nullptr;   // no row statistic wanted here
+    da.epi.R2 = dz_next; da.epi.ldr2 = b.r; da.epi.C2 = dh_prev; da.epi.ldc2 = b.r;
+  }
   gemm(c, da);
 }
 
@@ -428,7 +449,15 @@ GrpArgs group_args(const Blk& b, int G, int64_t d_out) {
   return g;
 }
 
-void block_fwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x, void* y, const lr_block_ckpt* ck) {
+// rank-r activation of a layer for the backward: sigma(z), or z + h_prev in the LaX variant
+void rebuild_act(Ctx& c, const Blk& b, const void* z, const void* h_prev, void* act, int64_t n, int lax) {
+  if (lax && h_prev) LAUNCH(c, k_add2_bf16(z, h_prev, act, b.T, n, c.st));
+  else LAUNCH(c, k_act_fwd(z, n, act, n, b.T, n, lax ? (int)LR_ACT_IDENTITY : b.act, LR_BF16, c.st));
+}
+
+void block_fwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x, void* y, const lr_block_ckpt* ck,
+                   const lr_block_lax* lx = nullptr) {
+  const int lax = lx != nullptr;
   const size_t es = 2;
   const int64_t T = b.T, d = b.d, r = b.r, f = b.f;
   void* qkv = c.take((size_t)3 * T * d * es);
@@ -442,23 +471,29 @@ void block_fwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x
   GrpArgs a = group_args(b, 3, d);
   a.x = x; a.gamma = p->gamma1; a.w_down_cat = p->w_dn_qkv; a.w_up_stack = p->w_up_qkv;
   a.z_cat = ck ? ck->z_qkv : nullptr; a.stat = ck ? ck->s1 : nullptr; a.y_stack = qkv; a.act_out = act;
+  a.lax = lax; a.h_prev = lax ? lx->h_prev_qkv : nullptr;
   group_fwd_seq(c, a);
   LAUNCH(c, attention_fwd_bf16(qkv, (char*)qkv + (size_t)T * d * es, (char*)qkv + (size_t)2 * T * d * es, o, lse, d,
                                (int)b.B, (int)b.S, (int)b.H, (int)b.hd, b.causal, c.st));
-  single_down(c, b, o, d, p->w_dn_o, ck ? ck->z_o : nullptr, act);
+  single_down(c, b, o, d, p->w_dn_o, ck ? ck->z_o : nullptr, act, lax, lax ? lx->h_prev_o : nullptr);
   single_up(c, b, act, p->w_up_o, d, x, h1, ck ? ck->s2 : nullptr);   // h1 = x + ..., s2 = sum h1^2 from the epilogue
   // MLP side
   GrpArgs m = group_args(b, 2, f);
   m.x = h1; m.gamma = p->gamma2; m.w_down_cat = p->w_dn_gu; m.w_up_stack = p->w_up_gu;
   m.z_cat = ck ? ck->z_gu : nullptr; m.stat = ck ? ck->s2 : nullptr; m.stat_ready = 1; m.act_out = act;
+  m.lax = lax; m.h_prev = lax ? lx->h_prev_gu : nullptr;
   group_down_seq(c, m, act);
   mlp_up_swiglu(c, b, p->w_up_gu, act, gg, nullptr, mm);
-  single_down(c, b, mm, f, p->w_dn_d, ck ? ck->z_d : nullptr, act);
+  single_down(c, b, mm, f, p->w_dn_d, ck ? ck->z_d : nullptr, act, lax, lax ? lx->h_prev_d : nullptr);
   single_up(c, b, act, p->w_up_d, d, h1, y, nullptr);
 }
 
 void block_bwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x, const void* dy,
-                   const lr_block_ckpt* ck, void* dx, const lr_block_params* g, int accumulate) {
+                   const lr_block_ckpt* ck, void* dx, const lr_block_params* g, int accumulate,
+                   const lr_block_lax* lx = nullptr) {
+  const int lax = lx != nullptr;
+  const lr_block_lax nlx{};
+  if (!lx) lx = &nlx;
   const size_t es = 2;
   const int64_t T = b.T, d = b.d, r = b.r, f = b.f;
   const lr_block_params np{};  // dry runs have no parameter structs
@@ -492,12 +527,12 @@ void block_bwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x
   }
 
   // ---- MLP side ----
-  LAUNCH(c, k_act_fwd(ck->z_d, r, act_d, r, T, r, b.act, LR_BF16, c.st));
-  single_up_bwd(c, b, dy, d, act_d, ck->z_d, p->w_up_d, g->w_up_d, dz1, accumulate);
+  rebuild_act(c, b, ck->z_d, lx->h_prev_d, act_d, r, lax);
+  single_up_bwd(c, b, dy, d, act_d, ck->z_d, p->w_up_d, g->w_up_d, dz1, accumulate, lax, lx->dz_next_d, lx->dh_prev_d);
   // re-forward from the rank-r checkpoints: h1, then g, u, m
-  LAUNCH(c, k_act_fwd(ck->z_o, r, act_o, r, T, r, b.act, LR_BF16, c.st));
+  rebuild_act(c, b, ck->z_o, lx->h_prev_o, act_o, r, lax);
   single_up(c, b, act_o, p->w_up_o, d, x, h1, nullptr);
-  LAUNCH(c, k_act_fwd(ck->z_gu, 2 * r, act_g, 2 * r, T, 2 * r, b.act, LR_BF16, c.st));
+  rebuild_act(c, b, ck->z_gu, lx->h_prev_gu, act_g, 2 * r, lax);
   GrpArgs m = group_args(b, 2, f);
   m.x = h1; m.gamma = p->gamma2; m.w_down_cat = p->w_dn_gu; m.w_up_stack = p->w_up_gu; m.y_stack = big;
   mlp_up_swiglu(c, b, p->w_up_gu, act_g, big, (char*)big + (size_t)T * f * es, mm);
@@ -514,12 +549,13 @@ void block_bwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x
   // gate/up group backward; dh1 = dy + RMSNorm-2 reverse
   m.zc = ck->z_gu; m.statc = ck->s2; m.dy_stack = big2; m.dx = dh1; m.dres = dy; m.dgamma = g->gamma2;
   m.dw_down_cat = g->w_dn_gu; m.dw_up_stack = g->w_up_gu; m.accumulate = accumulate;
+  m.lax = lax; m.dz_next = lx->dz_next_gu; m.dh_prev = lx->dh_prev_gu;
   group_bwd_seq(c, m, act_g);
 
   // ---- attention side ----
-  single_up_bwd(c, b, dh1, d, act_o, ck->z_o, p->w_up_o, g->w_up_o, dz1, accumulate);
+  single_up_bwd(c, b, dh1, d, act_o, ck->z_o, p->w_up_o, g->w_up_o, dz1, accumulate, lax, lx->dz_next_o, lx->dh_prev_o);
   // re-forward q, k, v, o
-  LAUNCH(c, k_act_fwd(ck->z_qkv, 3 * r, act_g, 3 * r, T, 3 * r, b.act, LR_BF16, c.st));
+  rebuild_act(c, b, ck->z_qkv, lx->h_prev_qkv, act_g, 3 * r, lax);
   GrpArgs a = group_args(b, 3, d);
   a.x = x; a.gamma = p->gamma1; a.w_down_cat = p->w_dn_qkv; a.w_up_stack = p->w_up_qkv; a.y_stack = qkv;
   group_up_seq(c, a, act_g);
@@ -544,6 +580,7 @@ void block_bwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x
   }
   a.zc = ck->z_qkv; a.statc = ck->s1; a.dy_stack = dqkv; a.dx = dx; a.dres = dh1; a.dgamma = g->gamma1;
   a.dw_down_cat = g->w_dn_qkv; a.dw_up_stack = g->w_up_qkv; a.accumulate = accumulate;
+  a.lax = lax; a.dz_next = lx->dz_next_qkv; a.dh_prev = lx->dh_prev_qkv;
   group_bwd_seq(c, a, act_g);
 }
 
@@ -745,6 +782,44 @@ int lr_block_bwd(const lr_block_desc* desc, const lr_block_params* params, const
   TRY(check_ws(ws, ws_bytes, lr_block_workspace_bytes(desc, 1)));
   Ctx c; c.base = (char*)ws; c.cap = ws_bytes; c.dt = LR_BF16; c.gdt = b.gdt; c.st = (hipStream_t)stream;
   block_bwd_seq(c, b, params, x, dy, ckpt, dx, grads, accumulate);
+  return c.err == hipErrorNotSupported ? LR_EUNSUPPORTED : status_of(c);
+}
+
+// ---- block, LaX variant -------------------------------------------------------------------------
+static int check_lax(const lr_block_desc* desc, const lr_block_lax* lx) {
+  if (!lx) return LR_EINVAL;
+  if (desc->act != LR_ACT_IDENTITY) return LR_EUNSUPPORTED;
+  for (const void* q : {lx->h_prev_qkv, lx->h_prev_o, lx->h_prev_gu, lx->h_prev_d, lx->dz_next_qkv, lx->dz_next_o,
+                        lx->dz_next_gu, lx->dz_next_d, (const void*)lx->dh_prev_qkv, (const void*)lx->dh_prev_o,
+                        (const void*)lx->dh_prev_gu, (const void*)lx->dh_prev_d})
+    if (q && !aligned16(q)) return LR_EALIGN;   // each is optional
+  return LR_OK;
+}
+
+int lr_block_lax_fwd(const lr_block_desc* desc, const lr_block_params* params, const void* x, void* y,
+                     const lr_block_ckpt* ckpt, const lr_block_lax* lax, void* ws, size_t ws_bytes, void* stream) {
+  Blk b; int why;
+  if (!block_desc_ok(desc, b, &why)) return why;
+  TRY(check_lax(desc, lax));
+  TRY(check_params(params)); TRY(check_ckpt(ckpt));
+  TRY(check_ptrs(LR_BF16, {x, y}));
+  TRY(check_ws(ws, ws_bytes, lr_block_workspace_bytes(desc, 0)));
+  Ctx c; c.base = (char*)ws; c.cap = ws_bytes; c.dt = LR_BF16; c.st = (hipStream_t)stream;
+  block_fwd_seq(c, b, params, x, y, ckpt, lax);
+  return c.err == hipErrorNotSupported ? LR_EUNSUPPORTED : status_of(c);
+}
+
+int lr_block_lax_bwd(const lr_block_desc* desc, const lr_block_params* params, const void* x, const void* dy,
+                     const lr_block_ckpt* ckpt, void* dx, const lr_block_params* grads, int accumulate,
+                     const lr_block_lax* lax, void* ws, size_t ws_bytes, void* stream) {
+  Blk b; int why;
+  if (!block_desc_ok(desc, b, &why)) return why;
+  TRY(check_lax(desc, lax));
+  TRY(check_params(params)); TRY(check_params(grads)); TRY(check_ckpt(ckpt));
+  TRY(check_ptrs(LR_BF16, {x, dy, dx}));
+  TRY(check_ws(ws, ws_bytes, lr_block_workspace_bytes(desc, 1)));
+  Ctx c; c.base = (char*)ws; c.cap = ws_bytes; c.dt = LR_BF16; c.gdt = b.gdt; c.st = (hipStream_t)stream;
+  block_bwd_seq(c, b, params, x, dy, ckpt, dx, grads, accumulate, lax);
   return c.err == hipErrorNotSupported ? LR_EUNSUPPORTED : status_of(c);
 }
 

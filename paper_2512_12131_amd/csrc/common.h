@@ -20,7 +20,11 @@ enum EpiKind : int {
   EPI_NORMBWD = 4,  // v = acc - (rho_m/d) * rowb_m * R2 + R ; C = v     (R2 = x, R = residual grad)
   EPI_PARTIAL = 5,  // fp32 store of a split-K partial: Cpart[split][M][N]
   EPI_SWIGLU_BWD = 6,  // v = acc (= dm); C = v*R2*silu'(R) (dg), C2 = v*silu(R) (du); R=g, R2=u
-  EPI_SWIGLU_FWD = 7   // v = acc (= u); C = v (skipped when C is null), C2 = silu(R)*v (m); R = g
+  EPI_SWIGLU_FWD = 7,  // v = acc (= u); C = v (skipped when C is null), C2 = silu(R)*v (m); R = g
+  // LaX variant (identity gate, rank-r residual from the layer below; App. "LaX variant"):
+  EPI_DOWN_LAX = 8,    // v = acc * rho_m ; C = v (= h_i) ; C2 = v + R (R = h_{i-1}; absent R reads as zero)
+  EPI_LAXGRAD = 9      // C2 = acc (gradient w.r.t. h_{i-1}) ; v = (acc + R2) * rho_m (R2 = the layer above's
+                       // gradient w.r.t. h_i) ; C = v ; rowpart = sum_n v * R (R = h_i)
 };
 
 struct Epilogue {
@@ -88,6 +92,8 @@ hipError_t k_act_fwd(const void* z, int64_t ldz, void* a, int64_t lda, int64_t T
                      int dt, hipStream_t);
 hipError_t k_swiglu_fwd(const void* g, const void* u, void* m, int64_t ld, int64_t T, int64_t f, int dt,
                         hipStream_t);
+// out = a + b, dense bf16 [T, n] (n a multiple of 8)
+hipError_t k_add2_bf16(const void* a, const void* b, void* out, int64_t T, int64_t n, hipStream_t);
 hipError_t k_swiglu_bwd(const void* g, const void* u, const void* dm, void* dg, void* du, int64_t ld,
                         int64_t T, int64_t f, int dt, hipStream_t);
 // out[r, c] = in[c, r] for in[rows, cols] (ld_in) -> out[cols, rows] (ld_out)

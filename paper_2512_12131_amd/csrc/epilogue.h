@@ -63,11 +63,12 @@ struct VecIO<bf16_t, 1> {
 // Which auxiliary tiles an epilogue kind reads (same shape as C): R and / or R2.
 template <int KIND>
 __device__ __forceinline__ bool epi_reads_r(const Epilogue& e) {
-  if constexpr (KIND == EPI_UP || KIND == EPI_NORMBWD) return e.R != nullptr;
+  if constexpr (KIND == EPI_UP || KIND == EPI_NORMBWD || KIND == EPI_DOWN_LAX || KIND == EPI_LAXGRAD) return e.R != nullptr;
   return KIND == EPI_ACTGRAD || KIND == EPI_SWIGLU_BWD || KIND == EPI_SWIGLU_FWD;
 }
 template <int KIND>
-__device__ __forceinline__ bool epi_reads_r2(const Epilogue&) {
+__device__ __forceinline__ bool epi_reads_r2(const Epilogue& e) {
+  if constexpr (KIND == EPI_LAXGRAD) return e.R2 != nullptr;
   return KIND == EPI_NORMBWD || KIND == EPI_SWIGLU_BWD;
 }
 
@@ -113,6 +114,19 @@ __device__ __forceinline__ float epi_math(int act, float inv_d, bool want2, floa
   } else if constexpr (KIND == EPI_SWIGLU_FWD) {
 #pragma unroll
     for (int i = 0; i < NV; i++) v2[i] = silu_f(r[i]) * v[i];
+  } else if constexpr (KIND == EPI_DOWN_LAX) {
+#pragma unroll
+    for (int i = 0; i < NV; i++) {
+      v[i] *= rho;
+      v2[i] = v[i] + r[i];
+    }
+  } else if constexpr (KIND == EPI_LAXGRAD) {
+#pragma unroll
+    for (int i = 0; i < NV; i++) {
+      v2[i] = v[i];
+      v[i] = (v[i] + r2[i]) * rho;
+      part += v[i] * r[i];
+    }
   }
   return part;
 }
@@ -124,10 +138,11 @@ __device__ __forceinline__ float epi_compute(const Epilogue& e, void* C, int64_t
                                              const float* r2) {
   using IO = VecIO<ST, NV>;
   float v2[NV];
-  const bool want2 = KIND == EPI_SWIGLU_BWD || KIND == EPI_SWIGLU_FWD || (KIND == EPI_DOWN && e.C2 != nullptr);
+  const bool want2 = KIND == EPI_SWIGLU_BWD || KIND == EPI_SWIGLU_FWD || KIND == EPI_DOWN_LAX || KIND == EPI_LAXGRAD ||
+                     (KIND == EPI_DOWN && e.C2 != nullptr);
   const float part = epi_math<NV, KIND>(e.act, e.inv_d, want2, v, v2, rho, rowb, r, r2);
   if (KIND != EPI_SWIGLU_FWD || C != nullptr) IO::store(C, (int64_t)b * sC + m * ldc + n, v);
-  if (want2) IO::store(e.C2, (int64_t)b * e.sC2 + m * e.ldc2 + n, v2);
+  if (want2 && e.C2 != nullptr) IO::store(e.C2, (int64_t)b * e.sC2 + m * e.ldc2 + n, v2);
   return part;
 }
 

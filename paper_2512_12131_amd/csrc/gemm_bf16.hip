@@ -427,8 +427,8 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
   // which auxiliary tiles a kind can read at all, and the prefetch distance in passes: kinds with one
   // auxiliary tile keep eight of its 16-byte vectors in flight per lane, kinds with two keep four of each
   constexpr bool HAS_R = KIND == EPI_UP || KIND == EPI_ACTGRAD || KIND == EPI_NORMBWD || KIND == EPI_SWIGLU_BWD ||
-                         KIND == EPI_SWIGLU_FWD;
-  constexpr bool HAS_R2 = KIND == EPI_NORMBWD || KIND == EPI_SWIGLU_BWD;
+                         KIND == EPI_SWIGLU_FWD || KIND == EPI_DOWN_LAX || KIND == EPI_LAXGRAD;
+  constexpr bool HAS_R2 = KIND == EPI_NORMBWD || KIND == EPI_SWIGLU_BWD || KIND == EPI_LAXGRAD;
   constexpr int PF = HAS_R2 ? 4 : 8;
   constexpr uint32_t EOOB = 0x80000000u;
   const int cg = lane % LPR, rsub = lane / LPR;
@@ -459,11 +459,12 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
   const int ldC = PARTIAL ? op.N * 4 : (int)op.ldc * 2;               // row pitches in bytes
   const int ldC2 = (int)e.ldc2 * 2, ldR = (int)e.ldr * 2, ldR2 = (int)e.ldr2 * 2;
   const uint32_t colC = col_ok ? (uint32_t)coln * (PARTIAL ? 4u : 2u) : EOOB, col2 = col_ok ? (uint32_t)coln * 2u : EOOB;
-  const bool want2 = KIND == EPI_SWIGLU_BWD || KIND == EPI_SWIGLU_FWD || (KIND == EPI_DOWN && e.C2 != nullptr);
+  const bool want2 = KIND == EPI_SWIGLU_BWD || KIND == EPI_SWIGLU_FWD || KIND == EPI_DOWN_LAX || KIND == EPI_LAXGRAD ||
+                     (KIND == EPI_DOWN && e.C2 != nullptr);
   const bool use_rho = !PARTIAL && e.use_rho;
   // row partials [M, rowpart_ld] and the statistic [M]: one lane per row writes, the others (and rows
   // past M) are given an out-of-range offset
-  constexpr bool ROWPART = KIND == EPI_UP || KIND == EPI_ACTGRAD;
+  constexpr bool ROWPART = KIND == EPI_UP || KIND == EPI_ACTGRAD || KIND == EPI_LAXGRAD;
   const __amdgpu_buffer_rsrc_t rsPart = __builtin_amdgcn_make_buffer_rsrc(
       (void*)((ROWPART && e.rowpart) ? e.rowpart + (int64_t)m0 * e.rowpart_ld : nullptr), 0,
       (ROWPART && e.rowpart) ? (uint32_t)rows_valid * (uint32_t)e.rowpart_ld * 4u : 0u, 0x00020000);
@@ -600,6 +601,9 @@ hipError_t dispatch(const GemmOp& op, hipStream_t st) {
     case EPI_PARTIAL: return launch<T, EPI_PARTIAL, false>(op, st);
     case EPI_SWIGLU_BWD: return launch<T, EPI_SWIGLU_BWD, false>(op, st);
     case EPI_SWIGLU_FWD: return launch<T, EPI_SWIGLU_FWD, false>(op, st);
+    case EPI_DOWN_LAX:
+      return op.epi.stat_from_a ? launch<T, EPI_DOWN_LAX, true>(op, st) : launch<T, EPI_DOWN_LAX, false>(op, st);
+    case EPI_LAXGRAD: return launch<T, EPI_LAXGRAD, false>(op, st);
     default: return hipErrorInvalidValue;
   }
 }

@@ -103,6 +103,8 @@ hipError_t gemm_f32(const GemmOp& op, hipStream_t st) {
     CASE(EPI_PARTIAL)
     CASE(EPI_SWIGLU_BWD)
     CASE(EPI_SWIGLU_FWD)
+    CASE(EPI_DOWN_LAX)
+    CASE(EPI_LAXGRAD)
 #undef CASE
     default: return hipErrorInvalidValue;
   }

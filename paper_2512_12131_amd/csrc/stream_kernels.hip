@@ -383,6 +383,30 @@ __global__ __launch_bounds__(256) void act_fwd_dense_kernel(const void* z, void*
   }
 }
 
+// out = a + b: the LaX variant's rank-r activation h_i + h_{i-1}, rebuilt in the backward
+template <int U>
+__global__ __launch_bounds__(256) void add2_dense_kernel(const void* a, const void* b, void* out, int64_t total_bytes) {
+  constexpr int64_t CHUNK = 256 * U * 16;
+  const __amdgpu_buffer_rsrc_t ra = chunk_rsrc(a, total_bytes, CHUNK), rb = chunk_rsrc(b, total_bytes, CHUNK),
+                               ro = chunk_rsrc(out, total_bytes, CHUNK);
+  u32x4_t aq[U], bq[U];
+#pragma unroll
+  for (int j = 0; j < U; j++) {
+    const int off = (j * 256 + (int)threadIdx.x) * 16;
+    aq[j] = __builtin_amdgcn_raw_buffer_load_b128(ra, off, 0, NT_POLICY);
+    bq[j] = __builtin_amdgcn_raw_buffer_load_b128(rb, off, 0, NT_POLICY);
+  }
+#pragma unroll
+  for (int j = 0; j < U; j++) {
+    float av[8], bv[8];
+    unpack8v(aq[j], av);
+    unpack8v(bq[j], bv);
+#pragma unroll
+    for (int k = 0; k < 8; k++) av[k] += bv[k];
+    __builtin_amdgcn_raw_buffer_store_b128(pack8v(av), ro, (j * 256 + (int)threadIdx.x) * 16, 0, NT_POLICY);
+  }
+}
+
 template <int U>
 __global__ __launch_bounds__(256) void swiglu_fwd_dense_kernel(const void* g, const void* u, void* m, int64_t total_bytes) {
   constexpr int64_t CHUNK = 256 * U * 16;
@@ -700,6 +724,12 @@ hipError_t k_act_fwd(const void* z, int64_t ldz, void* a, int64_t lda, int64_t T
   }
   const int nv = dt == LR_BF16 ? 8 : 1;
   DISPATCH_DT(dt, act_fwd_kernel, dim3(grid_chunks(T * (n / nv), 256 * EW_U)), dim3(256), st, z, ldz, a, lda, T, n, act);
+}
+hipError_t k_add2_bf16(const void* a, const void* b, void* out, int64_t T, int64_t n, hipStream_t st) {
+  if (T <= 0 || n <= 0) return hipSuccess;
+  const int64_t bytes = T * n * 2;
+  hipLaunchKernelGGL(add2_dense_kernel<DENSE_U>, dim3(grid_chunks(bytes / 16, 256 * DENSE_U)), dim3(256), 0, st, a, b, out, bytes);
+  return hipGetLastError();
 }
 hipError_t k_swiglu_fwd(const void* g, const void* u, void* m, int64_t ld, int64_t T, int64_t f, int dt,
                         hipStream_t st) {

@@ -66,6 +66,23 @@ def test_argument_errors_are_detected_on_the_host():
     assert a(fake, fake, fake, fake, null, 4096, 1, 128, 32, 128, 1, 1, None) == -1
 
 
+def test_lax_entry_points_refuse_on_the_host():
+    """The LaX block needs its struct and the identity gate; both are checked before any launch."""
+    lib = B.lib()
+    fake = C.c_void_p(0x1000)
+    desc_id = B.make_block_desc(1, 128, 128, 1, 128, 256, 256, 32, act=B.LR_ACT_IDENTITY)
+    desc_silu = B.make_block_desc(1, 128, 128, 1, 128, 256, 256, 32, act=B.LR_ACT_SILU)
+    ps = B.BlockParams(*[fake] * len(B.PARAM_NAMES))
+    ck = B.BlockCkpt(*[fake] * 6)
+    lx = B.BlockLax(*[C.c_void_p(0)] * 12)
+    odd = B.BlockLax(*([C.c_void_p(0x1002)] + [C.c_void_p(0)] * 11))
+    f = lib.lr_block_lax_fwd
+    assert f(C.byref(desc_id), C.byref(ps), fake, fake, C.byref(ck), None, fake, 1 << 30, None) == -1
+    assert f(C.byref(desc_silu), C.byref(ps), fake, fake, C.byref(ck), C.byref(lx), fake, 1 << 30, None) == -2
+    assert f(C.byref(desc_id), C.byref(ps), fake, fake, C.byref(ck), C.byref(odd), fake, 1 << 30, None) == -4
+    assert f(C.byref(desc_id), C.byref(ps), fake, fake, C.byref(ck), C.byref(lx), fake, 16, None) == -3
+
+
 def test_workspace_queries_scale_and_reject():
     lib = B.lib()
     a = lib.lr_group_workspace_bytes(3, 1024, 256, 64, 256, 1, 0)
