@@ -254,6 +254,33 @@ def attention_bwd(q, k, v, do, B, S, H, hd, causal=True):
 
 
 # --------------------------------------------------------------------------------------------
+# Rotary position embedding, an optional step of the block (LLaMA-style models, Sec. 5.2; the paper
+# does not describe it, the block applies it only on request).  Convention: the "rotate half" form.
+# Inside every head the pair (v[i], v[i + hd/2]), i < hd/2, of the token at position p of its sequence
+# is turned by the angle theta[p, i]; the caller supplies cos(theta) and sin(theta) as [S, hd/2]
+# tables.  inverse=True turns by -theta: the transpose of the rotation, which is what the backward
+# applies to the gradients of the rotated q and k.
+# --------------------------------------------------------------------------------------------
+def rope_tables(S, hd, base=10000.0):
+    """cos, sin [S, hd/2] of theta[p, i] = p * base^(-2 i / hd)  (the usual choice of angles)."""
+    i = np.arange(hd // 2, dtype=F64)
+    theta = np.arange(S, dtype=F64)[:, None] * base ** (-2.0 * i / hd)[None, :]
+    return np.cos(theta), np.sin(theta)
+
+
+def rope_apply(x, cos, sin, B, S, H, hd, inverse=False):
+    """x[T, H*hd] -> rotated copy; position of row t is t mod S."""
+    x4 = np.asarray(x, dtype=F64).reshape(B, S, H, hd)
+    c = np.asarray(cos, dtype=F64)[None, :, None, :]
+    sn = np.asarray(sin, dtype=F64)[None, :, None, :]
+    if inverse:
+        sn = -sn
+    lo, hi = x4[..., : hd // 2], x4[..., hd // 2:]
+    out = np.concatenate([lo * c - hi * sn, hi * c + lo * sn], axis=-1)
+    return out.reshape(B * S, H * hd)
+
+
+# --------------------------------------------------------------------------------------------
 # The decoder block.  Seven projections, each factored once at rank r (App. "Communication
 # volume analysis": 4 attention + 3 MLP maps, 11dr + 3 d_ff r parameters), pre-norm residual
 # layout of LLaMA-2 (Sec. 5.2), SwiGLU gate at width d_ff kept in addition to sigma at rank r.
@@ -268,14 +295,19 @@ def block_param_count(d, f, r):
     return 11 * d * r + 3 * f * r
 
 
-def block_fwd(x, p, B, S, H, hd, eps, act=ACT_SILU, causal=True):
-    """Returns (y, cache) where cache holds every intermediate (store-everything reference)."""
+def block_fwd(x, p, B, S, H, hd, eps, act=ACT_SILU, causal=True, rope=None):
+    """Returns (y, cache) where cache holds every intermediate (store-everything reference).
+    rope: None, or (cos, sin) tables [S, hd/2]: q and k are rotated before the attention."""
     x = np.asarray(x, dtype=F64)
     c = {"x": x}
     c["xh1"], c["rms1"] = rmsnorm_fwd(x, p["gamma1"], eps)
     for n in ("q", "k", "v"):
         c["z_" + n], c["a_" + n], c[n] = lr_linear_fwd(c["xh1"], p["wd_" + n], p["wu_" + n], act)
-    c["o"], c["lse"] = attention_fwd(c["q"], c["k"], c["v"], B, S, H, hd, causal)
+    c["qr"], c["kr"] = c["q"], c["k"]
+    if rope is not None:
+        c["qr"] = rope_apply(c["q"], rope[0], rope[1], B, S, H, hd)
+        c["kr"] = rope_apply(c["k"], rope[0], rope[1], B, S, H, hd)
+    c["o"], c["lse"] = attention_fwd(c["qr"], c["kr"], c["v"], B, S, H, hd, causal)
     c["z_o"], c["a_o"], c["attn_out"] = lr_linear_fwd(c["o"], p["wd_o"], p["wu_o"], act)
     c["h1"] = x + c["attn_out"]
     c["xh2"], c["rms2"] = rmsnorm_fwd(c["h1"], p["gamma2"], eps)
@@ -287,10 +319,10 @@ def block_fwd(x, p, B, S, H, hd, eps, act=ACT_SILU, causal=True):
     return y, c
 
 
-def block_bwd(x, p, dy, B, S, H, hd, eps, act=ACT_SILU, causal=True):
+def block_bwd(x, p, dy, B, S, H, hd, eps, act=ACT_SILU, causal=True, rope=None):
     """Gradients of L = sum(y * dy) w.r.t. x and every parameter.  Returns (dx, grads)."""
     dy = np.asarray(dy, dtype=F64)
-    _, c = block_fwd(x, p, B, S, H, hd, eps, act, causal)
+    _, c = block_fwd(x, p, B, S, H, hd, eps, act, causal, rope)
     g = {}
     # y = h1 + lr(m)
     dm, g["wd_d"], g["wu_d"] = lr_linear_bwd(c["m"], p["wd_d"], p["wu_d"], dy, act)
@@ -306,7 +338,10 @@ def block_bwd(x, p, dy, B, S, H, hd, eps, act=ACT_SILU, causal=True):
     dh1 += dh1_n
     # h1 = x + lr(o)
     do, g["wd_o"], g["wu_o"] = lr_linear_bwd(c["o"], p["wd_o"], p["wu_o"], dh1, act)
-    dq, dk, dv = attention_bwd(c["q"], c["k"], c["v"], do, B, S, H, hd, causal)
+    dq, dk, dv = attention_bwd(c["qr"], c["kr"], c["v"], do, B, S, H, hd, causal)
+    if rope is not None:                 # back through the rotations: their transposes
+        dq = rope_apply(dq, rope[0], rope[1], B, S, H, hd, inverse=True)
+        dk = rope_apply(dk, rope[0], rope[1], B, S, H, hd, inverse=True)
     dxh1 = np.zeros_like(c["xh1"])
     for n, dn in (("q", dq), ("k", dk), ("v", dv)):
         dxi, g["wd_" + n], g["wu_" + n] = lr_linear_bwd(c["xh1"], p["wd_" + n], p["wu_" + n], dn, act)
