@@ -39,6 +39,8 @@ WORKLOADS = {
     # activation of the layer below before its up-projection; timed as a middle block of a stack (it
     # receives h_prev and dz_next and returns dh_prev)
     "block-7B-lax": (4, 4096, 4096, 32, 11008, 1024, "lax"),
+    # rotary position embedding of q and k switched on (LLaMA-style attention; tables of the usual angles)
+    "block-7B-rope": (4, 4096, 4096, 32, 11008, 1024, "rope"),
 }
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 HBM_PEAK_GBS = 8000.0
@@ -127,7 +129,11 @@ def main():
     f_ld = si.pad_ld(f, 8)
     eps = 1e-5
     case = si.block_case(Bn, S, d, H, 128, f, r, seed=0)
-    desc = B.make_block_desc(Bn, S, d, H, 128, f, f_ld, r, eps=eps, act=act)
+    rope = None
+    if variant == "rope":
+        ang = torch.arange(S, dtype=torch.float64)[:, None] * 10000.0 ** (-2.0 * torch.arange(64, dtype=torch.float64) / 128)
+        rope = (torch.cos(ang).float().to(dev), torch.sin(ang).float().to(dev))
+    desc = B.make_block_desc(Bn, S, d, H, 128, f, f_ld, r, eps=eps, act=act, rope=rope)
     params = {k: v.to(dev) for k, v in si.pack_block_params(case["params"], f, f_ld).items()}
     x, dy = case["x"].to(dev), case["dy"].to(dev)
     ck = B.alloc_block_ckpt(desc, dev)
@@ -301,7 +307,8 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: low-rank decoder block fwd+bwd, batch {Bn}, seq {S}, d_model {d}, "
                                f"{H} heads of 128, ffn {f}, rank {r}, sigma {'identity' if act == B.LR_ACT_IDENTITY else 'SiLU'}"
-                               f"{' + rank-r residual from the layer below (LaX)' if variant == 'lax' else ''}, "
+                               f"{' + rank-r residual from the layer below (LaX)' if variant == 'lax' else ''}"
+                               f"{', rotary embedding of q and k' if variant == 'rope' else ''}, "
                                f"rank-r checkpoint recompute",
                    "tokens": T, "executed_tflop": round(fl["exec"] / 1e12, 3),
                    "model_tflop": round(fl["model"] / 1e12, 3),
@@ -335,8 +342,9 @@ def main():
             lorc.block_bwd(X0, P, hp, DY0, dzn, 1, s_len, H, 128, eps)
         else:
             oact = orc.ACT_IDENTITY if act == B.LR_ACT_IDENTITY else orc.ACT_SILU
-            orc.block_fwd(X0, P, 1, s_len, H, 128, eps, act=oact)
-            orc.block_bwd(X0, P, DY0, 1, s_len, H, 128, eps, act=oact)
+            orope = None if rope is None else (si.f64(rope[0].cpu()), si.f64(rope[1].cpu()))
+            orc.block_fwd(X0, P, 1, s_len, H, 128, eps, act=oact, rope=orope)
+            orc.block_bwd(X0, P, DY0, 1, s_len, H, 128, eps, act=oact, rope=orope)
         ct = time.perf_counter() - t0
         cfl = block_flops(1, s_len, d, H, f, r)
         cpu_flops = cfl["model"] + cfl["lin_fwd"] + cfl["attn_fwd"]   # block_bwd runs its own forward again

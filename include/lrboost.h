@@ -113,6 +113,12 @@ typedef struct {
   int dt;          /* LR_BF16                                                              */
   int grad_dt;     /* dtype of the weight / gamma gradient buffers: LR_F32 or LR_BF16      */
   int causal;      /* 1                                                                    */
+  /* Optional rotary position embedding of q and k (LLaMA-style models, Sec. 5.2), applied
+   * between the up-projections and the attention in the forward and in the re-forward, and
+   * transposed on dq, dk in the backward.  DEVICE pointers to cos / sin tables [seq, 64] fp32
+   * (16-byte aligned) of the angles of lr_rope below; both NULL: no rotary embedding.       */
+  const float* rope_cos;
+  const float* rope_sin;
 } lr_block_desc;
 
 typedef struct {
@@ -174,6 +180,16 @@ int lr_block_lax_bwd(const lr_block_desc* desc, const lr_block_params* params, c
                      const void* dy, const lr_block_ckpt* ckpt, void* dx,
                      const lr_block_params* grads, int accumulate, const lr_block_lax* lax,
                      void* ws, size_t ws_bytes, void* stream);
+
+/* ---- rotary position embedding (optional step of the block; the paper does not describe
+ * it, LLaMA-style attention has it) -------------------------------------------------------
+ * In place on x[B*S, ldx] (bf16, H heads of hd = 128 from column 0): inside every head the pair
+ * (v[i], v[i + 64]), i < 64, of the token at position p of its sequence becomes
+ * (v[i] c - v[i+64] s, v[i+64] c + v[i] s) with c = cos_tab[p, i], s = sin_tab[p, i]
+ * (DEVICE tables [S, 64] fp32).  inverse != 0 uses -s: the transpose of the rotation, which
+ * is its backward.  Other dtypes / head sizes: LR_EUNSUPPORTED.                             */
+int lr_rope(void* x, int64_t ldx, const float* cos_tab, const float* sin_tab, int64_t B,
+            int64_t S, int64_t H, int64_t hd, int inverse, int dt, void* stream);
 
 /* ---- causal multi-head attention (the sharded-safe op between the chunks, Sec. 4.2) ---- */
 /* q, k, v, o: [B*S, H*hd] token-major, head h in columns h*hd..; lse[B, H, S] fp32.

@@ -31,7 +31,7 @@ class LrError(RuntimeError):
 class BlockDesc(C.Structure):
     _fields_ = [("batch", _i64), ("seq", _i64), ("d_model", _i64), ("n_heads", _i64), ("head_dim", _i64),
                 ("ffn", _i64), ("ffn_ld", _i64), ("rank", _i64), ("eps", _f32), ("act", _int), ("norm", _int),
-                ("dt", _int), ("grad_dt", _int), ("causal", _int)]
+                ("dt", _int), ("grad_dt", _int), ("causal", _int), ("rope_cos", _vp), ("rope_sin", _vp)]
 
 
 class BlockParams(C.Structure):
@@ -72,6 +72,7 @@ _SIGS = {
                                 C.POINTER(BlockLax), _vp, _sz, _vp]),
     "lr_block_lax_bwd": (_int, [C.POINTER(BlockDesc), C.POINTER(BlockParams), _vp, _vp, C.POINTER(BlockCkpt), _vp,
                                 C.POINTER(BlockParams), _int, C.POINTER(BlockLax), _vp, _sz, _vp]),
+    "lr_rope": (_int, [_vp, _i64, _vp, _vp, _i64, _i64, _i64, _i64, _int, _int, _vp]),
     "lr_attention_fwd": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _int, _int, _vp]),
     "lr_attention_bwd_workspace_bytes": (_sz, [_i64, _i64, _i64, _i64]),
     "lr_attention_bwd": (_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _int, _int,
@@ -219,8 +220,16 @@ def lr_group_bwd(x, gamma, eps, norm, w_down_cat, w_up_stack, z_cat, stat, dy_st
 
 # ---- the decoder block -----------------------------------------------------------------------
 def make_block_desc(batch, seq, d_model, n_heads, head_dim, ffn, ffn_ld, rank, eps=1e-5, act=LR_ACT_SILU,
-                    norm=LR_NORM_ONLINE, dt=LR_BF16, grad_dt=LR_F32, causal=1):
-    return BlockDesc(batch, seq, d_model, n_heads, head_dim, ffn, ffn_ld, rank, eps, act, norm, dt, grad_dt, causal)
+                    norm=LR_NORM_ONLINE, dt=LR_BF16, grad_dt=LR_F32, causal=1, rope=None):
+    """rope: None, or (cos, sin) device tensors [seq, head_dim / 2] fp32.  The descriptor holds their
+    addresses only: keep the tensors alive while the descriptor is in use (desc._rope does)."""
+    cos_p = sin_p = None
+    if rope is not None:
+        cos_p, sin_p = rope[0].data_ptr(), rope[1].data_ptr()
+    desc = BlockDesc(batch, seq, d_model, n_heads, head_dim, ffn, ffn_ld, rank, eps, act, norm, dt, grad_dt, causal,
+                     cos_p, sin_p)
+    desc._rope = rope
+    return desc
 
 
 def _params_struct(params: dict):
@@ -334,6 +343,13 @@ def lr_block_lax_bwd(desc, params: dict, x, dy, ckpt: dict, h_prev: dict = None,
     _check(lib().lr_block_lax_bwd(C.byref(desc), C.byref(ps), _p(x), _p(dy), C.byref(cs), _p(dx), C.byref(gs),
                                   int(accumulate), C.byref(lx), _p(ws), ws.numel(), _stream()), "lr_block_lax_bwd")
     return dx, grads, dh
+
+
+# ---- rotary position embedding ----------------------------------------------------------------
+def lr_rope(x, cos, sin, B, S, H, hd, inverse=False):
+    """In place on x [B*S, >= H*hd] bf16; cos, sin [S, hd/2] fp32 device tensors.  Returns x."""
+    _check(lib().lr_rope(_p(x), _rowmajor(x), _p(cos), _p(sin), B, S, H, hd, int(inverse), _dt(x), _stream()), "lr_rope")
+    return x
 
 
 # ---- attention -----------------------------------------------------------------------------

@@ -349,6 +349,7 @@ struct Blk {
   int64_t B, S, T, d, H, hd, f, r;
   float eps;
   int act, norm, causal, gdt;
+  const float *rope_cos, *rope_sin;   // both null: no rotary embedding
 };
 
 bool block_desc_ok(const lr_block_desc* ds, Blk& b, int* why) {
@@ -370,6 +371,9 @@ bool block_desc_ok(const lr_block_desc* ds, Blk& b, int* why) {
   b.B = ds->batch; b.S = ds->seq; b.T = ds->batch * ds->seq; b.d = ds->d_model; b.H = ds->n_heads; b.hd = ds->head_dim;
   b.f = ds->ffn_ld; b.r = ds->rank; b.eps = ds->eps; b.act = ds->act; b.norm = ds->norm; b.causal = ds->causal;
   b.gdt = ds->grad_dt;
+  b.rope_cos = ds->rope_cos; b.rope_sin = ds->rope_sin;
+  if ((b.rope_cos == nullptr) != (b.rope_sin == nullptr)) { *why = LR_EINVAL; return false; }
+  if (b.rope_cos && (((uintptr_t)b.rope_cos & 15) || ((uintptr_t)b.rope_sin & 15))) { *why = LR_EALIGN; return false; }
   *why = LR_OK;
   return true;
 }
@@ -473,6 +477,8 @@ void block_fwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x
   a.z_cat = ck ? ck->z_qkv : nullptr; a.stat = ck ? ck->s1 : nullptr; a.y_stack = qkv; a.act_out = act;
   a.lax = lax; a.h_prev = lax ? lx->h_prev_qkv : nullptr;
   group_fwd_seq(c, a);
+  if (b.rope_cos)   // q and k are the first two [T, d] members of the stack: one pass over both
+    LAUNCH(c, k_rope128_bf16(qkv, d, b.rope_cos, b.rope_sin, 2 * T, (int)b.S, (int)b.H, 0, c.st));
   LAUNCH(c, attention_fwd_bf16(qkv, (char*)qkv + (size_t)T * d * es, (char*)qkv + (size_t)2 * T * d * es, o, lse, d,
                                (int)b.B, (int)b.S, (int)b.H, (int)b.hd, b.causal, c.st));
   single_down(c, b, o, d, p->w_dn_o, ck ? ck->z_o : nullptr, act, lax, lax ? lx->h_prev_o : nullptr);
@@ -559,6 +565,7 @@ void block_bwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x
   GrpArgs a = group_args(b, 3, d);
   a.x = x; a.gamma = p->gamma1; a.w_down_cat = p->w_dn_qkv; a.w_up_stack = p->w_up_qkv; a.y_stack = qkv;
   group_up_seq(c, a, act_g);
+  if (b.rope_cos) LAUNCH(c, k_rope128_bf16(qkv, d, b.rope_cos, b.rope_sin, 2 * T, (int)b.S, (int)b.H, 0, c.st));
   const void* q_ = qkv; const void* k_ = (char*)qkv + (size_t)T * d * es; const void* v_ = (char*)qkv + (size_t)2 * T * d * es;
   LAUNCH(c, attention_fwd_bf16(q_, k_, v_, o, lse, d, (int)b.B, (int)b.S, (int)b.H, (int)b.hd, b.causal, c.st));
   // down-O backward
@@ -578,6 +585,8 @@ void block_bwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x
                                  b.causal, aws, c.st));
     c.release(mk);
   }
+  // back through the rotations of q and k: their transposes, on dq and dk
+  if (b.rope_cos) LAUNCH(c, k_rope128_bf16(dqkv, d, b.rope_cos, b.rope_sin, 2 * T, (int)b.S, (int)b.H, 1, c.st));
   a.zc = ck->z_qkv; a.statc = ck->s1; a.dy_stack = dqkv; a.dx = dx; a.dres = dh1; a.dgamma = g->gamma1;
   a.dw_down_cat = g->w_dn_qkv; a.dw_up_stack = g->w_up_qkv; a.accumulate = accumulate;
   a.lax = lax; a.dz_next = lx->dz_next_qkv; a.dh_prev = lx->dh_prev_qkv;
@@ -857,6 +866,20 @@ int lr_attention_bwd(const void* q, const void* k, const void* v, const void* o,
   hipError_t e = attention_bwd_bf16(q, k, v, o, dout, lse, dq, dk, dv, ld, (int)B, (int)S, (int)H, (int)hd, causal, ws,
                                     (hipStream_t)stream);
   return e == hipSuccess ? LR_OK : (e == hipErrorNotSupported ? LR_EUNSUPPORTED : LR_ELAUNCH);
+}
+
+// ---- rotary position embedding -------------------------------------------------------------------
+int lr_rope(void* x, int64_t ldx, const float* cos_tab, const float* sin_tab, int64_t B, int64_t S, int64_t H,
+            int64_t hd, int inverse, int dt, void* stream) {
+  if (B < 0 || S <= 0 || H <= 0 || hd <= 0 || ldx < H * hd) return LR_EINVAL;
+  if (B * S > 0x7fffffffLL || H > 0x7fffffffLL || S > 0x7fffffffLL) return LR_EINVAL;
+  if (dt != LR_BF16 || hd != 128) return LR_EUNSUPPORTED;
+  if (B == 0) return LR_OK;
+  if (!cos_tab || !sin_tab) return LR_EINVAL;
+  TRY(check_ptrs(LR_BF16, {x, cos_tab, sin_tab}));
+  if (ldx % 8) return LR_EALIGN;
+  hipError_t e = k_rope128_bf16(x, ldx, cos_tab, sin_tab, B * S, (int)S, (int)H, inverse, (hipStream_t)stream);
+  return e == hipSuccess ? LR_OK : LR_ELAUNCH;
 }
 
 // ---- measurement aid ---------------------------------------------------------------------------

@@ -92,6 +92,10 @@ hipError_t k_act_fwd(const void* z, int64_t ldz, void* a, int64_t lda, int64_t T
                      int dt, hipStream_t);
 hipError_t k_swiglu_fwd(const void* g, const void* u, void* m, int64_t ld, int64_t T, int64_t f, int dt,
                         hipStream_t);
+// rotary embedding in place on x[rows, ld] (bf16, H heads of 128 from column 0, position = row % S);
+// cos / sin tables [S, 64] fp32; inverse = the transposed rotation
+hipError_t k_rope128_bf16(void* x, int64_t ld, const float* cos_tab, const float* sin_tab, int64_t rows, int S, int H,
+                          int inverse, hipStream_t);
 // out = a + b, dense bf16 [T, n] (n a multiple of 8)
 hipError_t k_add2_bf16(const void* a, const void* b, void* out, int64_t T, int64_t n, hipStream_t);
 hipError_t k_swiglu_bwd(const void* g, const void* u, const void* dm, void* dg, void* du, int64_t ld,

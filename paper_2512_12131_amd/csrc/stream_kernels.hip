@@ -462,6 +462,40 @@ __global__ __launch_bounds__(256) void swiglu_bwd_dense_kernel(const void* g, co
   }
 }
 
+// ---- rotary position embedding, in place, heads of 128 (rotate-half form) -----------------------
+// x[rows, ld], head h in columns 128 h ..; the pair (v[i], v[i + 64]) of the row at position p = row % S
+// is turned by the angle whose cosine and sine the caller tabulated as cs[p, i], sn[p, i] ([S, 64] fp32).
+// One lane owns 8 consecutive i of one head: two 16-byte loads, two 16-byte stores.  sgn = -1 applies the
+// transpose (the backward of the rotation).
+__global__ __launch_bounds__(256) void rope128_kernel(uint16_t* x, int64_t ld, const float* __restrict__ cs,
+                                                      const float* __restrict__ sn, int64_t rows, int S, int H, float sgn) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= rows * H * 8) return;
+  const int c8 = (int)(idx & 7) * 8;
+  const int64_t rh = idx >> 3;
+  const int h = (int)(rh % H);
+  const int64_t row = rh / H;
+  const int p = (int)(row % S);
+  uint16_t* ptr = x + row * ld + (int64_t)h * 128 + c8;
+  float lo[8], hi[8], c[8], s[8];
+  unpack8(*reinterpret_cast<const uint4*>(ptr), lo);
+  unpack8(*reinterpret_cast<const uint4*>(ptr + 64), hi);
+  const float4* cp = reinterpret_cast<const float4*>(cs + (int64_t)p * 64 + c8);
+  const float4* sp = reinterpret_cast<const float4*>(sn + (int64_t)p * 64 + c8);
+  const float4 c0 = cp[0], c1 = cp[1], s0 = sp[0], s1 = sp[1];
+  c[0] = c0.x; c[1] = c0.y; c[2] = c0.z; c[3] = c0.w; c[4] = c1.x; c[5] = c1.y; c[6] = c1.z; c[7] = c1.w;
+  s[0] = s0.x; s[1] = s0.y; s[2] = s0.z; s[3] = s0.w; s[4] = s1.x; s[5] = s1.y; s[6] = s1.z; s[7] = s1.w;
+  float olo[8], ohi[8];
+#pragma unroll
+  for (int i = 0; i < 8; i++) {
+    const float si = s[i] * sgn;
+    olo[i] = lo[i] * c[i] - hi[i] * si;
+    ohi[i] = hi[i] * c[i] + lo[i] * si;
+  }
+  *reinterpret_cast<uint4*>(ptr) = pack8(olo);
+  *reinterpret_cast<uint4*>(ptr + 64) = pack8(ohi);
+}
+
 // ---- transpose: out[c, r] = in[r, c]; 64x64 tiles through LDS.  Output columns rows..pad_to-1
 // are written as zeros, so a transposed activation can serve as a k-contiguous GEMM operand whose
 // k extent is rounded up to the 16-byte vector.
@@ -724,6 +758,14 @@ hipError_t k_act_fwd(const void* z, int64_t ldz, void* a, int64_t lda, int64_t T
   }
   const int nv = dt == LR_BF16 ? 8 : 1;
   DISPATCH_DT(dt, act_fwd_kernel, dim3(grid_chunks(T * (n / nv), 256 * EW_U)), dim3(256), st, z, ldz, a, lda, T, n, act);
+}
+hipError_t k_rope128_bf16(void* x, int64_t ld, const float* cos_tab, const float* sin_tab, int64_t rows, int S, int H,
+                          int inverse, hipStream_t st) {
+  if (rows <= 0 || H <= 0) return hipSuccess;
+  const int64_t items = rows * H * 8;
+  hipLaunchKernelGGL(rope128_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), 0, st, (uint16_t*)x, ld, cos_tab,
+                     sin_tab, rows, S, H, inverse ? -1.f : 1.f);
+  return hipGetLastError();
 }
 hipError_t k_add2_bf16(const void* a, const void* b, void* out, int64_t T, int64_t n, hipStream_t st) {
   if (T <= 0 || n <= 0) return hipSuccess;

@@ -83,6 +83,23 @@ def test_lax_entry_points_refuse_on_the_host():
     assert f(C.byref(desc_id), C.byref(ps), fake, fake, C.byref(ck), C.byref(lx), fake, 16, None) == -3
 
 
+def test_rope_arguments_are_checked_on_the_host():
+    lib = B.lib()
+    fake, null, odd = C.c_void_p(0x1000), C.c_void_p(0), C.c_void_p(0x1004)
+    f = lib.lr_rope
+    assert f(fake, 128, fake, fake, 2, 16, 2, 128, 0, 1, None) == -1           # row shorter than the heads
+    assert f(fake, 256, fake, fake, 2, 16, 2, 64, 0, 1, None) == -2            # other head sizes
+    assert f(fake, 256, fake, fake, 2, 16, 2, 128, 0, 0, None) == -2           # fp32
+    assert f(fake, 256, null, fake, 2, 16, 2, 128, 0, 1, None) == -1
+    assert f(odd, 256, fake, fake, 2, 16, 2, 128, 0, 1, None) == -4
+    assert f(fake, 256, fake, fake, 0, 16, 2, 128, 0, 1, None) == 0            # nothing to do
+    # the block descriptor wants both tables or neither
+    d = B.make_block_desc(1, 128, 128, 1, 128, 256, 256, 32)
+    assert lib.lr_block_workspace_bytes(C.byref(d), 0) > 0
+    d.rope_cos = 0x1000
+    assert lib.lr_block_workspace_bytes(C.byref(d), 0) == 0
+
+
 def test_workspace_queries_scale_and_reject():
     lib = B.lib()
     a = lib.lr_group_workspace_bytes(3, 1024, 256, 64, 256, 1, 0)
