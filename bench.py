@@ -48,7 +48,7 @@ HBM_PEAK_GBS = 8000.0
 # FETCH_SIZE and WRITE_SIZE runs of this benchmark, each scaled by what the same counter reads for a
 # plain 1 GiB copy (x2.000 and x1.000): profiles/gemm_bf16_block-7B_hbm_traffic.txt.  Counters cannot
 # be read from inside this process, so workloads without such a measurement report null.
-MEASURED_GEMM_TRAFFIC_BYTES = {"block-7B": 708.3e6}
+MEASURED_GEMM_TRAFFIC_BYTES = {"block-7B": 708.7e6}
 
 
 def block_flops(B, S, d, H, f, r):
