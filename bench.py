@@ -108,6 +108,9 @@ def main():
                     help="add an 'ablation' object: grouped / batched projections and the statistic taken "
                          "inside the GEMM against their separate forms (Table 3's compute rows, Sec. 5.3), "
                          "and the cost of the rank-r checkpoint recompute (Table 5), at 4096 and 16384 tokens")
+    ap.add_argument("--chain-stat", action="store_true",
+                    help="time the block as a middle block of a stack: the sum of squares of x arrives from the block "
+                         "below (ckpt s1 pre-filled) and the one of y is emitted from the epilogue of the last GEMM")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run a plain device copy of this many MiB (3 times), so that a hardware-counter "
                          "run of this command can scale FETCH_SIZE / WRITE_SIZE by a kernel of known traffic")
@@ -133,10 +136,14 @@ def main():
     if variant == "rope":
         ang = torch.arange(S, dtype=torch.float64)[:, None] * 10000.0 ** (-2.0 * torch.arange(64, dtype=torch.float64) / 128)
         rope = (torch.cos(ang).float().to(dev), torch.sin(ang).float().to(dev))
-    desc = B.make_block_desc(Bn, S, d, H, 128, f, f_ld, r, eps=eps, act=act, rope=rope)
+    chain = args.chain_stat
+    sy = torch.empty((Bn * S,), dtype=torch.float32, device=dev) if chain else None
+    desc = B.make_block_desc(Bn, S, d, H, 128, f, f_ld, r, eps=eps, act=act, rope=rope, stat_x_ready=chain, stat_y_out=sy)
     params = {k: v.to(dev) for k, v in si.pack_block_params(case["params"], f, f_ld).items()}
     x, dy = case["x"].to(dev), case["dy"].to(dev)
     ck = B.alloc_block_ckpt(desc, dev)
+    if chain:   # what the block below would have left there
+        ck["s1"].copy_(B.lr_rms_stat(x))
     y, dx = torch.empty_like(x), torch.empty_like(x)
     grads = {n: torch.zeros_like(params[n], dtype=torch.float32) for n in B.PARAM_NAMES}
     ws = torch.empty(max(B.lr_block_workspace_bytes(desc, 0), B.lr_block_workspace_bytes(desc, 1)),

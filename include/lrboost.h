@@ -119,6 +119,14 @@ typedef struct {
    * (16-byte aligned) of the angles of lr_rope below; both NULL: no rotary embedding.       */
   const float* rope_cos;
   const float* rope_sin;
+  /* Chaining the norm statistic through a stack of blocks (Sec. 4.2: the sum of squares travels
+   * with the GEMM that produces the normalised tensor).  stat_y_out, if not NULL: DEVICE [T] fp32,
+   * receives sum_j y[t,j]^2, accumulated from the fp32 output tiles in the epilogue of the block's
+   * last GEMM; it is the s1 of the block above.  stat_x_ready != 0: ckpt->s1 already holds
+   * sum_j x[t,j]^2 (the stat_y_out of the block below) and the forward takes it as given instead
+   * of computing it from x.                                                                    */
+  int stat_x_ready;
+  float* stat_y_out;
 } lr_block_desc;
 
 typedef struct {

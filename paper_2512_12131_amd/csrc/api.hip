@@ -350,6 +350,8 @@ struct Blk {
   float eps;
   int act, norm, causal, gdt;
   const float *rope_cos, *rope_sin;   // both null: no rotary embedding
+  int stat_x_ready;                   // ckpt->s1 arrives filled (by the block below)
+  float* stat_y_out;                  // optional: sum of squares of y for the block above
 };
 
 bool block_desc_ok(const lr_block_desc* ds, Blk& b, int* why) {
@@ -372,6 +374,8 @@ bool block_desc_ok(const lr_block_desc* ds, Blk& b, int* why) {
   b.f = ds->ffn_ld; b.r = ds->rank; b.eps = ds->eps; b.act = ds->act; b.norm = ds->norm; b.causal = ds->causal;
   b.gdt = ds->grad_dt;
   b.rope_cos = ds->rope_cos; b.rope_sin = ds->rope_sin;
+  b.stat_x_ready = ds->stat_x_ready != 0; b.stat_y_out = ds->stat_y_out;
+  if (b.stat_y_out && ((uintptr_t)b.stat_y_out & 3)) { *why = LR_EALIGN; return false; }
   if ((b.rope_cos == nullptr) != (b.rope_sin == nullptr)) { *why = LR_EINVAL; return false; }
   if (b.rope_cos && (((uintptr_t)b.rope_cos & 15) || ((uintptr_t)b.rope_sin & 15))) { *why = LR_EALIGN; return false; }
   *why = LR_OK;
@@ -475,6 +479,7 @@ void block_fwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x
   GrpArgs a = group_args(b, 3, d);
   a.x = x; a.gamma = p->gamma1; a.w_down_cat = p->w_dn_qkv; a.w_up_stack = p->w_up_qkv;
   a.z_cat = ck ? ck->z_qkv : nullptr; a.stat = ck ? ck->s1 : nullptr; a.y_stack = qkv; a.act_out = act;
+  a.stat_ready = b.stat_x_ready;
   a.lax = lax; a.h_prev = lax ? lx->h_prev_qkv : nullptr;
   group_fwd_seq(c, a);
   if (b.rope_cos)   // q and k are the first two [T, d] members of the stack: one pass over both
@@ -491,7 +496,7 @@ void block_fwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x
   group_down_seq(c, m, act);
   mlp_up_swiglu(c, b, p->w_up_gu, act, gg, nullptr, mm);
   single_down(c, b, mm, f, p->w_dn_d, ck ? ck->z_d : nullptr, act, lax, lax ? lx->h_prev_d : nullptr);
-  single_up(c, b, act, p->w_up_d, d, h1, y, nullptr);
+  single_up(c, b, act, p->w_up_d, d, h1, y, b.stat_y_out);   // optionally sum y^2 for the block above
 }
 
 void block_bwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x, const void* dy,

@@ -135,6 +135,38 @@ def test_block_identity_sigma():
         check("d" + name, got[name], ref, dt, floor=FLW)
 
 
+def test_block_statistic_chained_between_blocks():
+    """Block 1 emits sum y^2 from the epilogue of its last GEMM into block 2's s1; block 2 takes it as given
+    (stat_x_ready).  Block 2's results against the oracle, and the emitted statistic against sum x2^2."""
+    Bn, S, H, f, r = 2, 192, 2, 344, 64
+    d = 128 * H
+    f_ld = si.pad_ld(f, 8)
+    print("block statistic chain", flush=True)
+    case1 = si.block_case(Bn, S, d, H, 128, f, r, seed=6)
+    case2 = si.block_case(Bn, S, d, H, 128, f, r, seed=7)
+    p1 = {k: v.to(DEV) for k, v in si.pack_block_params(case1["params"], f, f_ld).items()}
+    p2 = {k: v.to(DEV) for k, v in si.pack_block_params(case2["params"], f, f_ld).items()}
+    x, dy = case1["x"].to(DEV), case1["dy"].to(DEV)
+    desc2 = B.make_block_desc(Bn, S, d, H, 128, f, f_ld, r, eps=EPS, stat_x_ready=True)
+    ck2 = B.alloc_block_ckpt(desc2, DEV)
+    desc1 = B.make_block_desc(Bn, S, d, H, 128, f, f_ld, r, eps=EPS, stat_y_out=ck2["s1"])
+    y1, ck1 = B.lr_block_fwd(desc1, p1, x)
+    y2, _ = B.lr_block_fwd(desc2, p2, y1, ckpt=ck2)
+    dx2, g2 = B.lr_block_bwd(desc2, p2, y1, dy, ck2)
+    torch.cuda.synchronize()
+    X2 = si.f64(y1)                                   # block 2's input as stored
+    check("s1 of block 2", ck2["s1"], orc.rms_stat(X2), torch.bfloat16, floor=0.0)
+    P2 = _oracle_params(case2["params"])
+    DY = si.f64(case1["dy"])
+    y_ref, _ = orc.block_fwd(X2, P2, Bn, S, H, 128, EPS)
+    dx_ref, g_ref = orc.block_bwd(X2, P2, DY, Bn, S, H, 128, EPS)
+    check("y2", y2, y_ref, torch.bfloat16, floor=FL)
+    check("dx2", dx2, dx_ref, torch.bfloat16, floor=FL)
+    got = _unpack_grads(g2, f, r)
+    for name in ("wd_q", "wu_k", "wd_g", "gamma1"):
+        check("d" + name, got[name], g_ref[name], torch.bfloat16, floor=FLW)
+
+
 def test_block_accumulate_and_determinism():
     Bn, S, H, f, r = 2, 128, 1, 256, 32
     d = 128
