@@ -10,12 +10,16 @@
 // leaving registers: the 32x32 accumulator layout (lane = column, 16 rows in 4-row groups) is, up
 // to a fixed permutation of the k slots that the V^T loads follow, the B-operand layout.
 //
-// Backward is two kernels, both free of atomics and therefore deterministic:
-//   dq kernel  - same walk as the forward (workgroup owns queries, streams keys):
-//                S^T, dP^T = V dO^T, dS^T = P^T*(dP^T - D), dQ^T += K^T dS^T
+// Backward, free of atomics and therefore deterministic, with D[q] = sum_h dO[q,h] O[q,h] and
+// lse * log2(e) from a small preprocessing kernel:
 //   dkv kernel - workgroup owns 128 keys, streams 64-query tiles from the diagonal on:
-//                S = Q K^T, dP = dO V^T, dV^T += dO^T P, dK^T += Q^T dS
-// with D[q] = sum_h dO[q,h] O[q,h] and lse * log2(e) from a small preprocessing kernel.
+//                S = Q K^T, dP = dO V^T, dV^T += dO^T P, dK^T += Q^T dS;
+//                in its usual form it also stores scale * dS^T (bf16, [key][query] per (batch, head)),
+//                and dQ = (scale dS^T)^T K is then one causal k-major GEMM (gemm_bf16.hip): the scores
+//                are formed once, 5 GEMM units in all
+//   dq kernel  - the form without that workspace (S not a multiple of 8, or too large): same walk as the
+//                forward (workgroup owns queries, streams keys): S^T, dP^T = V dO^T,
+//                dS^T = P^T*(dP^T - D), dQ^T += K^T dS^T; 7 units together with the dkv kernel
 #include "common.h"
 
 namespace lrb {

@@ -3,7 +3,9 @@
 // Two operand forms.  k-contiguous ("NT": the forward projections x.W^T, and the data-gradient GEMMs
 // after the small weight matrices have been transposed once): slices land in LDS as [row][k] and the
 // MFMA operands are plain 16-byte reads.  k-major (weight gradients, which reduce over tokens): slices
-// land as [k][column] and the operands are gathered with the LDS transpose read.
+// land as [k][column] and the operands are gathered with the LDS transpose read.  The k-major form with
+// a plain bf16 store, batched with two-level strides and with the k range of a row tile cut at its last
+// row, also computes the attention's query gradient from the stored score gradient.
 //
 // Work decomposition: one workgroup owns a BM x BN output tile, WM x WN wavefronts each own a
 // (BM/WM) x (BN/WN) sub-tile built from 32x32x16 MFMA blocks (256x256 by 8 wavefronts, two per SIMD,
@@ -11,9 +13,10 @@
 // (buffer_load ... lds, no register staging, whole 128-byte cache lines per row) through a ring of
 // three A slots and two B slots, one workgroup barrier per slice, the loads of a slice spread over
 // its four k16 steps; the 16-byte chunk index of a row is XOR-swizzled so that the MFMA-operand reads
-// spread over all banks.  The accumulator tile leaves through LDS as well, so that every global access
-// of the epilogue (C, the auxiliary tiles it reads, the secondary output) is a row-contiguous 16-byte
-// vector.  Workgroups map to tiles XCD by XCD in compact panels and all walk k front to back, so that
+// spread over all banks.  The accumulator tile (held transposed: the MFMAs are issued with their
+// operands exchanged) leaves through LDS as well, so that every global access of the epilogue (C, the
+// auxiliary tiles it reads, the secondary output) is a row-contiguous 16-byte vector through a per-tile
+// buffer resource, without branches.  Workgroups map to tiles XCD by XCD in compact panels and all walk k front to back, so that
 // the tiles resident in one XCD share operand slices in its L2.
 #include <type_traits>
 #include <vector>

@@ -2,6 +2,10 @@
 // forward / backward, transposes and the small reductions that finish weight gradients.
 // bf16 tensors move as 16-byte vectors (8 elements per lane, 1 KB per wavefront instruction);
 // fp32 tensors (precision path, arbitrary sizes) move element-wise.  All arithmetic is fp32.
+// The forms the block uses (dense bf16 tensors, rows of at most 4096 elements) reach memory through
+// buffer resources sized to what a workgroup or a row owns, so that they need no bounds branches: with
+// a test per vector the compiler puts a full memory wait inside every branch and a lane's loads go one
+// round trip after the other.  Also here: the rotary embedding and the LaX variant's rank-r sum.
 #include "epilogue.h"
 
 namespace lrb {
