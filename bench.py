@@ -103,6 +103,8 @@ def main():
     ap.add_argument("--steps", type=int, default=8)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="block-7B", choices=list(WORKLOADS))
+    ap.add_argument("--no-mfma-probe", action="store_true",
+                    help="skip the register-only MFMA rate measurement reported beside the roofline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--ablation", action="store_true",
                     help="add an 'ablation' object: grouped / batched projections and the statistic taken "
@@ -202,6 +204,13 @@ def main():
                 "launches_per_step": round(launches_per_step, 1), "avg_launch_us": round(avg_launch_ms * 1e3, 2),
                 "gemm_ms_per_step": round(gemm_ms / max(args.steps, 1), 3),
                 "gflop_per_launch": round(flops_per_launch / 1e9, 2)}
+    # What the matrix pipes of THIS box sustain from registers alone with pseudo-random operands (no
+    # memory traffic at all; the chip lowers its clock under matrix load): the ceiling an ideal GEMM
+    # kernel would reach here.  `frac` above stays against the published peak.
+    if not args.no_mfma_probe:
+        sustained = B.lr_mfma_probe(True, 20000, 20)
+        roofline["machine_sustained"] = round(sustained, 1)
+        roofline["frac_of_machine_sustained"] = round(achieved / sustained, 4)
 
     # ---- the memory-bound kernels against the HBM peak (fp32 statistic / bf16 tensors >= 0.5 GB so that
     # the 256 MB last-level cache cannot hold them)

@@ -225,6 +225,15 @@ int lr_attention_bwd(const void* q, const void* k, const void* v, const void* o,
  * the same quantity per linear layer: kernel time and utilisation).                        */
 int lr_gemm_timer_begin(int max_launches);
 int lr_gemm_timer_end(double* total_ms, int* launches);
+/* Sustained rate of the bf16 matrix pipes fed from registers alone (no LDS, no memory traffic):
+ * 2048 wavefronts, 8 independent 32x32x16 accumulator tiles each, iters instructions per tile and
+ * launch, `launches` timed launches after up to 4 untimed ones, on `stream`; *tflops (HOST pointer)
+ * receives the rate.  random_operands = 0 uses smooth operand values, otherwise pseudo-random ones in
+ * (-1, 1): the clock the chip holds under matrix load depends on how much the operand bits toggle,
+ * so the second figure is the ceiling for a GEMM on trained-weight-like data.  Creates and destroys
+ * two HIP events and waits for the launches.  iters in 1..2^20, launches in 1..1000, else
+ * LR_EINVAL.  The utilisation of Sec. 5.3 is read against this figure and the published peak.    */
+int lr_mfma_probe(int random_operands, int iters, int launches, double* tflops, void* stream);
 
 /* ---- standalone memory-bound kernels: the unfused twins of the fused epilogues ---------- */
 /* stat[t] = sum_j x[t,j]^2  (Alg. 1 line 1).                                               */

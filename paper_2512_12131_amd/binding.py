@@ -80,6 +80,7 @@ _SIGS = {
                                 _vp, _sz, _vp]),
     "lr_gemm_timer_begin": (_int, [_int]),
     "lr_gemm_timer_end": (_int, [C.POINTER(C.c_double), C.POINTER(_int)]),
+    "lr_mfma_probe": (_int, [_int, _int, _int, C.POINTER(C.c_double), _vp]),
     "lr_rms_stat": (_int, [_vp, _i64, _vp, _i64, _i64, _int, _vp]),
     "lr_rmsnorm_apply": (_int, [_vp, _i64, _vp, _vp, _f32, _vp, _i64, _i64, _i64, _int, _vp]),
     "lr_rmsnorm_bwd_parts": (_i64, [_i64]),
@@ -383,6 +384,13 @@ def lr_gemm_timer_end():
     ms, n = C.c_double(0.0), C.c_int(0)
     _check(lib().lr_gemm_timer_end(C.byref(ms), C.byref(n)), "lr_gemm_timer_end")
     return ms.value, n.value
+
+
+def lr_mfma_probe(random_operands=True, iters=20000, launches=20):
+    """TFLOP/s the bf16 matrix pipes sustain from registers alone (waits for its own launches)."""
+    tf = C.c_double(0.0)
+    _check(lib().lr_mfma_probe(int(bool(random_operands)), iters, launches, C.byref(tf), _stream()), "lr_mfma_probe")
+    return tf.value
 
 
 # ---- standalone memory-bound kernels ---------------------------------------------------------

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblrboost.so")
 OBJ_DIR = os.path.join(HERE, "_build")
-SOURCES = ["api.hip", "gemm_bf16.hip", "gemm_f32.hip", "stream_kernels.hip", "attention.hip"]
+SOURCES = ["api.hip", "gemm_bf16.hip", "gemm_f32.hip", "stream_kernels.hip", "attention.hip", "probe.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -100,6 +100,16 @@ def test_rope_arguments_are_checked_on_the_host():
     assert lib.lr_block_workspace_bytes(C.byref(d), 0) == 0
 
 
+def test_mfma_probe_arguments_are_checked_on_the_host():
+    f = B.lib().lr_mfma_probe
+    tf = C.c_double(0.0)
+    assert f(1, 100, 1, None, None) == -1            # nowhere to put the result
+    assert f(1, 0, 1, C.byref(tf), None) == -1
+    assert f(1, 100, 0, C.byref(tf), None) == -1
+    assert f(1, (1 << 20) + 1, 1, C.byref(tf), None) == -1
+    assert f(1, 100, 1001, C.byref(tf), None) == -1
+
+
 def test_workspace_queries_scale_and_reject():
     lib = B.lib()
     a = lib.lr_group_workspace_bytes(3, 1024, 256, 64, 256, 1, 0)
