@@ -103,6 +103,8 @@ def main():
     ap.add_argument("--steps", type=int, default=8)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="block-7B", choices=list(WORKLOADS))
+    ap.add_argument("--graph", action="store_true",
+                    help="record the step into a HIP graph after the warm-up and time replays of it")
     ap.add_argument("--no-mfma-probe", action="store_true",
                     help="skip the register-only MFMA rate measurement reported beside the roofline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -169,9 +171,19 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    run = step
+    if args.graph:
+        # the step's launches recorded once into a HIP graph (the library only launches kernels on the
+        # stream it is given), replayed per timed step: takes the host's launch cost out of small shapes
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        run = graph.replay
+        run()
+        torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        run()
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / max(args.steps, 1)
 
@@ -326,6 +338,7 @@ def main():
                                f"{' + rank-r residual from the layer below (LaX)' if variant == 'lax' else ''}"
                                f"{', rotary embedding of q and k' if variant == 'rope' else ''}, "
                                f"rank-r checkpoint recompute",
+                   "launch": "hip graph replay" if args.graph else "eager",
                    "tokens": T, "executed_tflop": round(fl["exec"] / 1e12, 3),
                    "model_tflop": round(fl["model"] / 1e12, 3),
                    "frac_mfma_peak_executed": round(value / MFMA_BF16_PEAK_TFLOPS, 4),
