@@ -216,6 +216,23 @@ int lr_attention_bwd(const void* q, const void* k, const void* v, const void* o,
                      int64_t ld, int64_t B, int64_t S, int64_t H, int64_t hd, int causal,
                      int dt, void* ws, size_t ws_bytes, void* stream);
 
+/* Grouped-query form (the extension named in the section "Discussion and Future Work": only the
+ * shapes of the K and V projections change).  Hkv key / value heads, H % Hkv == 0; query head h
+ * attends over key / value head h / (H / Hkv).  q, o, dout, dq: [B*S, ld] with H heads of hd columns;
+ * k, v, dk, dv: [B*S, ldkv] with Hkv heads; lse [B, H, S].  dk and dv are the sums over the query
+ * heads of each group.  Same restrictions and error behaviour as the multi-head calls, which are the
+ * case Hkv = H, ldkv = ld; for Hkv < H the backward workspace additionally holds one dK and one dV
+ * contribution per query head (2 * B*S*H*hd bf16), added up by a last kernel.               */
+int lr_attention_gqa_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
+                         int64_t ld, int64_t ldkv, int64_t B, int64_t S, int64_t H, int64_t Hkv,
+                         int64_t hd, int causal, int dt, void* stream);
+size_t lr_attention_gqa_bwd_workspace_bytes(int64_t B, int64_t S, int64_t H, int64_t Hkv,
+                                            int64_t hd);
+int lr_attention_gqa_bwd(const void* q, const void* k, const void* v, const void* o,
+                         const void* dout, const float* lse, void* dq, void* dk, void* dv,
+                         int64_t ld, int64_t ldkv, int64_t B, int64_t S, int64_t H, int64_t Hkv,
+                         int64_t hd, int causal, int dt, void* ws, size_t ws_bytes, void* stream);
+
 /* ---- measurement aid (not on the compute path) ------------------------------------------ */
 /* Between begin and end every bf16 MFMA GEMM launch the library makes is bracketed by two HIP
  * events on its stream; end waits for the last one and returns the summed kernel time (HOST

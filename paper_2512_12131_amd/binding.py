@@ -78,6 +78,10 @@ _SIGS = {
     "lr_attention_bwd_workspace_bytes": (_sz, [_i64, _i64, _i64, _i64]),
     "lr_attention_bwd": (_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _int, _int,
                                 _vp, _sz, _vp]),
+    "lr_attention_gqa_fwd": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _i64, _i64, _int, _int, _vp]),
+    "lr_attention_gqa_bwd_workspace_bytes": (_sz, [_i64, _i64, _i64, _i64, _i64]),
+    "lr_attention_gqa_bwd": (_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _i64, _i64,
+                                    _int, _int, _vp, _sz, _vp]),
     "lr_gemm_timer_begin": (_int, [_int]),
     "lr_gemm_timer_end": (_int, [C.POINTER(C.c_double), C.POINTER(_int)]),
     "lr_mfma_probe": (_int, [_int, _int, _int, C.POINTER(C.c_double), _vp]),
@@ -371,6 +375,28 @@ def lr_attention_bwd(q, k, v, o, dout, lse, B, S, H, hd, causal=True):
     ws = _ws(nb, q.device)
     _check(lib().lr_attention_bwd(_p(q), _p(k), _p(v), _p(o), _p(dout), _p(lse), _p(dq), _p(dk), _p(dv), _rowmajor(q),
                                   B, S, H, hd, int(causal), _dt(q), _p(ws), ws.numel(), _stream()), "lr_attention_bwd")
+    return dq, dk, dv
+
+
+def lr_attention_gqa_fwd(q, k, v, B, S, H, Hkv, hd, causal=True):
+    """q [B*S, >= H*hd], k and v [B*S, >= Hkv*hd] (k and v with the same row stride)."""
+    o = torch.empty_like(q)
+    lse = torch.empty((B, H, S), dtype=torch.float32, device=q.device)
+    assert _rowmajor(k) == _rowmajor(v)
+    _check(lib().lr_attention_gqa_fwd(_p(q), _p(k), _p(v), _p(o), _p(lse), _rowmajor(q), _rowmajor(k), B, S, H, Hkv, hd,
+                                      int(causal), _dt(q), _stream()), "lr_attention_gqa_fwd")
+    return o, lse
+
+
+def lr_attention_gqa_bwd(q, k, v, o, dout, lse, B, S, H, Hkv, hd, causal=True):
+    assert _rowmajor(k) == _rowmajor(v)
+    dq = torch.empty_like(q)
+    dk, dv = (torch.empty_strided(k.shape, k.stride(), dtype=k.dtype, device=k.device) for _ in range(2))   # rows of ldkv
+    nb = lib().lr_attention_gqa_bwd_workspace_bytes(B, S, H, Hkv, hd)
+    ws = _ws(nb, q.device)
+    _check(lib().lr_attention_gqa_bwd(_p(q), _p(k), _p(v), _p(o), _p(dout), _p(lse), _p(dq), _p(dk), _p(dv), _rowmajor(q),
+                                      _rowmajor(k), B, S, H, Hkv, hd, int(causal), _dt(q), _p(ws), ws.numel(), _stream()),
+           "lr_attention_gqa_bwd")
     return dq, dk, dv
 
 

@@ -873,6 +873,44 @@ int lr_attention_bwd(const void* q, const void* k, const void* v, const void* o,
   return e == hipSuccess ? LR_OK : (e == hipErrorNotSupported ? LR_EUNSUPPORTED : LR_ELAUNCH);
 }
 
+// grouped-query attention: H query heads over Hkv key / value heads
+static int check_attn_gqa(int64_t ld, int64_t ldkv, int64_t B, int64_t S, int64_t H, int64_t Hkv, int64_t hd, int causal,
+                          int dt) {
+  if (Hkv <= 0 || H <= 0 || H % Hkv != 0 || hd <= 0 || ldkv < Hkv * hd) return LR_EINVAL;
+  TRY(check_attn(ld, B, S, H, hd, causal, dt));
+  if (S * ldkv * 2 >= 0x7fffffffLL) return LR_EUNSUPPORTED;
+  if (ldkv % 8) return LR_EALIGN;
+  return LR_OK;
+}
+
+int lr_attention_gqa_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int64_t ld, int64_t ldkv,
+                         int64_t B, int64_t S, int64_t H, int64_t Hkv, int64_t hd, int causal, int dt, void* stream) {
+  TRY(check_attn_gqa(ld, ldkv, B, S, H, Hkv, hd, causal, dt));
+  TRY(check_ptrs(LR_BF16, {q, k, v, o}));
+  if (!lse) return LR_EINVAL;
+  hipError_t e = attention_gqa_fwd_bf16(q, k, v, o, lse, ld, ldkv, (int)B, (int)S, (int)H, (int)Hkv, (int)hd, causal,
+                                        (hipStream_t)stream);
+  return e == hipSuccess ? LR_OK : (e == hipErrorNotSupported ? LR_EUNSUPPORTED : LR_ELAUNCH);
+}
+
+size_t lr_attention_gqa_bwd_workspace_bytes(int64_t B, int64_t S, int64_t H, int64_t Hkv, int64_t hd) {
+  if (B <= 0 || S <= 0 || H <= 0 || Hkv <= 0 || H % Hkv != 0 || hd != 128) return 0;
+  if (B * S > 0x7fffffffLL || B * H > 0x7fffffffLL) return 0;
+  return attention_gqa_bwd_ws_bytes((int)B, (int)S, (int)H, (int)Hkv, (int)hd) + 256;
+}
+
+int lr_attention_gqa_bwd(const void* q, const void* k, const void* v, const void* o, const void* dout, const float* lse,
+                         void* dq, void* dk, void* dv, int64_t ld, int64_t ldkv, int64_t B, int64_t S, int64_t H,
+                         int64_t Hkv, int64_t hd, int causal, int dt, void* ws, size_t ws_bytes, void* stream) {
+  TRY(check_attn_gqa(ld, ldkv, B, S, H, Hkv, hd, causal, dt));
+  TRY(check_ptrs(LR_BF16, {q, k, v, o, dout, dq, dk, dv}));
+  if (!lse) return LR_EINVAL;
+  TRY(check_ws(ws, ws_bytes, lr_attention_gqa_bwd_workspace_bytes(B, S, H, Hkv, hd)));
+  hipError_t e = attention_gqa_bwd_bf16(q, k, v, o, dout, lse, dq, dk, dv, ld, ldkv, (int)B, (int)S, (int)H, (int)Hkv,
+                                        (int)hd, causal, ws, (hipStream_t)stream);
+  return e == hipSuccess ? LR_OK : (e == hipErrorNotSupported ? LR_EUNSUPPORTED : LR_ELAUNCH);
+}
+
 // ---- rotary position embedding -------------------------------------------------------------------
 int lr_rope(void* x, int64_t ldx, const float* cos_tab, const float* sin_tab, int64_t B, int64_t S, int64_t H,
             int64_t hd, int inverse, int dt, void* stream) {

@@ -20,6 +20,12 @@
 //   dq kernel  - the form without that workspace (S not a multiple of 8, or too large): same walk as the
 //                forward (workgroup owns queries, streams keys): S^T, dP^T = V dO^T,
 //                dS^T = P^T*(dP^T - D), dQ^T += K^T dS^T; 7 units together with the dkv kernel
+//
+// Grouped-query form (fewer key / value heads than query heads, H / Hkv consecutive query heads per
+// key / value head): the same kernels with K and V addressed by head / group and their own row stride.
+// The dkv kernel then writes one dK and one dV contribution per query head into the workspace and a
+// last kernel adds up each group; the dQ GEMM runs per batch element with (key / value head, head in
+// group) as its two batch levels.  Multi-head attention is the case of groups of one.
 #include "common.h"
 
 namespace lrb {
@@ -231,7 +237,8 @@ constexpr int FWD_LDS = 4 * TILE_BYTES;   // K and V, double buffered
 template <int MB>
 __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                                                        const uint16_t* __restrict__ v, uint16_t* __restrict__ o,
-                                                       float* __restrict__ lse, int64_t ld, int S, int H, float scale) {
+                                                       float* __restrict__ lse, int64_t ld, int64_t ldkv, int grp, int S,
+                                                       int H, float scale) {
   static_assert(MB == 1, "one 32-query block per wavefront");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int BQ = 4 * MB * 32;
@@ -244,13 +251,15 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const uint16_t* __rest
   const int head = wg.head, b = wg.b;
   const int64_t tok0 = (int64_t)b * S;
   const uint16_t* qb = q + tok0 * ld + head * HD;
-  const rsrc_t rsK = tile_rsrc(k + tok0 * ld + head * HD);
-  const rsrc_t rsV = tile_rsrc(v + tok0 * ld + head * HD);
+  // grouped-query attention: grp consecutive query heads share key / value head head / grp (rows of ldkv)
+  const int kvh = head / grp;
+  const rsrc_t rsK = tile_rsrc(k + tok0 * ldkv + kvh * HD);
+  const rsrc_t rsV = tile_rsrc(v + tok0 * ldkv + kvh * HD);
   const float c = scale * LOG2E;
   uint32_t offK[4], offV[4];
   int rowK[4], rowV[4];
-  dma_lane_offsets<SWZ_ROW16, 4>(offK, rowK, ld, wave, lane);
-  dma_lane_offsets<SWZ_ROW4, 4>(offV, rowV, ld, wave, lane);
+  dma_lane_offsets<SWZ_ROW16, 4>(offK, rowK, ldkv, wave, lane);
+  dma_lane_offsets<SWZ_ROW4, 4>(offV, rowV, ldkv, wave, lane);
   unsigned char* sK = smem;                              // 2 tiles
   unsigned char* sV = smem + 2 * TILE_BYTES;             // 2 tiles
 
@@ -277,16 +286,16 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(const uint16_t* __rest
   const int kv_end = min(S, q0 + BQ);                    // causal: keys up to the block's last query
   const int ntiles = (kv_end + KT - 1) / KT;
 
-  dma_tile(rsK, sK, offK, rowK, 0, S, ld, wave_s);
-  dma_tile(rsV, sV, offV, rowV, 0, S, ld, wave_s);
+  dma_tile(rsK, sK, offK, rowK, 0, S, ldkv, wave_s);
+  dma_tile(rsV, sV, offV, rowV, 0, S, ldkv, wave_s);
   wait_vm0();
   __syncthreads();
 
   for (int j = 0; j < ntiles; j++) {
     const int cur = j & 1;
     if (j + 1 < ntiles) {                                // next tiles land while this one is worked on
-      dma_tile(rsK, sK + (cur ^ 1) * TILE_BYTES, offK, rowK, (j + 1) * KT, S, ld, wave_s);
-      dma_tile(rsV, sV + (cur ^ 1) * TILE_BYTES, offV, rowV, (j + 1) * KT, S, ld, wave_s);
+      dma_tile(rsK, sK + (cur ^ 1) * TILE_BYTES, offK, rowK, (j + 1) * KT, S, ldkv, wave_s);
+      dma_tile(rsV, sV + (cur ^ 1) * TILE_BYTES, offV, rowV, (j + 1) * KT, S, ldkv, wave_s);
     }
     const int key0 = j * KT;
     const unsigned char* sKc = sK + cur * TILE_BYTES;
@@ -436,7 +445,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const uint16_t* __rest
                                                           const uint16_t* __restrict__ v,
                                                           const uint16_t* __restrict__ dout,
                                                           const float* __restrict__ lse2, const float* __restrict__ D,
-                                                          uint16_t* __restrict__ dq, int64_t ld, int S, int H,
+                                                          uint16_t* __restrict__ dq, int64_t ld, int64_t ldkv, int grp, int S, int H,
                                                           float scale) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int BQ = 4 * MB * 32;
@@ -450,11 +459,12 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const uint16_t* __rest
   const float c = scale * LOG2E;
   // K is needed row-wise (S^T) and transposed (dQ^T), V row-wise (dP^T): one LDS copy each, in the
   // swizzle that serves both reads, written by direct-to-LDS loads.
-  const rsrc_t rsK = tile_rsrc(k + tok0 * ld + hoff);
-  const rsrc_t rsV = tile_rsrc(v + tok0 * ld + hoff);
+  const int64_t kvoff = (head / grp) * HD;     // the key / value head this query head's group shares
+  const rsrc_t rsK = tile_rsrc(k + tok0 * ldkv + kvoff);
+  const rsrc_t rsV = tile_rsrc(v + tok0 * ldkv + kvoff);
   uint32_t offT[4];
   int rowT[4];
-  dma_lane_offsets<SWZ_BOTH, 4>(offT, rowT, ld, wave, lane);
+  dma_lane_offsets<SWZ_BOTH, 4>(offT, rowT, ldkv, wave, lane);
   // one query block from the late end and its mirror image from the early end: equal work per workgroup
   for (int pass = 0; pass < 2; pass++) {
   const int qblk = pass == 0 ? nqb - 1 - wg.x : wg.x;
@@ -487,16 +497,16 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(const uint16_t* __rest
   constexpr int STAGE = 2 * TILE_BYTES;                  // K, V
   const int kv_end = min(S, q0 + BQ);
   const int ntiles = (kv_end + KT - 1) / KT;
-  dma_tile<4>(rsK, smem, offT, rowT, 0, S, ld, wave);
-  dma_tile<4>(rsV, smem + TILE_BYTES, offT, rowT, 0, S, ld, wave);
+  dma_tile<4>(rsK, smem, offT, rowT, 0, S, ldkv, wave);
+  dma_tile<4>(rsV, smem + TILE_BYTES, offT, rowT, 0, S, ldkv, wave);
   wait_vm0();
   __syncthreads();
 
   for (int j = 0; j < ntiles; j++) {
     const int cur = j & 1;
     if (j + 1 < ntiles) {                                // lands while this tile is worked on
-      dma_tile<4>(rsK, smem + (cur ^ 1) * STAGE, offT, rowT, (j + 1) * KT, S, ld, wave);
-      dma_tile<4>(rsV, smem + (cur ^ 1) * STAGE + TILE_BYTES, offT, rowT, (j + 1) * KT, S, ld, wave);
+      dma_tile<4>(rsK, smem + (cur ^ 1) * STAGE, offT, rowT, (j + 1) * KT, S, ldkv, wave);
+      dma_tile<4>(rsV, smem + (cur ^ 1) * STAGE + TILE_BYTES, offT, rowT, (j + 1) * KT, S, ldkv, wave);
     }
     const unsigned char* sK = smem + cur * STAGE;
     const unsigned char* sVb = sK + TILE_BYTES;
@@ -588,7 +598,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const uint16_t* __res
                                                            const uint16_t* __restrict__ dout,
                                                            const float* __restrict__ lse2, const float* __restrict__ D,
                                                            uint16_t* __restrict__ dk, uint16_t* __restrict__ dv,
-                                                           uint16_t* __restrict__ dst, int64_t ld, int S, int H,
+                                                           uint16_t* __restrict__ dst, int64_t ld, int64_t ldkv, int64_t lddkv, int grp, int S, int H,
                                                            float scale) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int BN = 4 * NB * 32;
@@ -656,8 +666,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const uint16_t* __res
 
   // K and V rows of this wavefront stay in registers (B operands).
   bf16x8 kf[NB][8], vf[NB][8];
-  load_row_frags<NB>(kf, k + tok0 * ld + hoff, ld, nw0, S, lane);
-  load_row_frags<NB>(vf, v + tok0 * ld + hoff, ld, nw0, S, lane);
+  // (grouped-query attention: the group's shared key / value head, rows of ldkv; dk and dv below are
+  // this query head's contribution, laid out like q)
+  load_row_frags<NB>(kf, k + tok0 * ldkv + (head / grp) * HD, ldkv, nw0, S, lane);
+  load_row_frags<NB>(vf, v + tok0 * ldkv + (head / grp) * HD, ldkv, nw0, S, lane);
 
   f32x16 akv[2][NB][4];                                    // [0] = dK^T, [1] = dV^T
 #pragma unroll
@@ -777,11 +789,35 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const uint16_t* __res
   for (int nb = 0; nb < NB; nb++) {
     const int ni = nw0 + nb * 32 + (lane & 31);
     if (ni < S) {
-      store_acc_T(dk + (tok0 + ni) * ld + hoff, akv[0][nb], WRITE_DS ? 1.f : scale, lane);
-      store_acc_T(dv + (tok0 + ni) * ld + hoff, akv[1][nb], 1.f, lane);
+      store_acc_T(dk + (tok0 + ni) * lddkv + hoff, akv[0][nb], WRITE_DS ? 1.f : scale, lane);
+      store_acc_T(dv + (tok0 + ni) * lddkv + hoff, akv[1][nb], 1.f, lane);
     }
   }
   }  // pass
+}
+
+// Grouped-query attention: a key / value head's gradient is the sum of the contributions of the grp
+// query heads that share it.  part: two [T, H * HD] bf16 tensors (dK, then dV contributions, one per
+// query head), out: dk / dv [T, ldkv].  One thread adds grp 16-byte vectors in fp32.
+__global__ __launch_bounds__(256) void attn_group_sum_kernel(const uint16_t* __restrict__ part, int64_t part_elems,
+                                                             uint16_t* __restrict__ dk, uint16_t* __restrict__ dv,
+                                                             int64_t ldkv, int grp, int H, int64_t T) {
+  const int Hkv = H / grp;
+  const int64_t item = (int64_t)blockIdx.x * 256 + threadIdx.x;   // (token, kv head, 16-byte chunk)
+  if (item >= T * Hkv * (HD / 8)) return;
+  const int ch = (int)(item % (HD / 8));
+  const int kvh = (int)((item / (HD / 8)) % Hkv);
+  const int64_t t = item / ((int64_t)(HD / 8) * Hkv);
+  const uint16_t* src = part + (int64_t)blockIdx.y * part_elems + t * ((int64_t)H * HD) + (int64_t)kvh * grp * HD + ch * 8;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  for (int g = 0; g < grp; g++) {
+    float v[8];
+    unpack8(*reinterpret_cast<const uint4*>(src + g * HD), v);
+#pragma unroll
+    for (int e = 0; e < 8; e++) acc[e] += v[e];
+  }
+  uint16_t* dst = (blockIdx.y == 0 ? dk : dv) + t * ldkv + kvh * HD + ch * 8;
+  *reinterpret_cast<uint4*>(dst) = pack8(acc);
 }
 
 template <class K>
@@ -793,8 +829,17 @@ hipError_t set_lds(K kern, int bytes) {
 
 hipError_t attention_fwd_bf16(const void* q, const void* k, const void* v, void* o, float* lse, int64_t ld, int B,
                               int S, int H, int hd, int causal, hipStream_t st) {
+  return attention_gqa_fwd_bf16(q, k, v, o, lse, ld, ld, B, S, H, H, hd, causal, st);
+}
+
+// Hkv key / value heads (rows of ldkv elements) serve H query heads, H / Hkv consecutive ones each.
+hipError_t attention_gqa_fwd_bf16(const void* q, const void* k, const void* v, void* o, float* lse, int64_t ld,
+                                  int64_t ldkv, int B, int S, int H, int Hkv, int hd, int causal, hipStream_t st) {
   if (hd != HD || !causal) return hipErrorNotSupported;
-  if ((int64_t)S * ld * 2 >= (int64_t)0x7fffffff) return hipErrorNotSupported;   // 32-bit buffer offsets per (batch, head)
+  if (Hkv <= 0 || H % Hkv != 0) return hipErrorInvalidValue;
+  const int grp = H / Hkv;
+  // 32-bit buffer offsets per (batch, head)
+  if ((int64_t)S * ld * 2 >= (int64_t)0x7fffffff || (int64_t)S * ldkv * 2 >= (int64_t)0x7fffffff) return hipErrorNotSupported;
   constexpr int MB = 1;
   constexpr int BQ = 4 * MB * 32;
   static bool once = false;
@@ -806,7 +851,7 @@ hipError_t attention_fwd_bf16(const void* q, const void* k, const void* v, void*
   const int nqb = (S + BQ - 1) / BQ;
   dim3 grid((nqb + 1) / 2, H, B);                        // each workgroup: one query block and its mirror
   hipLaunchKernelGGL(attn_fwd_kernel<MB>, grid, dim3(256), FWD_LDS, st, (const uint16_t*)q, (const uint16_t*)k,
-                     (const uint16_t*)v, (uint16_t*)o, lse, ld, S, H, 1.f / sqrtf((float)hd));
+                     (const uint16_t*)v, (uint16_t*)o, lse, ld, ldkv, grp, S, H, 1.f / sqrtf((float)hd));
   return hipGetLastError();
 }
 
@@ -819,9 +864,13 @@ static bool keep_ds(int B, int S, int H) {
   return S % 8 == 0 && (int64_t)S * S * 2 < (int64_t)0x7fffffff && (size_t)B * H * S * S * 2 <= DS_WS_CAP;
 }
 // D and the base-2 exponent offsets lse * log2(e), both [B, H, S] fp32; then dS^T [B, H, S, S] bf16
-size_t attention_bwd_ws_bytes(int B, int S, int H, int hd) {
+size_t attention_bwd_ws_bytes(int B, int S, int H, int hd) { return attention_gqa_bwd_ws_bytes(B, S, H, H, hd); }
+// ... and, with fewer key / value heads than query heads, the per-query-head contributions to dK and dV
+// (two [B * S, H * hd] bf16 tensors) that a last kernel adds up group by group
+static size_t ds_bytes(int B, int S, int H) { return keep_ds(B, S, H) ? ((size_t)B * H * S * S * 2 + 255) / 256 * 256 : 0; }
+size_t attention_gqa_bwd_ws_bytes(int B, int S, int H, int Hkv, int hd) {
   const size_t small = (2 * (size_t)B * H * S * sizeof(float) + 255) / 256 * 256;
-  return small + (keep_ds(B, S, H) ? (size_t)B * H * S * S * 2 : 0);
+  return small + ds_bytes(B, S, H) + (Hkv < H ? 2 * (size_t)B * S * H * HD * 2 : 0);
 }
 
 constexpr int DQ_MB = 2;    // 32-query blocks per wavefront in the dQ kernel
@@ -830,8 +879,17 @@ constexpr int DKV_NB = 1;   // 32-key blocks per wavefront in the dK/dV kernel
 hipError_t attention_bwd_bf16(const void* q, const void* k, const void* v, const void* o, const void* dout,
                               const float* lse, void* dq, void* dk, void* dv, int64_t ld, int B, int S, int H, int hd,
                               int causal, void* ws, hipStream_t st) {
+  return attention_gqa_bwd_bf16(q, k, v, o, dout, lse, dq, dk, dv, ld, ld, B, S, H, H, hd, causal, ws, st);
+}
+
+hipError_t attention_gqa_bwd_bf16(const void* q, const void* k, const void* v, const void* o, const void* dout,
+                                  const float* lse, void* dq, void* dk, void* dv, int64_t ld, int64_t ldkv, int B, int S,
+                                  int H, int Hkv, int hd, int causal, void* ws, hipStream_t st) {
   if (hd != HD || !causal) return hipErrorNotSupported;
-  if ((int64_t)S * ld * 2 >= (int64_t)0x7fffffff) return hipErrorNotSupported;   // 32-bit buffer offsets per (batch, head)
+  if (Hkv <= 0 || H % Hkv != 0) return hipErrorInvalidValue;
+  const int grp = H / Hkv;
+  // 32-bit buffer offsets per (batch, head)
+  if ((int64_t)S * ld * 2 >= (int64_t)0x7fffffff || (int64_t)S * ldkv * 2 >= (int64_t)0x7fffffff) return hipErrorNotSupported;
   static bool once = false;
   if (!once) {
     hipError_t e = set_lds(attn_bwd_dq_kernel<DQ_MB>, DQ_LDS);
@@ -849,30 +907,61 @@ hipError_t attention_bwd_bf16(const void* q, const void* k, const void* v, const
                      (const uint16_t*)dout, (const uint16_t*)o, lse, D, lse2, ld, S, H, items);
   const float scale = 1.f / sqrtf((float)hd);
   const dim3 kv_grid(((S + DKV_NB * 128 - 1) / (DKV_NB * 128) + 1) / 2, H, B);
+  const size_t small = (2 * (size_t)items * sizeof(float) + 255) / 256 * 256;
+  // where the dK / dV kernel writes: the outputs themselves, or (fewer key / value heads than query
+  // heads) one contribution per query head, added up at the end
+  const int64_t T = (int64_t)B * S, part_elems = T * H * HD;
+  uint16_t* part = (uint16_t*)((char*)ws + small + ds_bytes(B, S, H));
+  uint16_t* dk_w = grp > 1 ? part : (uint16_t*)dk;
+  uint16_t* dv_w = grp > 1 ? part + part_elems : (uint16_t*)dv;
+  const int64_t lddkv = grp > 1 ? (int64_t)H * HD : ldkv;
+  auto group_sum = [&]() -> hipError_t {
+    if (grp == 1) return hipSuccess;
+    const int64_t n = T * Hkv * (HD / 8);
+    hipLaunchKernelGGL(attn_group_sum_kernel, dim3((unsigned)((n + 255) / 256), 2), dim3(256), 0, st, (const uint16_t*)part,
+                       part_elems, (uint16_t*)dk, (uint16_t*)dv, ldkv, grp, H, T);
+    return hipGetLastError();
+  };
   if (keep_ds(B, S, H)) {
-    uint16_t* dst = (uint16_t*)((char*)ws + (2 * (size_t)items * sizeof(float) + 255) / 256 * 256);
+    uint16_t* dst = (uint16_t*)((char*)ws + small);
     hipLaunchKernelGGL((attn_bwd_dkv_kernel<DKV_NB, true>), kv_grid, dim3(256), DKV_LDS, st, (const uint16_t*)q,
-                       (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)dout, lse2, D, (uint16_t*)dk,
-                       (uint16_t*)dv, dst, ld, S, H, scale);
+                       (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)dout, lse2, D, dk_w, dv_w, dst, ld, ldkv,
+                       lddkv, grp, S, H, scale);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     // dQ[q, :] = sum_key (scale dS^T)[key, q] * K[key, :], per (batch, head): both operands k-major, the
     // key range of a row tile cut at its last query
     GemmOp op;
-    op.A = dst; op.lda = S; op.transA = 1; op.sA = (int64_t)S * S; op.sAo = (int64_t)H * S * S;
-    op.B = k; op.ldb = ld; op.transB = 1; op.sB = HD; op.sBo = (int64_t)S * ld;
-    op.C = dq; op.ldc = ld; op.sC = HD; op.sCo = (int64_t)S * ld;
-    op.M = S; op.N = HD; op.K = S; op.batch = B * H; op.batch_inner = H; op.causal_k = 1;
+    op.lda = S; op.transA = 1; op.ldb = ldkv; op.transB = 1; op.ldc = ld;
+    op.M = S; op.N = HD; op.K = S; op.causal_k = 1;
     op.epi.kind = EPI_STORE;
-    return gemm_bf16_untimed(op, st);
+    if (grp == 1) {   // one launch: batch index = (batch element, head)
+      op.A = dst; op.sA = (int64_t)S * S; op.sAo = (int64_t)H * S * S;
+      op.B = k; op.sB = HD; op.sBo = (int64_t)S * ldkv;
+      op.C = dq; op.sC = HD; op.sCo = (int64_t)S * ld;
+      op.batch = B * H; op.batch_inner = H;
+      return gemm_bf16_untimed(op, st);
+    }
+    // one launch per batch element: batch index = (key / value head, query head inside its group)
+    for (int b = 0; b < B; b++) {
+      op.A = dst + (int64_t)b * H * S * S; op.sA = (int64_t)S * S; op.sAo = (int64_t)grp * S * S;
+      op.B = (const uint16_t*)k + (int64_t)b * S * ldkv; op.sB = 0; op.sBo = HD;
+      op.C = (uint16_t*)dq + (int64_t)b * S * ld; op.sC = HD; op.sCo = (int64_t)grp * HD;
+      op.batch = H; op.batch_inner = grp;
+      e = gemm_bf16_untimed(op, st);
+      if (e != hipSuccess) return e;
+    }
+    return group_sum();
   }
   hipLaunchKernelGGL(attn_bwd_dq_kernel<DQ_MB>, dim3(((S + DQ_MB * 128 - 1) / (DQ_MB * 128) + 1) / 2, H, B), dim3(256), DQ_LDS, st, (const uint16_t*)q,
-                     (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)dout, lse2, D, (uint16_t*)dq, ld, S, H,
-                     scale);
+                     (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)dout, lse2, D, (uint16_t*)dq, ld, ldkv, grp,
+                     S, H, scale);
   hipLaunchKernelGGL((attn_bwd_dkv_kernel<DKV_NB, false>), kv_grid, dim3(256), DKV_LDS, st, (const uint16_t*)q,
-                     (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)dout, lse2, D, (uint16_t*)dk,
-                     (uint16_t*)dv, (uint16_t*)nullptr, ld, S, H, scale);
-  return hipGetLastError();
+                     (const uint16_t*)k, (const uint16_t*)v, (const uint16_t*)dout, lse2, D, dk_w, dv_w,
+                     (uint16_t*)nullptr, ld, ldkv, lddkv, grp, S, H, scale);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return group_sum();
 }
 
 }  // namespace lrb

@@ -130,6 +130,13 @@ size_t attention_bwd_ws_bytes(int B, int S, int H, int hd);
 hipError_t attention_bwd_bf16(const void* q, const void* k, const void* v, const void* o, const void* dout,
                               const float* lse, void* dq, void* dk, void* dv, int64_t ld, int B, int S, int H,
                               int hd, int causal, void* ws, hipStream_t);
+// grouped-query form: Hkv key / value heads (k, v, dk, dv rows of ldkv elements), H % Hkv == 0
+hipError_t attention_gqa_fwd_bf16(const void* q, const void* k, const void* v, void* o, float* lse, int64_t ld,
+                                  int64_t ldkv, int B, int S, int H, int Hkv, int hd, int causal, hipStream_t);
+size_t attention_gqa_bwd_ws_bytes(int B, int S, int H, int Hkv, int hd);
+hipError_t attention_gqa_bwd_bf16(const void* q, const void* k, const void* v, const void* o, const void* dout,
+                                  const float* lse, void* dq, void* dk, void* dv, int64_t ld, int64_t ldkv, int B,
+                                  int S, int H, int Hkv, int hd, int causal, void* ws, hipStream_t);
 
 // ---------------------------------------------------------------------------------------------
 // device helpers

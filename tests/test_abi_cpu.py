@@ -100,6 +100,30 @@ def test_rope_arguments_are_checked_on_the_host():
     assert lib.lr_block_workspace_bytes(C.byref(d), 0) == 0
 
 
+def test_gqa_attention_arguments_are_checked_on_the_host():
+    lib = B.lib()
+    fake, odd = C.c_void_p(0x1000), C.c_void_p(0x1004)
+    f = lib.lr_attention_gqa_fwd
+    # q, k, v, o, lse, ld, ldkv, B, S, H, Hkv, hd, causal, dt, stream
+    assert f(fake, fake, fake, fake, fake, 512, 256, 1, 64, 4, 3, 128, 1, 1, None) == -1     # 3 does not divide 4
+    assert f(fake, fake, fake, fake, fake, 512, 128, 1, 64, 4, 2, 128, 1, 1, None) == -1     # kv rows too short
+    assert f(fake, fake, fake, fake, fake, 512, 256, 1, 64, 4, 0, 128, 1, 1, None) == -1
+    assert f(fake, fake, fake, fake, fake, 512, 260, 1, 64, 4, 2, 128, 1, 1, None) == -4     # row stride not x8
+    assert f(fake, odd, fake, fake, fake, 512, 256, 1, 64, 4, 2, 128, 1, 1, None) == -4
+    assert f(fake, fake, fake, fake, fake, 512, 256, 1, 64, 4, 2, 64, 1, 1, None) == -2      # other head sizes
+    assert f(fake, fake, fake, fake, fake, 512, 256, 1, 64, 4, 2, 128, 0, 1, None) == -2     # non-causal
+    assert f(fake, fake, fake, fake, None, 512, 256, 1, 64, 4, 2, 128, 1, 1, None) == -1
+    w = lib.lr_attention_gqa_bwd_workspace_bytes
+    assert w(1, 64, 4, 3, 128) == 0 and w(1, 64, 4, 2, 64) == 0
+    mha, gq = w(2, 256, 4, 4, 128), w(2, 256, 4, 2, 128)
+    assert mha == lib.lr_attention_bwd_workspace_bytes(2, 256, 4, 128)
+    assert gq == mha + 2 * (2 * 256) * (4 * 128) * 2          # one dK and one dV contribution per query head
+    g = lib.lr_attention_gqa_bwd
+    args = [fake] * 9 + [512, 256, 2, 256, 4, 2, 128, 1, 1]
+    assert g(*args, fake, gq - 1, None) == -3                  # short workspace
+    assert g(*args, None, gq, None) == -3
+
+
 def test_mfma_probe_arguments_are_checked_on_the_host():
     f = B.lib().lr_mfma_probe
     tf = C.c_double(0.0)

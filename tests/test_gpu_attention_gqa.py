@@ -1,0 +1,84 @@
+"""GPU parity of causal grouped-query attention (lr_attention_gqa_fwd / _bwd through the C ABI) against
+the fp64 oracle of oracle/gqa_oracle.py, element by element.  Shapes cover both backward forms (score
+gradient kept and dQ as a GEMM: S a multiple of 8; the recomputing form otherwise), ragged tails against
+the 128-query / 64-key / 256-row tiles, a single shared key / value head, and key / value rows wider
+than their heads (a row stride the kernels must honour).  Tolerances as for the multi-head tests, except
+that o is given two storage-floor units: the probabilities are rounded to bf16 before the P V product
+and o is rounded once more when stored, and for the first tokens of a sequence (one or a few keys, the
+largest elements by far against the RMS over all tokens) both roundings are of the size of the floor."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from oracle import gqa_oracle as gqa
+from parity import check
+from paper_2512_12131_amd import binding as B
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+HD = 128
+
+# B, S, H, Hkv, extra columns in the key / value rows
+CASES = [(2, 192, 4, 2, 0), (1, 300, 4, 1, 0), (1, 776, 8, 2, 0), (2, 320, 6, 3, 64), (1, 1096, 2, 1, 0),
+         (2, 333, 6, 2, 8)]
+
+
+@pytest.mark.parametrize("Bn,S,H,Hkv,pad", CASES)
+def test_attention_gqa_fwd_bwd(Bn, S, H, Hkv, pad):
+    print(f"gqa attention B={Bn} S={S} H={H} Hkv={Hkv} kv row pad={pad}", flush=True)
+    T, d, dkv = Bn * S, H * HD, Hkv * HD
+    dt = torch.bfloat16
+    q = si.gaussian(13, "q", (T, d), dtype=dt)
+    k = si.gaussian(13, "k", (T, dkv), dtype=dt)
+    v = si.gaussian(13, "v", (T, dkv), dtype=dt)
+    do = si.gaussian(13, "do", (T, d), dtype=dt)
+
+    def kv_dev(t):   # rows of dkv + pad elements, the heads in the first dkv columns
+        buf = torch.full((T, dkv + pad), 7.0, dtype=dt, device=DEV)
+        buf[:, :dkv] = t.to(DEV)
+        return buf[:, :dkv]
+
+    qd, dod = q.to(DEV), do.to(DEV)
+    kd, vd = kv_dev(k), kv_dev(v)
+    o, lse = B.lr_attention_gqa_fwd(qd, kd, vd, Bn, S, H, Hkv, HD)
+    dq, dk, dv = B.lr_attention_gqa_bwd(qd, kd, vd, o, dod, lse, Bn, S, H, Hkv, HD)
+    torch.cuda.synchronize()
+    Q, K, V, DO = (si.f64(t) for t in (q, k, v, do))
+    o_ref, lse_ref = gqa.attention_gqa_fwd(Q, K, V, Bn, S, H, Hkv, HD)
+    dq_ref, dk_ref, dv_ref = gqa.attention_gqa_bwd(Q, K, V, DO, Bn, S, H, Hkv, HD)
+    check("o", o, o_ref, dt, floor=2.0)
+    e = float(np.max(np.abs(lse.cpu().double().numpy() - lse_ref)))
+    print(f"    lse max abs err {e:.3e}", flush=True)
+    assert e < 2e-3
+    check("dq", dq, dq_ref, dt, floor=3.0)
+    check("dk", dk, dk_ref, dt, floor=3.0)
+    check("dv", dv, dv_ref, dt, floor=3.0)
+    # first token of every sequence attends only to itself: every query head returns its group's v_0
+    grp = H // Hkv
+    for b in range(Bn):
+        for h in range(H):
+            assert torch.equal(o[b * S, h * HD:(h + 1) * HD], vd[b * S, (h // grp) * HD:(h // grp + 1) * HD])
+
+
+def test_gqa_with_all_heads_distinct_is_the_multi_head_call():
+    """Hkv = H through the grouped-query entry points: bit-identical to lr_attention_fwd / _bwd."""
+    Bn, S, H = 2, 264, 3
+    T, d, dt = Bn * S, H * HD, torch.bfloat16
+    q, k, v, do = (si.gaussian(14, n, (T, d), dtype=dt).to(DEV) for n in ("q", "k", "v", "do"))
+    o0, lse0 = B.lr_attention_fwd(q, k, v, Bn, S, H, HD)
+    g0 = B.lr_attention_bwd(q, k, v, o0, do, lse0, Bn, S, H, HD)
+    o1, lse1 = B.lr_attention_gqa_fwd(q, k, v, Bn, S, H, H, HD)
+    g1 = B.lr_attention_gqa_bwd(q, k, v, o1, do, lse1, Bn, S, H, H, HD)
+    torch.cuda.synchronize()
+    assert torch.equal(o0, o1) and torch.equal(lse0, lse1)
+    for a, b in zip(g0, g1):
+        assert torch.equal(a, b)
+
+
+def test_gqa_rejects_head_counts_that_do_not_divide():
+    T, dt = 128, torch.bfloat16
+    q = torch.zeros((T, 3 * HD), dtype=dt, device=DEV)
+    kv = torch.zeros((T, 2 * HD), dtype=dt, device=DEV)
+    with pytest.raises(B.LrError):
+        B.lr_attention_gqa_fwd(q, kv, kv, 1, T, 3, 2, HD)
