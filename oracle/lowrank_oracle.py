@@ -295,9 +295,26 @@ def block_param_count(d, f, r):
     return 11 * d * r + 3 * f * r
 
 
-def block_fwd(x, p, B, S, H, hd, eps, act=ACT_SILU, causal=True, rope=None):
+def _attn_fwd(q, k, v, B, S, H, Hkv, hd, causal):
+    if Hkv == H:
+        return attention_fwd(q, k, v, B, S, H, hd, causal)
+    from . import gqa_oracle          # grouped-query attention (section "Discussion and Future Work")
+    return gqa_oracle.attention_gqa_fwd(q, k, v, B, S, H, Hkv, hd, causal)
+
+
+def _attn_bwd(q, k, v, do, B, S, H, Hkv, hd, causal):
+    if Hkv == H:
+        return attention_bwd(q, k, v, do, B, S, H, hd, causal)
+    from . import gqa_oracle
+    return gqa_oracle.attention_gqa_bwd(q, k, v, do, B, S, H, Hkv, hd, causal)
+
+
+def block_fwd(x, p, B, S, H, hd, eps, act=ACT_SILU, causal=True, rope=None, Hkv=None):
     """Returns (y, cache) where cache holds every intermediate (store-everything reference).
-    rope: None, or (cos, sin) tables [S, hd/2]: q and k are rotated before the attention."""
+    rope: None, or (cos, sin) tables [S, hd/2]: q and k are rotated before the attention.
+    Hkv: None (= H), or the number of key / value heads of grouped-query attention: the K and V
+    up-projections then have Hkv * hd rows, nothing else changes."""
+    Hkv = H if Hkv is None else Hkv
     x = np.asarray(x, dtype=F64)
     c = {"x": x}
     c["xh1"], c["rms1"] = rmsnorm_fwd(x, p["gamma1"], eps)
@@ -306,8 +323,8 @@ def block_fwd(x, p, B, S, H, hd, eps, act=ACT_SILU, causal=True, rope=None):
     c["qr"], c["kr"] = c["q"], c["k"]
     if rope is not None:
         c["qr"] = rope_apply(c["q"], rope[0], rope[1], B, S, H, hd)
-        c["kr"] = rope_apply(c["k"], rope[0], rope[1], B, S, H, hd)
-    c["o"], c["lse"] = attention_fwd(c["qr"], c["kr"], c["v"], B, S, H, hd, causal)
+        c["kr"] = rope_apply(c["k"], rope[0], rope[1], B, S, Hkv, hd)
+    c["o"], c["lse"] = _attn_fwd(c["qr"], c["kr"], c["v"], B, S, H, Hkv, hd, causal)
     c["z_o"], c["a_o"], c["attn_out"] = lr_linear_fwd(c["o"], p["wd_o"], p["wu_o"], act)
     c["h1"] = x + c["attn_out"]
     c["xh2"], c["rms2"] = rmsnorm_fwd(c["h1"], p["gamma2"], eps)
@@ -319,10 +336,11 @@ def block_fwd(x, p, B, S, H, hd, eps, act=ACT_SILU, causal=True, rope=None):
     return y, c
 
 
-def block_bwd(x, p, dy, B, S, H, hd, eps, act=ACT_SILU, causal=True, rope=None):
+def block_bwd(x, p, dy, B, S, H, hd, eps, act=ACT_SILU, causal=True, rope=None, Hkv=None):
     """Gradients of L = sum(y * dy) w.r.t. x and every parameter.  Returns (dx, grads)."""
     dy = np.asarray(dy, dtype=F64)
-    _, c = block_fwd(x, p, B, S, H, hd, eps, act, causal, rope)
+    Hkv = H if Hkv is None else Hkv
+    _, c = block_fwd(x, p, B, S, H, hd, eps, act, causal, rope, Hkv)
     g = {}
     # y = h1 + lr(m)
     dm, g["wd_d"], g["wu_d"] = lr_linear_bwd(c["m"], p["wd_d"], p["wu_d"], dy, act)
@@ -338,10 +356,10 @@ def block_bwd(x, p, dy, B, S, H, hd, eps, act=ACT_SILU, causal=True, rope=None):
     dh1 += dh1_n
     # h1 = x + lr(o)
     do, g["wd_o"], g["wu_o"] = lr_linear_bwd(c["o"], p["wd_o"], p["wu_o"], dh1, act)
-    dq, dk, dv = attention_bwd(c["qr"], c["kr"], c["v"], do, B, S, H, hd, causal)
+    dq, dk, dv = _attn_bwd(c["qr"], c["kr"], c["v"], do, B, S, H, Hkv, hd, causal)
     if rope is not None:                 # back through the rotations: their transposes
         dq = rope_apply(dq, rope[0], rope[1], B, S, H, hd, inverse=True)
-        dk = rope_apply(dk, rope[0], rope[1], B, S, H, hd, inverse=True)
+        dk = rope_apply(dk, rope[0], rope[1], B, S, Hkv, hd, inverse=True)
     dxh1 = np.zeros_like(c["xh1"])
     for n, dn in (("q", dq), ("k", dk), ("v", dv)):
         dxi, g["wd_" + n], g["wu_" + n] = lr_linear_bwd(c["xh1"], p["wd_" + n], p["wu_" + n], dn, act)

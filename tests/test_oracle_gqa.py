@@ -98,3 +98,73 @@ def test_gradients_by_finite_differences():
     assert _relerr(dq, fd(q)) < 1e-6
     assert _relerr(dk, fd(k)) < 1e-6
     assert _relerr(dv, fd(v)) < 1e-6
+
+
+# ---- the block with grouped K / V projections -------------------------------------------------
+def _block_params(rng, D, Dkv, F, R):
+    dims = {"q": (D, D), "k": (D, Dkv), "v": (D, Dkv), "o": (D, D), "g": (D, F), "u": (D, F), "d": (F, D)}
+    p = {}
+    for n, (d_in, d_out) in dims.items():
+        p["wd_" + n] = rng.normal(size=(R, d_in)) * d_in ** -0.5
+        p["wu_" + n] = rng.normal(size=(d_out, R)) * R ** -0.5
+    p["gamma1"] = 1.0 + 0.1 * rng.normal(size=(D,))
+    p["gamma2"] = 1.0 + 0.1 * rng.normal(size=(D,))
+    return p
+
+
+@pytest.mark.parametrize("with_rope", [False, True])
+def test_gqa_block_equals_the_multi_head_block_with_repeated_kv_up_projection_rows(with_rope):
+    """A block with Hkv key / value heads is the multi-head block whose K and V up-projections repeat every
+    head's rows H / Hkv times; the gradient of a shared row block is the sum over its copies."""
+    rng = np.random.default_rng(21)
+    B, S, H, Hkv, hd, F, R = 2, 5, 4, 2, 4, 6, 3
+    D, Dkv, T, grp = H * hd, Hkv * hd, B * S, H // Hkv
+    p = _block_params(rng, D, Dkv, F, R)
+    x, dy = rng.normal(size=(T, D)), rng.normal(size=(T, D))
+    rope = orc.rope_tables(S, hd, 100.0) if with_rope else None
+
+    def rep_rows(w):      # [Hkv*hd, R] -> [H*hd, R]
+        return np.repeat(w.reshape(Hkv, 1, hd, R), grp, axis=1).reshape(H * hd, R)
+
+    def sum_rows(w):      # [H*hd, R] -> [Hkv*hd, R]
+        return w.reshape(Hkv, grp, hd, R).sum(axis=1).reshape(Hkv * hd, R)
+
+    pf = dict(p)
+    pf["wu_k"], pf["wu_v"] = rep_rows(p["wu_k"]), rep_rows(p["wu_v"])
+    y, _ = orc.block_fwd(x, p, B, S, H, hd, 1e-5, rope=rope, Hkv=Hkv)
+    y0, _ = orc.block_fwd(x, pf, B, S, H, hd, 1e-5, rope=rope)
+    assert _relerr(y, y0) < 1e-12
+    dx, g = orc.block_bwd(x, p, dy, B, S, H, hd, 1e-5, rope=rope, Hkv=Hkv)
+    dx0, g0 = orc.block_bwd(x, pf, dy, B, S, H, hd, 1e-5, rope=rope)
+    assert _relerr(dx, dx0) < 1e-11
+    for k in g:
+        want = sum_rows(g0[k]) if k in ("wu_k", "wu_v") else g0[k]
+        assert _relerr(g[k], want) < 1e-11, k
+
+
+def test_gqa_block_gradients_by_finite_differences():
+    rng = np.random.default_rng(22)
+    B, S, H, Hkv, hd, F, R = 1, 4, 4, 2, 2, 5, 3
+    D, Dkv, T = H * hd, Hkv * hd, B * S
+    p = _block_params(rng, D, Dkv, F, R)
+    x, dy = rng.normal(size=(T, D)), rng.normal(size=(T, D))
+
+    def loss():
+        return float(np.sum(orc.block_fwd(x, p, B, S, H, hd, 1e-5, Hkv=Hkv)[0] * dy))
+
+    def fd(arr, eps=1e-6):
+        g = np.zeros_like(arr)
+        for idx in np.ndindex(*arr.shape):
+            old = arr[idx]
+            arr[idx] = old + eps
+            fp = loss()
+            arr[idx] = old - eps
+            fm = loss()
+            arr[idx] = old
+            g[idx] = (fp - fm) / (2 * eps)
+        return g
+
+    dx, g = orc.block_bwd(x, p, dy, B, S, H, hd, 1e-5, Hkv=Hkv)
+    assert _relerr(dx, fd(x)) < 1e-6
+    for k in ("wu_k", "wu_v", "wd_k", "wd_v", "wu_q", "wd_o", "gamma1"):
+        assert _relerr(g[k], fd(p[k])) < 1e-6, k
