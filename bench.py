@@ -41,6 +41,9 @@ WORKLOADS = {
     "block-7B-lax": (4, 4096, 4096, 32, 11008, 1024, "lax"),
     # rotary position embedding of q and k switched on (LLaMA-style attention; tables of the usual angles)
     "block-7B-rope": (4, 4096, 4096, 32, 11008, 1024, "rope"),
+    # grouped-query attention, 8 key / value heads for 32 query heads (the extension of the section
+    # "Discussion and Future Work": the K and V up-projections are 1024 wide instead of 4096)
+    "block-7B-gqa8": (4, 4096, 4096, 32, 11008, 1024, "gqa8"),
 }
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 HBM_PEAK_GBS = 8000.0
@@ -51,13 +54,15 @@ HBM_PEAK_GBS = 8000.0
 MEASURED_GEMM_TRAFFIC_BYTES = {"block-7B": 708.7e6}
 
 
-def block_flops(B, S, d, H, f, r):
-    """FLOPs = 2MNK per GEMM; attention counted causal-halved.  Returns a dict of the totals."""
+def block_flops(B, S, d, H, f, r, dkv=None):
+    """FLOPs = 2MNK per GEMM; attention counted causal-halved.  Returns a dict of the totals.
+    dkv: width of k and v (grouped-query attention), d if None."""
     T = B * S
-    lin_fwd = 2.0 * T * (11 * d * r + 3 * f * r)
+    dkv = d if dkv is None else dkv
+    lin_fwd = 2.0 * T * (9 * d * r + 2 * dkv * r + 3 * f * r)
     attn_fwd = 2.0 * 2.0 * B * H * S * S * (d // H) / 2.0        # QK^T and PV, causal half
     model = 3.0 * lin_fwd + 3.5 * attn_fwd                       # bwd: 2x linear, 2.5x attention
-    recompute_lin = 2.0 * T * r * (4 * d + 2 * f)                # six of the seven up-projections
+    recompute_lin = 2.0 * T * r * (2 * d + 2 * dkv + 2 * f)      # six of the seven up-projections
     gemm_exec = 3.0 * lin_fwd + recompute_lin
     # attention as executed here: fwd, re-fwd, and a backward of 5 GEMM units against the 2 of the forward
     # (S, dP, dV, dK in one kernel that also leaves dS; dQ as one GEMM over it)
@@ -66,25 +71,30 @@ def block_flops(B, S, d, H, f, r):
             "lin_fwd": lin_fwd, "attn_fwd": attn_fwd}
 
 
-def gemm_classes(B, S, d, H, f, r):
+def gemm_classes(B, S, d, H, f, r, dkv=None):
     """Every GEMM launch class of one block step as (FLOPs, ideal bytes): 2MNK and one read of each
     operand plus one write of the result (bf16; weight gradients leave as fp32)."""
     T = B * S
+    dkv = d if dkv is None else dkv
     out = []
 
     def g(M, N, K, count=1, out_bytes=2):
         out.append((count * 2.0 * M * N * K, count * (2.0 * (M * K + N * K) + out_bytes * M * N)))
 
     # (input width, output width, group size) of the four grouped low-rank layers: qkv, o, gate/up, down
-    for d_in, d_out, G in ((d, d, 3), (d, d, 1), (d, f, 2), (f, d, 1)):
+    # members as (output width, how many)
+    qkv = ((d, 3),) if dkv == d else ((d, 1), (dkv, 2))
+    for d_in, members in ((d, qkv), (d, ((d, 1),)), (d, ((f, 2),)), (f, ((d, 1),))):
+        G = sum(n for _, n in members)
         g(T, G * r, d_in)                 # forward: grouped down-projection
-        g(T, d_out, r, G)                 # forward: batched up-projections
-        g(T, r, d_out, G)                 # backward: data gradient through the up-projections
-        g(d_out, r, T, G, 4)              # backward: weight gradient of the up-projections
+        for d_out, n in members:
+            g(T, d_out, r, n)             # forward: batched up-projections
+            g(T, r, d_out, n)             # backward: data gradient through the up-projections
+            g(d_out, r, T, n, 4)          # backward: weight gradient of the up-projections
         g(T, d_in, G * r)                 # backward: data gradient through the down-projection
         g(G * r, d_in, T, 1, 4)           # backward: weight gradient of the down-projection
-    for d_out, G in ((d, 3), (d, 1), (f, 2)):
-        g(T, d_out, r, G)                 # re-forward from the rank-r checkpoints (all but the last layer)
+    for d_out, n in qkv + ((d, 1), (f, 2)):
+        g(T, d_out, r, n)                 # re-forward from the rank-r checkpoints (all but the last layer)
     return out
 
 
@@ -135,14 +145,17 @@ def main():
     act = B.LR_ACT_IDENTITY if variant in ("identity", "lax") else B.LR_ACT_SILU
     f_ld = si.pad_ld(f, 8)
     eps = 1e-5
-    case = si.block_case(Bn, S, d, H, 128, f, r, seed=0)
+    Hkv = 8 if variant == "gqa8" else None
+    dkv = None if Hkv is None else Hkv * 128
+    case = si.block_case(Bn, S, d, H, 128, f, r, seed=0, Hkv=Hkv)
     rope = None
     if variant == "rope":
         ang = torch.arange(S, dtype=torch.float64)[:, None] * 10000.0 ** (-2.0 * torch.arange(64, dtype=torch.float64) / 128)
         rope = (torch.cos(ang).float().to(dev), torch.sin(ang).float().to(dev))
     chain = args.chain_stat
     sy = torch.empty((Bn * S,), dtype=torch.float32, device=dev) if chain else None
-    desc = B.make_block_desc(Bn, S, d, H, 128, f, f_ld, r, eps=eps, act=act, rope=rope, stat_x_ready=chain, stat_y_out=sy)
+    desc = B.make_block_desc(Bn, S, d, H, 128, f, f_ld, r, eps=eps, act=act, rope=rope, stat_x_ready=chain, stat_y_out=sy,
+                             n_kv_heads=Hkv or 0)
     params = {k: v.to(dev) for k, v in si.pack_block_params(case["params"], f, f_ld).items()}
     x, dy = case["x"].to(dev), case["dy"].to(dev)
     ck = B.alloc_block_ckpt(desc, dev)
@@ -187,7 +200,7 @@ def main():
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / max(args.steps, 1)
 
-    fl = block_flops(Bn, S, d, H, f, r)
+    fl = block_flops(Bn, S, d, H, f, r, dkv)
     value = fl["exec"] / dt / 1e12
 
     # ---- roofline of the dominant kernel: gemm_bf16_kernel (all of the block's projection GEMMs,
@@ -203,7 +216,7 @@ def main():
     avg_launch_ms = gemm_ms / max(gemm_launches, 1)
     flops_per_launch = fl["gemm_exec"] / launches_per_step        # algorithmic FLOPs (2MNK) per launch
     achieved = flops_per_launch / (avg_launch_ms * 1e-3) / 1e12
-    classes = gemm_classes(Bn, S, d, H, f, r)
+    classes = gemm_classes(Bn, S, d, H, f, r, dkv)
     assert abs(sum(c[0] for c in classes) - fl["gemm_exec"]) < 1e-6 * fl["gemm_exec"]
     attainable = attainable_tflops(classes)
     roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
@@ -336,7 +349,8 @@ def main():
         "config": {"workload": f"{args.workload}: low-rank decoder block fwd+bwd, batch {Bn}, seq {S}, d_model {d}, "
                                f"{H} heads of 128, ffn {f}, rank {r}, sigma {'identity' if act == B.LR_ACT_IDENTITY else 'SiLU'}"
                                f"{' + rank-r residual from the layer below (LaX)' if variant == 'lax' else ''}"
-                               f"{', rotary embedding of q and k' if variant == 'rope' else ''}, "
+                               f"{', rotary embedding of q and k' if variant == 'rope' else ''}"
+                               f"{', 8 key / value heads (grouped-query attention)' if variant == 'gqa8' else ''}, "
                                f"rank-r checkpoint recompute",
                    "launch": "hip graph replay" if args.graph else "eager",
                    "tokens": T, "executed_tflop": round(fl["exec"] / 1e12, 3),
@@ -372,10 +386,10 @@ def main():
         else:
             oact = orc.ACT_IDENTITY if act == B.LR_ACT_IDENTITY else orc.ACT_SILU
             orope = None if rope is None else (si.f64(rope[0].cpu()), si.f64(rope[1].cpu()))
-            orc.block_fwd(X0, P, 1, s_len, H, 128, eps, act=oact, rope=orope)
-            orc.block_bwd(X0, P, DY0, 1, s_len, H, 128, eps, act=oact, rope=orope)
+            orc.block_fwd(X0, P, 1, s_len, H, 128, eps, act=oact, rope=orope, Hkv=Hkv)
+            orc.block_bwd(X0, P, DY0, 1, s_len, H, 128, eps, act=oact, rope=orope, Hkv=Hkv)
         ct = time.perf_counter() - t0
-        cfl = block_flops(1, s_len, d, H, f, r)
+        cfl = block_flops(1, s_len, d, H, f, r, dkv)
         cpu_flops = cfl["model"] + cfl["lin_fwd"] + cfl["attn_fwd"]   # block_bwd runs its own forward again
         out["cpu_baseline"] = {"value": round(cpu_flops / ct / 1e12, 4), "unit": "TFLOP/s",
                                "cores": os.cpu_count() if not os.environ.get("OMP_NUM_THREADS") else

@@ -127,6 +127,11 @@ typedef struct {
    * of computing it from x.                                                                    */
   int stat_x_ready;
   float* stat_y_out;
+  /* Grouped-query attention (section "Discussion and Future Work": only the shapes of the K and V
+   * projections change).  0 or n_heads: multi-head.  Otherwise a divisor of n_heads: the K and V
+   * up-projections are [n_kv_heads * head_dim, rank], and w_up_qkv (and its gradient) is packed:
+   * W_up,q [d_model, rank], then W_up,k, then W_up,v.  Everything else keeps its shape.          */
+  int64_t n_kv_heads;
 } lr_block_desc;
 
 typedef struct {

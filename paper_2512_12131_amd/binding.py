@@ -32,7 +32,7 @@ class BlockDesc(C.Structure):
     _fields_ = [("batch", _i64), ("seq", _i64), ("d_model", _i64), ("n_heads", _i64), ("head_dim", _i64),
                 ("ffn", _i64), ("ffn_ld", _i64), ("rank", _i64), ("eps", _f32), ("act", _int), ("norm", _int),
                 ("dt", _int), ("grad_dt", _int), ("causal", _int), ("rope_cos", _vp), ("rope_sin", _vp),
-                ("stat_x_ready", _int), ("stat_y_out", _vp)]
+                ("stat_x_ready", _int), ("stat_y_out", _vp), ("n_kv_heads", _i64)]
 
 
 class BlockParams(C.Structure):
@@ -227,15 +227,17 @@ def lr_group_bwd(x, gamma, eps, norm, w_down_cat, w_up_stack, z_cat, stat, dy_st
 # ---- the decoder block -----------------------------------------------------------------------
 def make_block_desc(batch, seq, d_model, n_heads, head_dim, ffn, ffn_ld, rank, eps=1e-5, act=LR_ACT_SILU,
                     norm=LR_NORM_ONLINE, dt=LR_BF16, grad_dt=LR_F32, causal=1, rope=None, stat_x_ready=False,
-                    stat_y_out=None):
-    """rope: None, or (cos, sin) device tensors [seq, head_dim / 2] fp32.  stat_y_out: None or a device
+                    stat_y_out=None, n_kv_heads=0):
+    """n_kv_heads: 0 (= n_heads) or a divisor of n_heads (grouped-query attention; w_up_qkv is then the
+    packed [d_model + 2 * n_kv_heads * head_dim, rank] matrix: q rows, k rows, v rows).  rope: None, or (cos, sin) device tensors [seq, head_dim / 2] fp32.  stat_y_out: None or a device
     tensor [T] fp32 that receives sum y^2; stat_x_ready: ckpt["s1"] arrives filled.  The descriptor holds
     addresses only: keep the tensors alive while the descriptor is in use (desc._keep does)."""
     cos_p = sin_p = None
     if rope is not None:
         cos_p, sin_p = rope[0].data_ptr(), rope[1].data_ptr()
     desc = BlockDesc(batch, seq, d_model, n_heads, head_dim, ffn, ffn_ld, rank, eps, act, norm, dt, grad_dt, causal,
-                     cos_p, sin_p, int(bool(stat_x_ready)), None if stat_y_out is None else stat_y_out.data_ptr())
+                     cos_p, sin_p, int(bool(stat_x_ready)), None if stat_y_out is None else stat_y_out.data_ptr(),
+                     int(n_kv_heads))
     desc._keep = (rope, stat_y_out)
     return desc
 

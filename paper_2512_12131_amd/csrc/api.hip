@@ -170,10 +170,32 @@ struct GrpArgs {
   const void *h_prev, *dz_next;
   void* dh_prev;
   int stat_ready;            // stat[] already holds sum_j x^2 (gathered by the GEMM that produced x)
+  // d_out_tail > 0: member 0 is d_out wide and members 1..G-1 are d_out_tail wide (a block with fewer
+  // key / value heads than query heads); w_up_stack, y_stack, dy_stack and dw_up_stack are then packed:
+  // member 0 ([d_out, r] / [T, d_out]) followed by the others ([d_out_tail, r] / [T, d_out_tail]).
+  int64_t d_out_tail;
   int64_t ldx, ldy, y_bs, lddy, dy_bs, lddx, T, d_in, r, d_out;
   int G, act, norm, accumulate;
   float eps;
 };
+
+// Members of a group that one batched GEMM launch can take: equal width, constant strides.
+struct GrpRun {
+  int g0, n;                        // first member, number of members
+  int64_t d_out, w_off;             // width; element offset of the first member's W_up (and dW_up)
+  int64_t y_off, ldy, y_bs;         // element offset, row stride and member stride in y_stack
+  int64_t dy_off, lddy, dy_bs;      // the same in dy_stack
+};
+int group_runs(const GrpArgs& a, GrpRun (&run)[2]) {
+  if (a.d_out_tail <= 0 || a.G < 2) {
+    run[0] = GrpRun{0, a.G, a.d_out, 0, 0, a.ldy, a.y_bs, 0, a.lddy, a.dy_bs};
+    return 1;
+  }
+  const int64_t w0 = a.d_out * a.r, y0 = a.T * a.d_out, yt = a.T * a.d_out_tail;
+  run[0] = GrpRun{0, 1, a.d_out, 0, 0, a.d_out, y0, 0, a.d_out, y0};
+  run[1] = GrpRun{1, a.G - 1, a.d_out_tail, w0, y0, a.d_out_tail, yt, y0, a.d_out_tail, yt};
+  return 2;
+}
 
 // z_cat = RMSNorm(x) . w_down_cat^T (+ sigma(z_cat) into `act`)
 void group_down_seq(Ctx& c, const GrpArgs& a, void* act) {
@@ -211,14 +233,20 @@ void group_down_seq(Ctx& c, const GrpArgs& a, void* act) {
 }
 
 void group_up_seq(Ctx& c, const GrpArgs& a, const void* act) {
+  const size_t es = esize(c.dt);
   const int64_t GR = (int64_t)a.G * a.r;
-  GemmOp up;
-  up.A = act; up.lda = GR; up.sA = a.r;
-  up.B = a.w_up_stack; up.ldb = a.r; up.sB = a.d_out * a.r;
-  up.C = a.y_stack; up.ldc = a.ldy; up.sC = a.y_bs;
-  up.M = (int)a.T; up.N = (int)a.d_out; up.K = (int)a.r; up.batch = a.G;
-  up.epi.kind = EPI_STORE;
-  gemm(c, up);
+  GrpRun run[2];
+  const int nrun = group_runs(a, run);
+  for (int i = 0; i < nrun; i++) {
+    const GrpRun& u = run[i];
+    GemmOp up;
+    up.A = (const char*)act + (size_t)u.g0 * a.r * es; up.lda = GR; up.sA = a.r;
+    up.B = (const char*)a.w_up_stack + (size_t)u.w_off * es; up.ldb = a.r; up.sB = u.d_out * a.r;
+    up.C = (char*)a.y_stack + (size_t)u.y_off * es; up.ldc = u.ldy; up.sC = u.y_bs;
+    up.M = (int)a.T; up.N = (int)u.d_out; up.K = (int)a.r; up.batch = u.n;
+    up.epi.kind = EPI_STORE;
+    gemm(c, up);
+  }
 }
 
 void group_fwd_seq(Ctx& c, const GrpArgs& a) {
@@ -233,39 +261,50 @@ void group_bwd_seq(Ctx& c, const GrpArgs& a, const void* act) {
   const size_t es = esize(c.dt);
   const int64_t GR = (int64_t)a.G * a.r;
   const bool normed = a.norm != LR_NORM_NONE;
+  GrpRun run[2];
+  const int nrun = group_runs(a, run);
   // dW_up[g] = dy_g^T . sigma(z_g)
-  for (int g = 0; g < a.G; g++)
-    wgrad(c, (const char*)a.dy_stack + (size_t)g * a.dy_bs * es, a.lddy, (int)a.d_out,
-          (const char*)act + (size_t)g * a.r * es, GR, (int)a.r, a.T,
-          (char*)a.dw_up_stack + (size_t)g * a.d_out * a.r * esize(c.gdt), nullptr, nullptr, nullptr,
-          a.accumulate);
+  for (int i = 0; i < nrun; i++)
+    for (int j = 0; j < run[i].n; j++) {
+      const GrpRun& u = run[i];
+      wgrad(c, (const char*)a.dy_stack + (size_t)(u.dy_off + j * u.dy_bs) * es, u.lddy, (int)u.d_out,
+            (const char*)act + (size_t)(u.g0 + j) * a.r * es, GR, (int)a.r, a.T,
+            (char*)a.dw_up_stack + (size_t)(u.w_off + j * u.d_out * a.r) * esize(c.gdt), nullptr, nullptr, nullptr,
+            a.accumulate);
+    }
   // dp_g = rho * (dy_g . W_up_g) * sigma'(z_g), batched over g, written into the columns of dp_cat;
   // cdot[t] = sum_n dp[t,n] z[t,n] is the RMSNorm-backward statistic, taken at rank r.
   void* dp = c.take((size_t)a.T * GR * es);
   float* cdot = normed ? (float*)c.take((size_t)a.T * sizeof(float)) : nullptr;
-  GemmOp da;
-  da.A = a.dy_stack; da.lda = a.lddy; da.sA = a.dy_bs;
-  da.B = a.w_up_stack; da.ldb = a.r; da.sB = a.d_out * a.r; da.transB = 1;
-  da.C = dp; da.ldc = GR; da.sC = a.r;
-  da.M = (int)a.T; da.N = (int)a.r; da.K = (int)a.d_out; da.batch = a.G;
-  da.epi.kind = EPI_ACTGRAD; da.epi.act = a.act; da.epi.R = a.zc; da.epi.ldr = GR; da.epi.sR = a.r;
-  if (a.lax) {
-    da.epi.kind = EPI_LAXGRAD;
-    da.epi.R2 = a.dz_next; da.epi.ldr2 = GR; da.epi.sR2 = a.r;
-    da.epi.C2 = a.dh_prev; da.epi.ldc2 = GR; da.epi.sC2 = a.r;
-  }
-  if (normed) {
-    da.epi.use_rho = 1; da.epi.rowa = a.statc; da.epi.inv_d = 1.f / (float)a.d_in; da.epi.eps = a.eps;
-  }
-  if (normed && c.dt == LR_BF16) {
-    const int slabs = gemm_bf16_rowpart_slabs((int)a.r) * a.G;
-    float* parts = (float*)c.take((size_t)a.T * slabs * sizeof(float));
-    da.epi.rowpart = parts; da.epi.rowpart_ld = slabs;
+  // one launch per run of equally wide members (one launch in all unless the key / value members are narrower)
+  const int slabs1 = (normed && c.dt == LR_BF16) ? gemm_bf16_rowpart_slabs((int)a.r) : 0;   // row-partial columns per member
+  float* parts = slabs1 ? (float*)c.take((size_t)a.T * slabs1 * a.G * sizeof(float)) : nullptr;
+  auto at = [&](const void* p, int g0) -> const void* { return p ? (const char*)p + (size_t)g0 * a.r * es : nullptr; };
+  for (int i = 0; i < nrun; i++) {
+    const GrpRun& u = run[i];
+    GemmOp da;
+    da.A = (const char*)a.dy_stack + (size_t)u.dy_off * es; da.lda = u.lddy; da.sA = u.dy_bs;
+    da.B = (const char*)a.w_up_stack + (size_t)u.w_off * es; da.ldb = a.r; da.sB = u.d_out * a.r; da.transB = 1;
+    da.C = (char*)dp + (size_t)u.g0 * a.r * es; da.ldc = GR; da.sC = a.r;
+    da.M = (int)a.T; da.N = (int)a.r; da.K = (int)u.d_out; da.batch = u.n;
+    da.epi.kind = EPI_ACTGRAD; da.epi.act = a.act; da.epi.R = at(a.zc, u.g0); da.epi.ldr = GR; da.epi.sR = a.r;
+    if (a.lax) {
+      da.epi.kind = EPI_LAXGRAD;
+      da.epi.R2 = at(a.dz_next, u.g0); da.epi.ldr2 = GR; da.epi.sR2 = a.r;
+      da.epi.C2 = (void*)at(a.dh_prev, u.g0); da.epi.ldc2 = GR; da.epi.sC2 = a.r;
+    }
+    if (normed) {
+      da.epi.use_rho = 1; da.epi.rowa = a.statc; da.epi.inv_d = 1.f / (float)a.d_in; da.epi.eps = a.eps;
+    }
+    if (parts) {
+      da.epi.rowpart = parts; da.epi.rowpart_ld = slabs1 * a.G; da.epi.rowpart_off = u.g0 * slabs1;
+    }
     gemm(c, da);
-    LAUNCH(c, k_rowsum_parts(parts, slabs, slabs, cdot, a.T, c.st));
-  } else {
-    gemm(c, da);
-    if (normed) LAUNCH(c, k_rowdot(dp, GR, a.zc, GR, cdot, a.T, GR, c.dt, c.st));
+  }
+  if (parts) {
+    LAUNCH(c, k_rowsum_parts(parts, slabs1 * a.G, slabs1 * a.G, cdot, a.T, c.st));
+  } else if (normed) {
+    LAUNCH(c, k_rowdot(dp, GR, a.zc, GR, cdot, a.T, GR, c.dt, c.st));
   }
   // dW_down_cat: with the norm folded in, the GEMM yields the gradient of (w * gamma); the finishing
   // pass scales it by gamma and also produces dgamma[k] = sum_n w[n,k] * dW'[n,k].
@@ -347,6 +386,7 @@ int check_sizes_fit_int(std::initializer_list<int64_t> v) {
 // ---------------------------------------------------------------------------------------------
 struct Blk {
   int64_t B, S, T, d, H, hd, f, r;
+  int64_t Hkv, dkv;                   // key / value heads and their total width (= H, d: multi-head)
   float eps;
   int act, norm, causal, gdt;
   const float *rope_cos, *rope_sin;   // both null: no rotary embedding
@@ -373,6 +413,9 @@ bool block_desc_ok(const lr_block_desc* ds, Blk& b, int* why) {
   b.B = ds->batch; b.S = ds->seq; b.T = ds->batch * ds->seq; b.d = ds->d_model; b.H = ds->n_heads; b.hd = ds->head_dim;
   b.f = ds->ffn_ld; b.r = ds->rank; b.eps = ds->eps; b.act = ds->act; b.norm = ds->norm; b.causal = ds->causal;
   b.gdt = ds->grad_dt;
+  b.Hkv = ds->n_kv_heads > 0 ? ds->n_kv_heads : ds->n_heads;
+  if (b.Hkv > b.H || b.H % b.Hkv != 0) { *why = LR_EINVAL; return false; }
+  b.dkv = b.Hkv * b.hd;
   b.rope_cos = ds->rope_cos; b.rope_sin = ds->rope_sin;
   b.stat_x_ready = ds->stat_x_ready != 0; b.stat_y_out = ds->stat_y_out;
   if (b.stat_y_out && ((uintptr_t)b.stat_y_out & 3)) { *why = LR_EALIGN; return false; }
@@ -449,6 +492,16 @@ void mlp_up_swiglu(Ctx& c, const Blk& b, const void* w_up_gu, const void* act, v
   gemm(c, up);
 }
 
+// the Q/K/V group of a block: K and V may be narrower than Q (fewer key / value heads)
+GrpArgs group_args(const Blk& b, int G, int64_t d_out);
+GrpArgs qkv_group_args(const Blk& b) {
+  GrpArgs g = group_args(b, 3, b.d);
+  if (b.dkv != b.d) g.d_out_tail = b.dkv;
+  return g;
+}
+// q and k of a stack laid out as q [T, d], k [T, dkv], v [T, dkv]: rotary embedding (or its transpose)
+void rope_qk(Ctx& c, const Blk& b, void* qkv, int inverse);
+
 GrpArgs group_args(const Blk& b, int G, int64_t d_out) {
   GrpArgs g{};
   g.G = G; g.T = b.T; g.d_in = b.d; g.r = b.r; g.d_out = d_out; g.act = b.act; g.norm = b.norm; g.eps = b.eps;
@@ -463,12 +516,23 @@ void rebuild_act(Ctx& c, const Blk& b, const void* z, const void* h_prev, void* 
   else LAUNCH(c, k_act_fwd(z, n, act, n, b.T, n, lax ? (int)LR_ACT_IDENTITY : b.act, LR_BF16, c.st));
 }
 
+void rope_qk(Ctx& c, const Blk& b, void* qkv, int inverse) {
+  if (b.dkv == b.d) {   // q and k are two [T, d] tensors back to back: one pass over both
+    LAUNCH(c, k_rope128_bf16(qkv, b.d, b.rope_cos, b.rope_sin, 2 * b.T, (int)b.S, (int)b.H, inverse, c.st));
+    return;
+  }
+  LAUNCH(c, k_rope128_bf16(qkv, b.d, b.rope_cos, b.rope_sin, b.T, (int)b.S, (int)b.H, inverse, c.st));
+  LAUNCH(c, k_rope128_bf16((char*)qkv + (size_t)b.T * b.d * 2, b.dkv, b.rope_cos, b.rope_sin, b.T, (int)b.S, (int)b.Hkv,
+                           inverse, c.st));
+}
+
 void block_fwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x, void* y, const lr_block_ckpt* ck,
                    const lr_block_lax* lx = nullptr) {
   const int lax = lx != nullptr;
   const size_t es = 2;
   const int64_t T = b.T, d = b.d, r = b.r, f = b.f;
-  void* qkv = c.take((size_t)3 * T * d * es);
+  const int64_t dkv = b.dkv;
+  void* qkv = c.take((size_t)T * (d + 2 * dkv) * es);     // q [T, d], k [T, dkv], v [T, dkv]
   void* o = c.take((size_t)T * d * es);
   void* h1 = c.take((size_t)T * d * es);
   float* lse = (float*)c.take((size_t)b.B * b.H * b.S * sizeof(float));
@@ -476,16 +540,15 @@ void block_fwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x
   void* gg = c.take((size_t)T * f * es);
   void* mm = c.take((size_t)T * f * es);
   // attention side
-  GrpArgs a = group_args(b, 3, d);
+  GrpArgs a = qkv_group_args(b);
   a.x = x; a.gamma = p->gamma1; a.w_down_cat = p->w_dn_qkv; a.w_up_stack = p->w_up_qkv;
   a.z_cat = ck ? ck->z_qkv : nullptr; a.stat = ck ? ck->s1 : nullptr; a.y_stack = qkv; a.act_out = act;
   a.stat_ready = b.stat_x_ready;
   a.lax = lax; a.h_prev = lax ? lx->h_prev_qkv : nullptr;
   group_fwd_seq(c, a);
-  if (b.rope_cos)   // q and k are the first two [T, d] members of the stack: one pass over both
-    LAUNCH(c, k_rope128_bf16(qkv, d, b.rope_cos, b.rope_sin, 2 * T, (int)b.S, (int)b.H, 0, c.st));
-  LAUNCH(c, attention_fwd_bf16(qkv, (char*)qkv + (size_t)T * d * es, (char*)qkv + (size_t)2 * T * d * es, o, lse, d,
-                               (int)b.B, (int)b.S, (int)b.H, (int)b.hd, b.causal, c.st));
+  if (b.rope_cos) rope_qk(c, b, qkv, 0);
+  LAUNCH(c, attention_gqa_fwd_bf16(qkv, (char*)qkv + (size_t)T * d * es, (char*)qkv + (size_t)T * (d + dkv) * es, o, lse,
+                                   d, dkv, (int)b.B, (int)b.S, (int)b.H, (int)b.Hkv, (int)b.hd, b.causal, c.st));
   single_down(c, b, o, d, p->w_dn_o, ck ? ck->z_o : nullptr, act, lax, lax ? lx->h_prev_o : nullptr);
   single_up(c, b, act, p->w_up_o, d, x, h1, ck ? ck->s2 : nullptr);   // h1 = x + ..., s2 = sum h1^2 from the epilogue
   // MLP side
@@ -522,11 +585,12 @@ void block_bwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x
   void* big2 = c.take((size_t)2 * T * f * es);    // dg,du (later dq,dk,dv)
   void* mm = c.take((size_t)T * f * es);          // m, later o and do
   float* lse = (float*)c.take((size_t)b.B * b.H * b.S * sizeof(float));
+  const int64_t dkv = b.dkv;
   void* qkv = big;
   void* dqkv = big2;
-  if (3 * d > 2 * f) {  // unusual shapes: separate buffers
-    qkv = c.take((size_t)3 * T * d * es);
-    dqkv = c.take((size_t)3 * T * d * es);
+  if (d + 2 * dkv > 2 * f) {  // unusual shapes: separate buffers
+    qkv = c.take((size_t)T * (d + 2 * dkv) * es);
+    dqkv = c.take((size_t)T * (d + 2 * dkv) * es);
   }
   void* o = mm;
   void* dout = nullptr;
@@ -567,12 +631,13 @@ void block_bwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x
   single_up_bwd(c, b, dh1, d, act_o, ck->z_o, p->w_up_o, g->w_up_o, dz1, accumulate, lax, lx->dz_next_o, lx->dh_prev_o);
   // re-forward q, k, v, o
   rebuild_act(c, b, ck->z_qkv, lx->h_prev_qkv, act_g, 3 * r, lax);
-  GrpArgs a = group_args(b, 3, d);
+  GrpArgs a = qkv_group_args(b);
   a.x = x; a.gamma = p->gamma1; a.w_down_cat = p->w_dn_qkv; a.w_up_stack = p->w_up_qkv; a.y_stack = qkv;
   group_up_seq(c, a, act_g);
-  if (b.rope_cos) LAUNCH(c, k_rope128_bf16(qkv, d, b.rope_cos, b.rope_sin, 2 * T, (int)b.S, (int)b.H, 0, c.st));
-  const void* q_ = qkv; const void* k_ = (char*)qkv + (size_t)T * d * es; const void* v_ = (char*)qkv + (size_t)2 * T * d * es;
-  LAUNCH(c, attention_fwd_bf16(q_, k_, v_, o, lse, d, (int)b.B, (int)b.S, (int)b.H, (int)b.hd, b.causal, c.st));
+  if (b.rope_cos) rope_qk(c, b, qkv, 0);
+  const void* q_ = qkv; const void* k_ = (char*)qkv + (size_t)T * d * es; const void* v_ = (char*)qkv + (size_t)T * (d + dkv) * es;
+  LAUNCH(c, attention_gqa_fwd_bf16(q_, k_, v_, o, lse, d, dkv, (int)b.B, (int)b.S, (int)b.H, (int)b.Hkv, (int)b.hd,
+                                   b.causal, c.st));
   // down-O backward
   wgrad(c, dz1, r, (int)r, o, d, (int)d, T, g->w_dn_o, nullptr, nullptr, nullptr, accumulate);
   {
@@ -584,14 +649,14 @@ void block_bwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x
   }
   {
     const size_t mk = c.mark();
-    void* aws = c.take(attention_bwd_ws_bytes((int)b.B, (int)b.S, (int)b.H, (int)b.hd));
-    LAUNCH(c, attention_bwd_bf16(q_, k_, v_, o, dout, lse, dqkv, (char*)dqkv + (size_t)T * d * es,
-                                 (char*)dqkv + (size_t)2 * T * d * es, d, (int)b.B, (int)b.S, (int)b.H, (int)b.hd,
-                                 b.causal, aws, c.st));
+    void* aws = c.take(attention_gqa_bwd_ws_bytes((int)b.B, (int)b.S, (int)b.H, (int)b.Hkv, (int)b.hd));
+    LAUNCH(c, attention_gqa_bwd_bf16(q_, k_, v_, o, dout, lse, dqkv, (char*)dqkv + (size_t)T * d * es,
+                                     (char*)dqkv + (size_t)T * (d + dkv) * es, d, dkv, (int)b.B, (int)b.S, (int)b.H,
+                                     (int)b.Hkv, (int)b.hd, b.causal, aws, c.st));
     c.release(mk);
   }
   // back through the rotations of q and k: their transposes, on dq and dk
-  if (b.rope_cos) LAUNCH(c, k_rope128_bf16(dqkv, d, b.rope_cos, b.rope_sin, 2 * T, (int)b.S, (int)b.H, 1, c.st));
+  if (b.rope_cos) rope_qk(c, b, dqkv, 1);
   a.zc = ck->z_qkv; a.statc = ck->s1; a.dy_stack = dqkv; a.dx = dx; a.dres = dh1; a.dgamma = g->gamma1;
   a.dw_down_cat = g->w_dn_qkv; a.dw_up_stack = g->w_up_qkv; a.accumulate = accumulate;
   a.lax = lax; a.dz_next = lx->dz_next_qkv; a.dh_prev = lx->dh_prev_qkv;

@@ -66,12 +66,14 @@ def group_case(T, d_in, r, d_out, G, dtype=torch.bfloat16, seed=0):
     return c
 
 
-def block_case(B, S, d, H, hd, f, r, dtype=torch.bfloat16, seed=0, gamma_std=0.1):
-    """Decoder block: seven factored projections, two norm scales, x and the upstream grad."""
+def block_case(B, S, d, H, hd, f, r, dtype=torch.bfloat16, seed=0, gamma_std=0.1, Hkv=None):
+    """Decoder block: seven factored projections, two norm scales, x and the upstream grad.
+    Hkv: key / value heads of grouped-query attention (None: as many as query heads)."""
     assert H * hd == d
     T = B * S
     p = {}
-    dims = {"q": (d, d), "k": (d, d), "v": (d, d), "o": (d, d), "g": (d, f), "u": (d, f), "d": (f, d)}
+    dkv = d if Hkv is None else Hkv * hd
+    dims = {"q": (d, d), "k": (d, dkv), "v": (d, dkv), "o": (d, d), "g": (d, f), "u": (d, f), "d": (f, d)}
     for n in PROJ:
         d_in, d_out = dims[n]
         p["wd_" + n] = gaussian(seed, "wd_" + n, (r, d_in), std=d_in ** -0.5, dtype=dtype)
@@ -112,7 +114,9 @@ def pack_block_params(p, f, f_ld):
     return {
         "gamma1": p["gamma1"].contiguous(),
         "w_dn_qkv": torch.cat([p["wd_q"], p["wd_k"], p["wd_v"]], dim=0).contiguous(),
-        "w_up_qkv": torch.stack([p["wu_q"], p["wu_k"], p["wu_v"]], dim=0).contiguous(),
+        # [3, d, r] stacked; with fewer key / value heads the rows of q, k, v packed one after the other
+        "w_up_qkv": (torch.stack([p["wu_q"], p["wu_k"], p["wu_v"]], dim=0) if p["wu_k"].shape == p["wu_q"].shape
+                     else torch.cat([p["wu_q"], p["wu_k"], p["wu_v"]], dim=0)).contiguous(),
         "w_dn_o": p["wd_o"].contiguous(),
         "w_up_o": p["wu_o"].contiguous(),
         "gamma2": p["gamma2"].contiguous(),
