@@ -82,3 +82,35 @@ def test_gqa_rejects_head_counts_that_do_not_divide():
     kv = torch.zeros((T, 2 * HD), dtype=dt, device=DEV)
     with pytest.raises(B.LrError):
         B.lr_attention_gqa_fwd(q, kv, kv, 1, T, 3, 2, HD)
+
+
+def test_attention_gqa_full_shape_sampled_group():
+    """The attention shape of the 7B block with 8 key / value heads (B 4, S 4096, 32 query heads), in the
+    launch configuration the benchmark times.  The oracle runs one group of one batch element (4 query
+    heads over their shared key / value head: outputs of a group depend on nothing else) and is compared
+    with those rows and columns of o, lse, dq, dk, dv."""
+    Bn, S, H, Hkv = 4, 4096, 32, 8
+    grp, T, dt = H // Hkv, Bn * S, torch.bfloat16
+    print(f"gqa attention full shape B={Bn} S={S} H={H} Hkv={Hkv}, sampled group", flush=True)
+    q = si.gaussian(15, "q", (T, H * HD), dtype=dt)
+    k = si.gaussian(15, "k", (T, Hkv * HD), dtype=dt)
+    v = si.gaussian(15, "v", (T, Hkv * HD), dtype=dt)
+    do = si.gaussian(15, "do", (T, H * HD), dtype=dt)
+    qd, kd, vd, dod = (t.to(DEV) for t in (q, k, v, do))
+    o, lse = B.lr_attention_gqa_fwd(qd, kd, vd, Bn, S, H, Hkv, HD)
+    dq, dk, dv = B.lr_attention_gqa_bwd(qd, kd, vd, o, dod, lse, Bn, S, H, Hkv, HD)
+    torch.cuda.synchronize()
+    b, g = 2, 5                                    # batch element, key / value head
+    rows = slice(b * S, (b + 1) * S)
+    qc = slice(g * grp * HD, (g + 1) * grp * HD)   # the group's query heads
+    kc = slice(g * HD, (g + 1) * HD)
+    Q, K, V, DO = si.f64(q[rows, qc]), si.f64(k[rows, kc]), si.f64(v[rows, kc]), si.f64(do[rows, qc])
+    o_ref, lse_ref = gqa.attention_gqa_fwd(Q, K, V, 1, S, grp, 1, HD)
+    dq_ref, dk_ref, dv_ref = gqa.attention_gqa_bwd(Q, K, V, DO, 1, S, grp, 1, HD)
+    check("o", o[rows, qc], o_ref, dt, floor=2.0)
+    e = float(np.max(np.abs(lse[b, g * grp:(g + 1) * grp].cpu().double().numpy() - lse_ref[0])))
+    print(f"    lse max abs err {e:.3e}", flush=True)
+    assert e < 2e-3
+    check("dq", dq[rows, qc], dq_ref, dt, floor=3.0)
+    check("dk", dk[rows, kc], dk_ref, dt, floor=3.0)
+    check("dv", dv[rows, kc], dv_ref, dt, floor=3.0)
