@@ -64,15 +64,18 @@ def lax_linear_bwd(x, w_down, w_up, h_prev, dy, dz_next):
     return dx, dw_down, dw_up, da
 
 
-def block_fwd(x, p, h_prev, B, S, H, hd, eps, causal=True):
-    """Returns (y, z, cache): z is the dict of this block's seven h_i (for the block above)."""
+def block_fwd(x, p, h_prev, B, S, H, hd, eps, causal=True, Hkv=None):
+    """Returns (y, z, cache): z is the dict of this block's seven h_i (for the block above).
+    Hkv: key / value heads of grouped-query attention (None: as many as query heads); the K and V
+    up-projections then have Hkv * hd rows."""
     x = np.asarray(x, dtype=F64)
+    Hkv = H if Hkv is None else Hkv
     c = {"x": x}
     z = {}
     c["xh1"], c["rms1"] = base.rmsnorm_fwd(x, p["gamma1"], eps)
     for n in ("q", "k", "v"):
         z[n], c[n] = lax_linear_fwd(c["xh1"], p["wd_" + n], p["wu_" + n], h_prev[n])
-    c["o"], c["lse"] = base.attention_fwd(c["q"], c["k"], c["v"], B, S, H, hd, causal)
+    c["o"], c["lse"] = base._attn_fwd(c["q"], c["k"], c["v"], B, S, H, Hkv, hd, causal)
     z["o"], c["attn_out"] = lax_linear_fwd(c["o"], p["wd_o"], p["wu_o"], h_prev["o"])
     c["h1"] = x + c["attn_out"]
     c["xh2"], c["rms2"] = base.rmsnorm_fwd(c["h1"], p["gamma2"], eps)
@@ -84,11 +87,12 @@ def block_fwd(x, p, h_prev, B, S, H, hd, eps, causal=True):
     return y, z, c
 
 
-def block_bwd(x, p, h_prev, dy, dz_next, B, S, H, hd, eps, causal=True):
+def block_bwd(x, p, h_prev, dy, dz_next, B, S, H, hd, eps, causal=True, Hkv=None):
     """Gradients of L = sum(y * dy) + sum_n sum(z_n * dz_next_n).
     Returns (dx, grads, dh_prev) with dh_prev the dict of gradients w.r.t. the seven h_prev."""
     dy = np.asarray(dy, dtype=F64)
-    _, _, c = block_fwd(x, p, h_prev, B, S, H, hd, eps, causal)
+    Hkv = H if Hkv is None else Hkv
+    _, _, c = block_fwd(x, p, h_prev, B, S, H, hd, eps, causal, Hkv)
     g, dh = {}, {}
     dm, g["wd_d"], g["wu_d"], dh["d"] = lax_linear_bwd(c["m"], p["wd_d"], p["wu_d"], h_prev["d"], dy, dz_next["d"])
     dh1 = dy.copy()
@@ -102,7 +106,7 @@ def block_bwd(x, p, h_prev, dy, dz_next, B, S, H, hd, eps, causal=True):
     dh1_n, g["gamma2"] = base.rmsnorm_bwd(c["h1"], p["gamma2"], eps, dxh2)
     dh1 += dh1_n
     do, g["wd_o"], g["wu_o"], dh["o"] = lax_linear_bwd(c["o"], p["wd_o"], p["wu_o"], h_prev["o"], dh1, dz_next["o"])
-    dq, dk, dv = base.attention_bwd(c["q"], c["k"], c["v"], do, B, S, H, hd, causal)
+    dq, dk, dv = base._attn_bwd(c["q"], c["k"], c["v"], do, B, S, H, Hkv, hd, causal)
     dxh1 = np.zeros_like(c["xh1"])
     for n, dn in (("q", dq), ("k", dk), ("v", dv)):
         dxi, g["wd_" + n], g["wu_" + n], dh[n] = lax_linear_bwd(c["xh1"], p["wd_" + n], p["wu_" + n], h_prev[n], dn,

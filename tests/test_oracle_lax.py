@@ -132,3 +132,41 @@ def test_two_block_stack_chains_through_dh_prev_and_dz_next():
         assert _relerr(g1[k], _fd_grad(loss, p1[k])) < 1e-6, k
     for k in ("wu_q", "wd_d"):
         assert _relerr(g2[k], _fd_grad(loss, p2[k])) < 1e-6, k
+
+
+def test_lax_block_with_grouped_kv_heads_by_finite_differences():
+    """Fewer key / value heads than query heads (the K and V up-projections narrower): every gradient the
+    backward returns, including the inter-layer ones, against central differences; and with as many
+    key / value heads as query heads the option changes nothing."""
+    rng = np.random.default_rng(123)
+    Bq, Sq, Hq, Hkv, hd, Fq, Rq = 1, 4, 4, 2, 2, 5, 3
+    Dq, Dkv, Tq = Hq * hd, Hkv * hd, Bq * Sq
+    dims = {"q": (Dq, Dq), "k": (Dq, Dkv), "v": (Dq, Dkv), "o": (Dq, Dq), "g": (Dq, Fq), "u": (Dq, Fq), "d": (Fq, Dq)}
+    p = {}
+    for n, (d_in, d_out) in dims.items():
+        p["wd_" + n] = rng.normal(size=(Rq, d_in)) * d_in ** -0.5
+        p["wu_" + n] = rng.normal(size=(d_out, Rq)) * Rq ** -0.5
+    p["gamma1"] = 1.0 + 0.1 * rng.normal(size=(Dq,))
+    p["gamma2"] = 1.0 + 0.1 * rng.normal(size=(Dq,))
+    x, dy = rng.normal(size=(Tq, Dq)), rng.normal(size=(Tq, Dq))
+    h_prev = {n: 0.5 * rng.normal(size=(Tq, Rq)) for n in lax.PROJ}
+    dz_next = {n: rng.normal(size=(Tq, Rq)) for n in lax.PROJ}
+
+    def loss():
+        y, z, _ = lax.block_fwd(x, p, h_prev, Bq, Sq, Hq, hd, EPS, Hkv=Hkv)
+        return float(np.sum(y * dy) + sum(np.sum(z[n] * dz_next[n]) for n in lax.PROJ))
+
+    dx, g, dh = lax.block_bwd(x, p, h_prev, dy, dz_next, Bq, Sq, Hq, hd, EPS, Hkv=Hkv)
+    assert g["wu_k"].shape == (Dkv, Rq)
+    assert _relerr(dx, _fd_grad(loss, x)) < 1e-6
+    for k in ("wu_k", "wu_v", "wd_k", "wu_q", "wd_o", "gamma1"):
+        assert _relerr(g[k], _fd_grad(loss, p[k])) < 1e-6, k
+    for n in ("k", "v", "q", "d"):
+        assert _relerr(dh[n], _fd_grad(loss, h_prev[n])) < 1e-6, n
+    # Hkv = H is the plain LaX block
+    p2 = _params(RNG)
+    x2, dy2 = RNG.normal(size=(T, D)), RNG.normal(size=(T, D))
+    hp2, dz2 = _hdict(RNG, 0.5), _hdict(RNG)
+    a = lax.block_bwd(x2, p2, hp2, dy2, dz2, B, S, H, HD, EPS)
+    b = lax.block_bwd(x2, p2, hp2, dy2, dz2, B, S, H, HD, EPS, Hkv=H)
+    assert np.array_equal(a[0], b[0])
