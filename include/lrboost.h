@@ -179,8 +179,8 @@ int lr_block_bwd(const lr_block_desc* desc, const lr_block_params* params, const
  * w.r.t. its h_prev_*.  Layouts as the checkpoints: qkv [T, 3r], o [T, r], gu [T, 2r], d [T, r],
  * bf16, dense.  Each pointer may be NULL: an absent h_prev / dz_next counts as zeros (first /
  * last block of a stack), an absent dh_prev is not written.  desc->act must be
- * LR_ACT_IDENTITY and desc->n_kv_heads 0 or n_heads (else LR_EUNSUPPORTED); everything else
- * as lr_block_fwd / lr_block_bwd, same workspace sizes.                                      */
+ * LR_ACT_IDENTITY (else LR_EUNSUPPORTED); everything else as lr_block_fwd / lr_block_bwd
+ * (grouped key / value heads included), same workspace sizes.                               */
 typedef struct {
   const void *h_prev_qkv, *h_prev_o, *h_prev_gu, *h_prev_d;       /* forward and backward inputs  */
   const void *dz_next_qkv, *dz_next_o, *dz_next_gu, *dz_next_d;   /* backward inputs              */

@@ -868,8 +868,6 @@ int lr_block_bwd(const lr_block_desc* desc, const lr_block_params* params, const
 static int check_lax(const lr_block_desc* desc, const lr_block_lax* lx) {
   if (!lx) return LR_EINVAL;
   if (desc->act != LR_ACT_IDENTITY) return LR_EUNSUPPORTED;
-  // the LaX variant is covered for multi-head blocks only
-  if (desc->n_kv_heads > 0 && desc->n_kv_heads != desc->n_heads) return LR_EUNSUPPORTED;
   for (const void* q : {lx->h_prev_qkv, lx->h_prev_o, lx->h_prev_gu, lx->h_prev_d, lx->dz_next_qkv, lx->dz_next_o,
                         lx->dz_next_gu, lx->dz_next_d, (const void*)lx->dh_prev_qkv, (const void*)lx->dh_prev_o,
                         (const void*)lx->dh_prev_gu, (const void*)lx->dh_prev_d})

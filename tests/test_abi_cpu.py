@@ -134,13 +134,6 @@ def test_block_descriptor_checks_the_kv_head_count():
         d = B.make_block_desc(1, 128, 512, 4, 128, 256, 256, 32, n_kv_heads=bad)
         want_zero = bad > 0
         assert (lib.lr_block_workspace_bytes(C.byref(d), 0) == 0) == want_zero, bad
-    # the LaX entry points take multi-head blocks only
-    lax = B.make_block_desc(1, 128, 512, 4, 128, 256, 256, 32, act=B.LR_ACT_IDENTITY, n_kv_heads=2)
-    fake = C.c_void_p(0x1000)
-    ps = B.BlockParams(*[fake] * 10)
-    ck = B.BlockCkpt(*[fake] * 6)
-    lx = B.BlockLax()
-    assert lib.lr_block_lax_fwd(C.byref(lax), C.byref(ps), fake, fake, C.byref(ck), C.byref(lx), fake, 1 << 40, None) == -2
 
 
 def test_mfma_probe_arguments_are_checked_on_the_host():

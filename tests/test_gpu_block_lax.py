@@ -155,3 +155,41 @@ def test_two_block_stack_through_the_library():
     got1 = _unpack_grads(g1, f, r)
     for name in ("wd_q", "wu_v", "wd_o", "wd_g", "wu_u", "wd_d", "gamma1"):
         check("d" + name, got1[name], g1r[name], dt, scale=2.0, floor=FLW)
+
+
+def test_block_lax_with_grouped_kv_heads():
+    """LaX block with 4 query and 2 key / value heads: outputs, checkpoints, dx, dh_prev and the weight
+    gradients against the fp64 oracle."""
+    Bn, S, H, Hkv, f, r = 2, 192, 4, 2, 344, 64
+    d, dkv, f_ld = 128 * H, 128 * Hkv, si.pad_ld(f, 8)
+    print(f"block lax gqa B={Bn} S={S} H={H} Hkv={Hkv} f={f} r={r}", flush=True)
+    case = si.block_case(Bn, S, d, H, 128, f, r, seed=24, Hkv=Hkv)
+    desc = B.make_block_desc(Bn, S, d, H, 128, f, f_ld, r, eps=EPS, act=B.LR_ACT_IDENTITY, n_kv_heads=Hkv)
+    packed = {k: v.to(DEV) for k, v in si.pack_block_params(case["params"], f, f_ld).items()}
+    T = Bn * S
+    h_prev = _rank_tensors(24, "hprev", T, r, 0.5)
+    dz_next = _rank_tensors(24, "dznext", T, r, 1.0)
+    x, dy = case["x"].to(DEV), case["dy"].to(DEV)
+    hp_dev, dzn_dev = _cat(h_prev, DEV), _cat(dz_next, DEV)
+    y, ck = B.lr_block_lax_fwd(desc, packed, x, h_prev=hp_dev)
+    dx, grads, dh = B.lr_block_lax_bwd(desc, packed, x, dy, ck, h_prev=hp_dev, dz_next=dzn_dev)
+    torch.cuda.synchronize()
+    P = {k: si.f64(v) for k, v in case["params"].items()}
+    X, DY = si.f64(case["x"]), si.f64(case["dy"])
+    y_ref, z_ref, _ = lax.block_fwd(X, P, _f64(h_prev), Bn, S, H, 128, EPS, Hkv=Hkv)
+    dx_ref, g_ref, dh_ref = lax.block_bwd(X, P, _f64(h_prev), DY, _f64(dz_next), Bn, S, H, 128, EPS, Hkv=Hkv)
+    dt = torch.bfloat16
+    check("y", y, y_ref, dt, floor=FL)
+    z_gpu = _split({k: ck["z_" + k] for k in PARTS}, r)
+    for n in lax.PROJ:
+        check("z_" + n, z_gpu[n], z_ref[n], dt, floor=FL)
+    check("dx", dx, dx_ref, dt, floor=FL)
+    dh_gpu = _split(dh, r)
+    for n in lax.PROJ:
+        check("dh_prev_" + n, dh_gpu[n], dh_ref[n], dt, floor=FLW)
+    wq = grads["w_up_qkv"].reshape(-1, r)
+    got = {"wu_q": wq[:d], "wu_k": wq[d:d + dkv], "wu_v": wq[d + dkv:], "wd_q": grads["w_dn_qkv"][:r],
+           "wd_k": grads["w_dn_qkv"][r:2 * r], "wd_v": grads["w_dn_qkv"][2 * r:], "wu_o": grads["w_up_o"],
+           "gamma1": grads["gamma1"], "wd_d": grads["w_dn_d"][:, :f]}
+    for name, g in got.items():
+        check("d" + name, g, g_ref[name], dt, floor=FLW)
