@@ -20,7 +20,7 @@ DEV = "cuda:0"
 HD = 128
 
 # B, S, H, Hkv, extra columns in the key / value rows
-CASES = [(2, 192, 4, 2, 0), (1, 300, 4, 1, 0), (1, 776, 8, 2, 0), (2, 320, 6, 3, 64), (1, 1096, 2, 1, 0),
+CASES = [(1, 1, 2, 1, 0), (2, 64, 4, 2, 0), (2, 192, 4, 2, 0), (1, 300, 4, 1, 0), (1, 776, 8, 2, 0), (2, 320, 6, 3, 64), (1, 1096, 2, 1, 0),
          (2, 333, 6, 2, 8)]
 
 
