@@ -137,7 +137,7 @@ typedef struct {
 typedef struct {
   void* gamma1;    /* [d]                                                                  */
   void* w_dn_qkv;  /* [3r, d]   q, k, v concatenated along the rank axis                   */
-  void* w_up_qkv;  /* [3, d, r]                                                            */
+  void* w_up_qkv;  /* [3, d, r]  (n_kv_heads < n_heads: [d + 2 n_kv_heads head_dim, r])     */
   void* w_dn_o;    /* [r, d]                                                               */
   void* w_up_o;    /* [d, r]                                                               */
   void* gamma2;    /* [d]                                                                  */
