@@ -104,10 +104,14 @@ def rmsnorm_bwd(x, gamma, eps, dxhat):
 
 
 def online_rmsnorm_sharded(x, gamma, w, k, eps):
-    """Alg. 1 taken step by step over k simulated tensor-parallel shards of the feature axis.
+    """The sharded form of RMSNorm + row-split projection (Sec. 4.2, Alg. 1 / Eq. 5) over k simulated
+    tensor-parallel ranks, as a check of its equivalence with the unsharded two-pass result.
 
-    x[T, d], gamma[d], w[d, r] (row-split: shard i owns rows i*d/k .. (i+1)*d/k).  The
-    all-reduce of line 6 is a plain sum over the shards.  Returns Y[T, r].
+    x[T, d], gamma[d], w[d, r]; rank i owns the feature slice i*d/k .. (i+1)*d/k of x and gamma and the
+    matching rows of w.  Each rank normalises its slice by its own local rms, multiplies by its weight
+    rows and undoes the local scale on the product; the partial products and the local sums of squares
+    are then added over the ranks (the all-reduce), and the global rms computed from the summed
+    statistic rescales the sum.  Returns Y[T, r].
     """
     x = np.asarray(x, dtype=F64)
     gamma = np.asarray(gamma, dtype=F64)
@@ -115,21 +119,15 @@ def online_rmsnorm_sharded(x, gamma, w, k, eps):
     T, d = x.shape
     assert d % k == 0
     dl = d // k
-    h_global = np.zeros((T, w.shape[1]), dtype=F64)
-    s_global = np.zeros(T, dtype=F64)
-    for i in range(k):
-        xi = x[:, i * dl:(i + 1) * dl]
-        wi = w[i * dl:(i + 1) * dl, :]
-        gi = gamma[i * dl:(i + 1) * dl]
-        s_local = np.sum(xi * xi, axis=1)                    # line 1
-        rms_local = np.sqrt(s_local / dl + eps)              # line 2
-        xi_n = xi / rms_local[:, None] * gi[None, :]         # line 3
-        hi = xi_n @ wi                                       # line 4
-        hi = hi * rms_local[:, None]                         # line 5
-        h_global += hi                                       # line 6 (sum over ranks)
-        s_global += s_local
-    rms_global = np.sqrt(s_global / d + eps)                 # line 7
-    return h_global / rms_global[:, None]                    # line 8
+    xs = x.reshape(T, k, dl)                                   # [token, rank, local feature]
+    gs = gamma.reshape(k, dl)
+    ws = w.reshape(k, dl, w.shape[1])
+    s_local = np.einsum("tkj,tkj->tk", xs, xs)                 # per rank: sum of squares of its slice
+    rms_local = np.sqrt(s_local / dl + eps)
+    xn = xs / rms_local[:, :, None] * gs[None, :, :]           # locally normalised, scaled by gamma
+    part = np.einsum("tkj,kjr->tkr", xn, ws) * rms_local[:, :, None]   # local product, local scale undone
+    rms_global = np.sqrt(s_local.sum(axis=1) / d + eps)        # from the statistic summed over ranks
+    return part.sum(axis=1) / rms_global[:, None]
 
 
 # --------------------------------------------------------------------------------------------
