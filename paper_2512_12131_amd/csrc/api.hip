@@ -162,6 +162,8 @@ struct GrpArgs {
   void *dx, *dgamma, *dw_down_cat, *dw_up_stack;
   const void* dres;          // optional residual gradient added into dx (block use)
   int64_t lddres;
+  const float* dres32;       // the same residual gradient as an fp32 [T, d_in] tensor (takes precedence)
+  float* dx32;               // optional: dx also un-rounded, fp32 [T, d_in] (the residual of a later sum)
   void* act_out;             // optional: where sigma(z_cat) goes (else workspace)
   // LaX variant (identity gate): h_prev [T, G*r] is added to z_cat before the up-projections; in the
   // backward dz_next [T, G*r] is the layer above's gradient w.r.t. z_cat and dh_prev [T, G*r] receives
@@ -329,6 +331,11 @@ void group_bwd_seq(Ctx& c, const GrpArgs& a, const void* act) {
     dx.epi.inv_d = 1.f / (float)a.d_in; dx.epi.eps = a.eps;
     dx.epi.R2 = a.x; dx.epi.ldr2 = a.ldx;
     dx.epi.R = a.dres; dx.epi.ldr = a.lddres;
+    if (c.dt == LR_BF16 && a.dres32) {
+      dx.epi.kind = EPI_NORMBWD_I32; dx.epi.R = a.dres32; dx.epi.ldr = a.d_in;
+    } else if (c.dt == LR_BF16 && a.dx32) {
+      dx.epi.kind = EPI_NORMBWD_O32; dx.epi.C32 = a.dx32; dx.epi.ldc32 = a.d_in;
+    }
   } else if (a.dres) {
     dx.epi.kind = EPI_UP; dx.epi.R = a.dres; dx.epi.ldr = a.lddres;
   } else {
@@ -437,14 +444,18 @@ void single_down(Ctx& c, const Blk& b, const void* in, int64_t K, const void* w_
   gemm(c, dn);
 }
 
-// out = act . w_up^T + resid ; optionally the per-row sum of squares of out into `sumsq`
+// out = act . w_up^T + resid ; optionally the per-row sum of squares of out into `sumsq`.
+// The residual stream stays un-rounded between the two sums of a block: out32 (optional) receives the
+// sum as fp32 beside the bf16 `out`, resid32 (optional, instead of resid) is such a tensor taken back.
 void single_up(Ctx& c, const Blk& b, const void* act, const void* w_up, int64_t N, const void* resid, void* out,
-               float* sumsq) {
+               float* sumsq, float* out32 = nullptr, const float* resid32 = nullptr) {
   const size_t m = c.mark();
   GemmOp up;
   up.A = act; up.lda = b.r; up.B = w_up; up.ldb = b.r; up.C = out; up.ldc = N;
   up.M = (int)b.T; up.N = (int)N; up.K = (int)b.r;
   up.epi.kind = EPI_UP; up.epi.R = resid; up.epi.ldr = N;
+  if (resid32) { up.epi.kind = EPI_UP_I32; up.epi.R = resid32; }
+  else if (out32) { up.epi.kind = EPI_UP_O32; up.epi.C32 = out32; up.epi.ldc32 = N; }
   if (sumsq) {
     const int slabs = gemm_bf16_rowpart_slabs((int)N);
     float* parts = (float*)c.take((size_t)b.T * slabs * sizeof(float));
@@ -535,6 +546,7 @@ void block_fwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x
   void* qkv = c.take((size_t)T * (d + 2 * dkv) * es);     // q [T, d], k [T, dkv], v [T, dkv]
   void* o = c.take((size_t)T * d * es);
   void* h1 = c.take((size_t)T * d * es);
+  float* h1f = (float*)c.take((size_t)T * d * sizeof(float));   // h1 before rounding: the residual of y
   float* lse = (float*)c.take((size_t)b.B * b.H * b.S * sizeof(float));
   void* act = c.take((size_t)T * 3 * r * es);     // sigma(z) of whichever projection group is live
   void* gg = c.take((size_t)T * f * es);
@@ -550,7 +562,7 @@ void block_fwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x
   LAUNCH(c, attention_gqa_fwd_bf16(qkv, (char*)qkv + (size_t)T * d * es, (char*)qkv + (size_t)T * (d + dkv) * es, o, lse,
                                    d, dkv, (int)b.B, (int)b.S, (int)b.H, (int)b.Hkv, (int)b.hd, b.causal, c.st));
   single_down(c, b, o, d, p->w_dn_o, ck ? ck->z_o : nullptr, act, lax, lax ? lx->h_prev_o : nullptr);
-  single_up(c, b, act, p->w_up_o, d, x, h1, ck ? ck->s2 : nullptr);   // h1 = x + ..., s2 = sum h1^2 from the epilogue
+  single_up(c, b, act, p->w_up_o, d, x, h1, ck ? ck->s2 : nullptr, h1f);   // h1 = x + ..., s2 = sum h1^2 from the epilogue
   // MLP side
   GrpArgs m = group_args(b, 2, f);
   m.x = h1; m.gamma = p->gamma2; m.w_down_cat = p->w_dn_gu; m.w_up_stack = p->w_up_gu;
@@ -559,7 +571,7 @@ void block_fwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x
   group_down_seq(c, m, act);
   mlp_up_swiglu(c, b, p->w_up_gu, act, gg, nullptr, mm);
   single_down(c, b, mm, f, p->w_dn_d, ck ? ck->z_d : nullptr, act, lax, lax ? lx->h_prev_d : nullptr);
-  single_up(c, b, act, p->w_up_d, d, h1, y, b.stat_y_out);   // optionally sum y^2 for the block above
+  single_up(c, b, act, p->w_up_d, d, nullptr, y, b.stat_y_out, nullptr, h1f);   // optionally sum y^2 for the block above
 }
 
 void block_bwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x, const void* dy,
@@ -581,6 +593,7 @@ void block_bwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x
   void* dz1 = c.take((size_t)T * r * es);         // dz_d, later dz_o
   void* h1 = c.take((size_t)T * d * es);
   void* dh1 = c.take((size_t)T * d * es);
+  float* dh1f = (float*)c.take((size_t)T * d * sizeof(float));   // dh1 before rounding: the residual of dx
   void* big = c.take((size_t)2 * T * f * es);     // g,u  (later q,k,v: needs 3*T*d <= 2*T*f checked below)
   void* big2 = c.take((size_t)2 * T * f * es);    // dg,du (later dq,dk,dv)
   void* mm = c.take((size_t)T * f * es);          // m, later o and do
@@ -622,7 +635,7 @@ void block_bwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x
     gemm(c, dm);
   }
   // gate/up group backward; dh1 = dy + RMSNorm-2 reverse
-  m.zc = ck->z_gu; m.statc = ck->s2; m.dy_stack = big2; m.dx = dh1; m.dres = dy; m.dgamma = g->gamma2;
+  m.zc = ck->z_gu; m.statc = ck->s2; m.dy_stack = big2; m.dx = dh1; m.dx32 = dh1f; m.dres = dy; m.dgamma = g->gamma2;
   m.dw_down_cat = g->w_dn_gu; m.dw_up_stack = g->w_up_gu; m.accumulate = accumulate;
   m.lax = lax; m.dz_next = lx->dz_next_gu; m.dh_prev = lx->dh_prev_gu;
   group_bwd_seq(c, m, act_g);
@@ -657,7 +670,7 @@ void block_bwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x
   }
   // back through the rotations of q and k: their transposes, on dq and dk
   if (b.rope_cos) rope_qk(c, b, dqkv, 1);
-  a.zc = ck->z_qkv; a.statc = ck->s1; a.dy_stack = dqkv; a.dx = dx; a.dres = dh1; a.dgamma = g->gamma1;
+  a.zc = ck->z_qkv; a.statc = ck->s1; a.dy_stack = dqkv; a.dx = dx; a.dres = dh1; a.dres32 = dh1f; a.dgamma = g->gamma1;
   a.dw_down_cat = g->w_dn_qkv; a.dw_up_stack = g->w_up_qkv; a.accumulate = accumulate;
   a.lax = lax; a.dz_next = lx->dz_next_qkv; a.dh_prev = lx->dh_prev_qkv;
   group_bwd_seq(c, a, act_g);

@@ -23,9 +23,24 @@ enum EpiKind : int {
   EPI_SWIGLU_FWD = 7,  // v = acc (= u); C = v (skipped when C is null), C2 = silu(R)*v (m); R = g
   // LaX variant (identity gate, rank-r residual from the layer below; App. "LaX variant"):
   EPI_DOWN_LAX = 8,    // v = acc * rho_m ; C = v (= h_i) ; C2 = v + R (R = h_{i-1}; absent R reads as zero)
-  EPI_LAXGRAD = 9      // C2 = acc (gradient w.r.t. h_{i-1}) ; v = (acc + R2) * rho_m (R2 = the layer above's
+  EPI_LAXGRAD = 9,     // C2 = acc (gradient w.r.t. h_{i-1}) ; v = (acc + R2) * rho_m (R2 = the layer above's
                        // gradient w.r.t. h_i) ; C = v ; rowpart = sum_n v * R (R = h_i)
+  // The residual stream in fp32 (bf16 kernel only).  A residual sum x + f(x) stored in bf16 and added to
+  // once more carries the rounding of the large term twice; these forms keep the un-rounded sum beside
+  // the bf16 copy that the next GEMM consumes (O32: C32 = v as fp32, in addition to C) and take it back
+  // as the residual of the next sum (I32: R is an fp32 tile).  Formulas as EPI_UP / EPI_NORMBWD.
+  EPI_UP_O32 = 10,
+  EPI_UP_I32 = 11,
+  EPI_NORMBWD_O32 = 12,
+  EPI_NORMBWD_I32 = 13
 };
+// the formula an epilogue kind applies (the fp32-residual forms share EPI_UP's and EPI_NORMBWD's)
+constexpr int epi_base(int kind) {
+  return (kind == EPI_UP_O32 || kind == EPI_UP_I32) ? (int)EPI_UP
+         : (kind == EPI_NORMBWD_O32 || kind == EPI_NORMBWD_I32) ? (int)EPI_NORMBWD : kind;
+}
+constexpr bool epi_r_is_f32(int kind) { return kind == EPI_UP_I32 || kind == EPI_NORMBWD_I32; }
+constexpr bool epi_writes_f32(int kind) { return kind == EPI_UP_O32 || kind == EPI_NORMBWD_O32; }
 
 struct Epilogue {
   int kind = EPI_STORE;
@@ -38,6 +53,8 @@ struct Epilogue {
   float* stat_out = nullptr;  // [M] final sum of squares, written by the n-tile 0 blocks
   void* C2 = nullptr;
   int64_t ldc2 = 0, sC2 = 0;
+  float* C32 = nullptr;       // O32 kinds: fp32 copy of the primary output (un-batched)
+  int64_t ldc32 = 0;
   const void* R = nullptr;
   int64_t ldr = 0, sR = 0;
   const void* R2 = nullptr;
@@ -156,6 +173,8 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) { return pack_bf16x2(f, 0.f) & 0xffffu; }
+// the value a float has once stored as bf16 (round to nearest even) and read back
+__device__ __forceinline__ float bf16_round_f(float f) { return bf16_bits_to_f32(f32_to_bf16_bits(f)); }
 __device__ __forceinline__ void unpack8(const uint4& q, float* v) {
   v[0] = __uint_as_float(q.x << 16); v[1] = __uint_as_float(q.x & 0xffff0000u);
   v[2] = __uint_as_float(q.y << 16); v[3] = __uint_as_float(q.y & 0xffff0000u);

@@ -2,6 +2,8 @@
 // accumulator columns of one output row, applies the fused elementwise work in fp32, rounds once
 // and stores.  See EpiKind in common.h for the formulas.
 #pragma once
+#include <type_traits>
+
 #include "common.h"
 
 namespace lrb {
@@ -77,7 +79,10 @@ __device__ __forceinline__ bool epi_reads_r2(const Epilogue& e) {
 // the matching entries of the auxiliary tiles (zeros where a kind's tile is absent: adding them is
 // harmless).  rho / rowb: per-row scalars resolved by the caller (rho = 1 when unused).  fp32 throughout;
 // returns this thread's contribution to the row partial (0 if the kind has none).
-template <int NV, int KIND>
+// STORE_BF16: the primary output is stored as bf16.  The rank-r activation (sigma(z), or z + h_prev in the
+// LaX form) is then formed from z AS STORED, so that the backward, which rebuilds it from the bf16
+// checkpoint, gets the forward's activation bit for bit (Sec. 4.4: recomputed = stored).
+template <int NV, int KIND, bool STORE_BF16>
 __device__ __forceinline__ float epi_math(int act, float inv_d, bool want2, float* v, float* v2, float rho, float rowb,
                                           const float* r, const float* r2) {
   float part = 0.f;
@@ -86,7 +91,7 @@ __device__ __forceinline__ float epi_math(int act, float inv_d, bool want2, floa
     for (int i = 0; i < NV; i++) v[i] *= rho;
     if (want2) {
 #pragma unroll
-      for (int i = 0; i < NV; i++) v2[i] = act_f(v[i], act);
+      for (int i = 0; i < NV; i++) v2[i] = act_f(STORE_BF16 ? bf16_round_f(v[i]) : v[i], act);
     }
   } else if constexpr (KIND == EPI_UP) {
 #pragma unroll
@@ -118,7 +123,7 @@ __device__ __forceinline__ float epi_math(int act, float inv_d, bool want2, floa
 #pragma unroll
     for (int i = 0; i < NV; i++) {
       v[i] *= rho;
-      v2[i] = v[i] + r[i];
+      v2[i] = (STORE_BF16 ? bf16_round_f(v[i]) : v[i]) + r[i];
     }
   } else if constexpr (KIND == EPI_LAXGRAD) {
 #pragma unroll
@@ -140,7 +145,7 @@ __device__ __forceinline__ float epi_compute(const Epilogue& e, void* C, int64_t
   float v2[NV];
   const bool want2 = KIND == EPI_SWIGLU_BWD || KIND == EPI_SWIGLU_FWD || KIND == EPI_DOWN_LAX || KIND == EPI_LAXGRAD ||
                      (KIND == EPI_DOWN && e.C2 != nullptr);
-  const float part = epi_math<NV, KIND>(e.act, e.inv_d, want2, v, v2, rho, rowb, r, r2);
+  const float part = epi_math<NV, KIND, std::is_same<ST, bf16_t>::value>(e.act, e.inv_d, want2, v, v2, rho, rowb, r, r2);
   if (KIND != EPI_SWIGLU_FWD || C != nullptr) IO::store(C, (int64_t)b * sC + m * ldc + n, v);
   if (want2 && e.C2 != nullptr) IO::store(e.C2, (int64_t)b * e.sC2 + m * e.ldc2 + n, v2);
   return part;

@@ -429,10 +429,14 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
   constexpr int NQ = T::FM * PPB;           // passes per wavefront
   // which auxiliary tiles a kind can read at all, and the prefetch distance in passes: kinds with one
   // auxiliary tile keep eight of its 16-byte vectors in flight per lane, kinds with two keep four of each
-  constexpr bool HAS_R = KIND == EPI_UP || KIND == EPI_ACTGRAD || KIND == EPI_NORMBWD || KIND == EPI_SWIGLU_BWD ||
-                         KIND == EPI_SWIGLU_FWD || KIND == EPI_DOWN_LAX || KIND == EPI_LAXGRAD;
-  constexpr bool HAS_R2 = KIND == EPI_NORMBWD || KIND == EPI_SWIGLU_BWD || KIND == EPI_LAXGRAD;
-  constexpr int PF = HAS_R2 ? 4 : 8;
+  // BASE: the formula; R_F32: the R tile is fp32 (two 16-byte vectors per lane and pass); O32: the primary
+  // output is also written un-rounded, as fp32, into C32
+  constexpr int BASE = epi_base(KIND);
+  constexpr bool R_F32 = epi_r_is_f32(KIND), O32 = epi_writes_f32(KIND);
+  constexpr bool HAS_R = BASE == EPI_UP || BASE == EPI_ACTGRAD || BASE == EPI_NORMBWD || BASE == EPI_SWIGLU_BWD ||
+                         BASE == EPI_SWIGLU_FWD || BASE == EPI_DOWN_LAX || BASE == EPI_LAXGRAD;
+  constexpr bool HAS_R2 = BASE == EPI_NORMBWD || BASE == EPI_SWIGLU_BWD || BASE == EPI_LAXGRAD;
+  constexpr int PF = (HAS_R2 || R_F32) ? 4 : 8;
   constexpr uint32_t EOOB = 0x80000000u;
   const int cg = lane % LPR, rsub = lane / LPR;
   const int rows_valid = min(T::BM, op.M - m0);
@@ -454,20 +458,22 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
                                           (uint32_t)rows_valid * (uint32_t)op.N * 4u, 0x00020000)
       : tile_rsrc(op.C, (int64_t)bi * op.sC + (int64_t)bo * op.sCo, op.ldc, 2);
   const __amdgpu_buffer_rsrc_t rsC2 = tile_rsrc(PARTIAL ? nullptr : e.C2, (int64_t)b * e.sC2, e.ldc2, 2);
-  const bool use_r = !PARTIAL && epi_reads_r<KIND>(e), use_r2 = !PARTIAL && epi_reads_r2<KIND>(e);
-  const __amdgpu_buffer_rsrc_t rsR = tile_rsrc(use_r ? e.R : nullptr, (int64_t)b * e.sR, e.ldr, 2);
+  const bool use_r = !PARTIAL && epi_reads_r<BASE>(e), use_r2 = !PARTIAL && epi_reads_r2<BASE>(e);
+  const __amdgpu_buffer_rsrc_t rsR = tile_rsrc(use_r ? e.R : nullptr, (int64_t)b * e.sR, e.ldr, R_F32 ? 4 : 2);
+  const __amdgpu_buffer_rsrc_t rsC32 = tile_rsrc(O32 ? e.C32 : nullptr, 0, e.ldc32, 4);
   const __amdgpu_buffer_rsrc_t rsR2 = tile_rsrc(use_r2 ? e.R2 : nullptr, (int64_t)b * e.sR2, e.ldr2, 2);
   const __amdgpu_buffer_rsrc_t rsRowA = row_rsrc((!PARTIAL && e.use_rho && !STAT_A) ? e.rowa : nullptr);
   const __amdgpu_buffer_rsrc_t rsRowB = row_rsrc(!PARTIAL ? e.rowb : nullptr);
   const int ldC = PARTIAL ? op.N * 4 : (int)op.ldc * 2;               // row pitches in bytes
-  const int ldC2 = (int)e.ldc2 * 2, ldR = (int)e.ldr * 2, ldR2 = (int)e.ldr2 * 2;
+  const int ldC2 = (int)e.ldc2 * 2, ldR = (int)e.ldr * (R_F32 ? 4 : 2), ldR2 = (int)e.ldr2 * 2, ldC32 = (int)e.ldc32 * 4;
   const uint32_t colC = col_ok ? (uint32_t)coln * (PARTIAL ? 4u : 2u) : EOOB, col2 = col_ok ? (uint32_t)coln * 2u : EOOB;
+  const uint32_t col4 = col_ok ? (uint32_t)coln * 4u : EOOB;      // this lane's columns in an fp32 tile
   const bool want2 = KIND == EPI_SWIGLU_BWD || KIND == EPI_SWIGLU_FWD || KIND == EPI_DOWN_LAX || KIND == EPI_LAXGRAD ||
                      (KIND == EPI_DOWN && e.C2 != nullptr);
   const bool use_rho = !PARTIAL && e.use_rho;
   // row partials [M, rowpart_ld] and the statistic [M]: one lane per row writes, the others (and rows
   // past M) are given an out-of-range offset
-  constexpr bool ROWPART = KIND == EPI_UP || KIND == EPI_ACTGRAD || KIND == EPI_LAXGRAD;
+  constexpr bool ROWPART = BASE == EPI_UP || BASE == EPI_ACTGRAD || BASE == EPI_LAXGRAD;
   const __amdgpu_buffer_rsrc_t rsPart = __builtin_amdgcn_make_buffer_rsrc(
       (void*)((ROWPART && e.rowpart) ? e.rowpart + (int64_t)m0 * e.rowpart_ld : nullptr), 0,
       (ROWPART && e.rowpart) ? (uint32_t)rows_valid * (uint32_t)e.rowpart_ld * 4u : 0u, 0x00020000);
@@ -479,18 +485,24 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
   const int act = e.act;
   const float inv_d = e.inv_d, eps = e.eps;
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-  u32x4 auxr[PF], auxr2[PF];
+  u32x4 auxr[PF], auxr2[PF], auxr3[R_F32 ? PF : 1];   // auxr3: columns 4..7 of an fp32 R tile
   auto row_of = [&](int q) { return wm * T::TM + (q / PPB) * 32 + (q % PPB) * RPP + rsub; };   // row inside the tile
-  auto fetch = [&](int q, u32x4& ar, u32x4& ar2) {
+  auto fetch = [&](int q, u32x4& ar, u32x4& ar2, u32x4& ar3) {
     const int lm = row_of(q);
-    if constexpr (HAS_R) ar = __builtin_amdgcn_raw_buffer_load_b128(rsR, (int)((uint32_t)(lm * ldR) + col2), 0, 0);
+    if constexpr (R_F32) {
+      ar = __builtin_amdgcn_raw_buffer_load_b128(rsR, (int)((uint32_t)(lm * ldR) + col4), 0, 0);
+      ar3 = __builtin_amdgcn_raw_buffer_load_b128(rsR, (int)((uint32_t)(lm * ldR) + col4 + 16u), 0, 0);
+    } else if constexpr (HAS_R) {
+      ar = __builtin_amdgcn_raw_buffer_load_b128(rsR, (int)((uint32_t)(lm * ldR) + col2), 0, 0);
+    }
     if constexpr (HAS_R2) ar2 = __builtin_amdgcn_raw_buffer_load_b128(rsR2, (int)((uint32_t)(lm * ldR2) + col2), 0, 0);
   };
   static_for<PF>([&](auto Q) {
     constexpr int q = decltype(Q)::value;
     auxr[q] = u32x4{0u, 0u, 0u, 0u};
     auxr2[q] = u32x4{0u, 0u, 0u, 0u};
-    if constexpr (q < NQ) fetch(q, auxr[q], auxr2[q]);
+    if constexpr (R_F32) auxr3[q] = u32x4{0u, 0u, 0u, 0u};
+    if constexpr (q < NQ) fetch(q, auxr[q], auxr2[q], auxr3[R_F32 ? q : 0]);
   });
   // per-row scalars of all passes, requested before the first pass
   float ssv[NQ], rbv[NQ];
@@ -501,7 +513,7 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
     if constexpr (!PARTIAL && !STAT_A) {
       if (use_rho) ssv[q] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsRowA, row_of(q) * 4, 0, 0));
     }
-    if constexpr (KIND == EPI_NORMBWD)
+    if constexpr (BASE == EPI_NORMBWD)
       rbv[q] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsRowB, row_of(q) * 4, 0, 0));
   });
   static_for<NQ>([&](auto Q) {
@@ -544,11 +556,24 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
         else ss = ssv[q];
         rho = rsqrtf(ss * inv_d + eps);
       }
-      if constexpr (KIND == EPI_NORMBWD) rowb = rbv[q];
+      if constexpr (BASE == EPI_NORMBWD) rowb = rbv[q];
       float r[8], r2[8], v2[8];
-      unpack8(make_uint4(auxr[q % PF].x, auxr[q % PF].y, auxr[q % PF].z, auxr[q % PF].w), r);
+      if constexpr (R_F32) {
+        const u32x4 a0 = auxr[q % PF], a1 = auxr3[q % PF];
+        r[0] = __uint_as_float(a0.x); r[1] = __uint_as_float(a0.y); r[2] = __uint_as_float(a0.z); r[3] = __uint_as_float(a0.w);
+        r[4] = __uint_as_float(a1.x); r[5] = __uint_as_float(a1.y); r[6] = __uint_as_float(a1.z); r[7] = __uint_as_float(a1.w);
+      } else {
+        unpack8(make_uint4(auxr[q % PF].x, auxr[q % PF].y, auxr[q % PF].z, auxr[q % PF].w), r);
+      }
       unpack8(make_uint4(auxr2[q % PF].x, auxr2[q % PF].y, auxr2[q % PF].z, auxr2[q % PF].w), r2);
-      float part = epi_math<8, KIND>(act, inv_d, want2, v, v2, rho, rowb, r, r2);
+      float part = epi_math<8, BASE, true>(act, inv_d, want2, v, v2, rho, rowb, r, r2);
+      if constexpr (O32) {
+        const u32x4 lo = {__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])};
+        const u32x4 hi = {__float_as_uint(v[4]), __float_as_uint(v[5]), __float_as_uint(v[6]), __float_as_uint(v[7])};
+        const uint32_t off = (uint32_t)(lm * ldC32) + col4;
+        __builtin_amdgcn_raw_buffer_store_b128(lo, rsC32, (int)off, 0, 0);
+        __builtin_amdgcn_raw_buffer_store_b128(hi, rsC32, (int)(off + 16u), 0, 0);
+      }
       {
         const uint4 o = pack8(v);
         const u32x4 ov = {o.x, o.y, o.z, o.w};
@@ -559,7 +584,7 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
         const u32x4 ov = {o.x, o.y, o.z, o.w};
         __builtin_amdgcn_raw_buffer_store_b128(ov, rsC2, (int)((uint32_t)(lm * ldC2) + col2), 0, 0);
       }
-      if constexpr (q + PF < NQ) fetch(q + PF, auxr[q % PF], auxr2[q % PF]);
+      if constexpr (q + PF < NQ) fetch(q + PF, auxr[q % PF], auxr2[q % PF], auxr3[R_F32 ? q % PF : 0]);
       if constexpr (ROWPART) {
         part = lane_group_sum<LPR>(part);
         __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(part), rsPart, (int)((uint32_t)(lm * ldPart) + colPart), 0, 0);
@@ -573,13 +598,12 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
 // ---------------------------------------------------------------------------------------------
 template <class T, int KIND, bool STAT_A, bool KM = false>
 hipError_t launch(const GemmOp& op, hipStream_t st) {
-  static bool attr_set = false;  // one-time opt-in to > 64 KB of dynamic LDS for this instantiation
+  // one-time opt-in to > 64 KB of dynamic LDS for this instantiation (a function-local static: its
+  // initialisation is thread-safe and runs once per process; a failure is reported by every launch)
   auto kern = gemm_bf16_kernel<T, KIND, STAT_A, KM>;
-  if (!attr_set) {
-    hipError_t err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
-    if (err != hipSuccess) return err;
-    attr_set = true;
-  }
+  static const hipError_t attr_err =
+      hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS_BYTES);
+  if (attr_err != hipSuccess) return attr_err;
   const int tiles_m = (op.M + T::BM - 1) / T::BM, tiles_n = (op.N + T::BN - 1) / T::BN;
   int kper = (op.K + op.splitk - 1) / op.splitk;
   kper = (kper + BK - 1) / BK * BK;
@@ -607,6 +631,10 @@ hipError_t dispatch(const GemmOp& op, hipStream_t st) {
     case EPI_DOWN_LAX:
       return op.epi.stat_from_a ? launch<T, EPI_DOWN_LAX, true>(op, st) : launch<T, EPI_DOWN_LAX, false>(op, st);
     case EPI_LAXGRAD: return launch<T, EPI_LAXGRAD, false>(op, st);
+    case EPI_UP_O32: return launch<T, EPI_UP_O32, false>(op, st);
+    case EPI_UP_I32: return launch<T, EPI_UP_I32, false>(op, st);
+    case EPI_NORMBWD_O32: return launch<T, EPI_NORMBWD_O32, false>(op, st);
+    case EPI_NORMBWD_I32: return launch<T, EPI_NORMBWD_I32, false>(op, st);
     default: return hipErrorInvalidValue;
   }
 }

@@ -1,26 +1,43 @@
 """Shared helpers of the GPU parity tests (comparison metric and tolerances).
 
-Metric: max |got - ref| / RMS(ref) per output tensor, ref = fp64 oracle.
-Bar: 1e-4 for the fp32 path, 2e-2 for the bf16 path.  A bf16 tensor cannot be closer to the oracle
-than the oracle's own correctly rounded image; for Gaussian-like tensors of 10^5..10^8 elements
-that storage error alone is 0.8e-2 .. 1.6e-2 in this metric (entries near 4 RMS sit in a binade
-whose half-ulp is 2^-8 * 4).  The 2e-2 is therefore applied to what the computation adds on top of
-that floor: tol = 2e-2 + floor * storage_error(ref), where storage_error is computed exactly (round
-the oracle to bf16, measure) and floor counts the bf16 tensors of that dynamic range between the
-inputs and the result (1 for the single-stage entry points; 3 for attention gradients, which also
-pass through P and dS, and for the block, whose outputs sit behind a chain of about ten rounded
-tensors whose errors add in quadrature).  The plain metric is printed for every tensor so the margin
-to a flat 2e-2 stays visible.
+Metric: max |got - ref| / RMS(ref) per output tensor, ref = fp64 oracle on the same (already rounded)
+inputs.  Bars: 1e-4 for the fp32 path, 2e-2 for the bf16 path.
 
-Because a max over 10^5..10^8 entries is a noisy statistic, two size-independent checks sit beside it
-for every bf16 tensor: the relative L2 error must stay below 1e-2 and the least-squares slope of got
-on ref within 3e-3 of 1.  A dropped or mis-scaled term of a percent or more fails these whatever
-the tensor size.
+How the 2e-2 is applied to a bf16-path tensor:
+
+  1. fp32-stored outputs (weight and gamma gradients in fp32, the row statistics): flat 2e-2.
+  2. bf16-stored outputs: 2e-2 plus ONE unit of the tensor's own storage error, i.e. what rounding the
+     exact result to bf16 costs in this metric.  That term is computed exactly per tensor (round the
+     oracle, measure); for Gaussian-like tensors of 1e5..1e8 elements it is 0.8e-2 .. 1.6e-2, because a
+     few entries reach the binade [4, 8) RMS, whose half-ulp is 2^-8 * 4.  No multiple of it is granted.
+  3. A tensor may exceed (1) / (2) only inside a DERIVED budget: the error of an ideal bf16
+     implementation of the same data flow (tests/bf16_model.py: float64 arithmetic, one
+     round-to-nearest-even wherever the design stores bf16), measured on the same inputs, as a pair
+     (max-norm error, relative L2 error), each the largest over a few realisations of the rounding errors.
+     The tensor must then satisfy BOTH
+         relative L2 error <= 1.1 x the modelled L2 error     (the sharp bound), and
+         max-norm error    <= 1.5 x the modelled max-norm error.
+     The L2 figure is a sum over all elements and agrees between the GPU and the model to a few percent
+     (the budget takes the largest of its realisations), so 1.1 leaves no room for a kernel that adds
+     error of its own.  The maximum over a tensor is an
+     extreme-value statistic of heavy-tailed per-element errors (a weight gradient is dominated by a few
+     tokens with large activations); two realisations of the SAME ideal pipeline differ in it by up to
+     1.4x (tests/test_bf16_model.py shows the spread), hence the wider factor there.
+     The model is pinned to the oracle in tests/test_bf16_model.py; the rule that let a tensor pass is
+     printed with every check.
+
+Two size-independent checks sit beside the max-norm for every bf16-path tensor: the relative L2 error
+must stay below 1e-2 (or inside the modelled budget, rule 3) and the least-squares slope of got on ref
+within 3e-3 of 1.  A dropped or mis-scaled term of a percent or more fails these whatever the tensor
+size.
 """
 import numpy as np
 import torch
 
 TOL = {torch.bfloat16: 2e-2, torch.float32: 1e-4}
+BUDGET_MARGIN_MAX = 1.5
+BUDGET_MARGIN_L2 = 1.1
+L2_BOUND = 1e-2
 
 
 def _np(got):
@@ -60,19 +77,28 @@ def l2_and_slope(got, ref):
     return float(np.linalg.norm(got - ref) / np.sqrt(rr)), float(np.dot(got, ref) / rr)
 
 
-def check(name, got, ref, dtype, scale=1.0, floor=None):
-    """dtype: the path's arithmetic type (picks the bar).  floor: see the module docstring; None means
-    1 for a tensor stored in bf16 and 0 otherwise."""
+def check(name, got, ref, dtype, budget=None, scale=1.0):
+    """dtype: the path's arithmetic type (picks the bar).  budget: (max-norm error, relative L2 error) of
+    an ideal bf16 pipeline for this tensor (rule 3 of the module docstring), or None when no excess is
+    granted."""
     e = relerr(got, ref)
-    if floor is None:
-        floor = 1.0 if (isinstance(got, torch.Tensor) and got.dtype == torch.bfloat16) else 0.0
-    fl = storage_error(ref, torch.bfloat16) * floor if floor else 0.0
-    tol = TOL[dtype] * scale + fl
+    stored_bf16 = isinstance(got, torch.Tensor) and got.dtype == torch.bfloat16
+    own = storage_error(ref, torch.bfloat16) if (stored_bf16 and dtype == torch.bfloat16) else 0.0
+    tol = TOL[dtype] * scale + own
+    rule = "flat" if own == 0.0 else "flat+own storage"
     l2, slope = l2_and_slope(got, ref)
-    print(f"    parity {name}: max/rms {e:.3e} (tol {TOL[dtype] * scale:.1e} + floor {fl:.2e})  l2 {l2:.2e}  "
-          f"slope-1 {slope - 1:+.1e}", flush=True)
-    assert e <= tol, f"{name}: max|err|/RMS(ref) = {e:.3e} > {tol:.2e}"
+    l2_tol = L2_BOUND * scale
+    if budget is not None:
+        bmax, bl2 = budget
+        l2_tol = max(l2_tol, BUDGET_MARGIN_L2 * bl2)
+        if e > tol:
+            tol, rule = BUDGET_MARGIN_MAX * bmax, "modelled bf16 budget (max x1.5, l2 x1.1)"
+            l2_tol = BUDGET_MARGIN_L2 * bl2
+    btxt = "-" if budget is None else f"max {budget[0]:.2e} l2 {budget[1]:.2e}"
+    print(f"    parity {name}: max/rms {e:.3e}  l2 {l2:.2e}  slope-1 {slope - 1:+.1e}  (flat {TOL[dtype] * scale:.1e}, "
+          f"own storage {own:.2e}, model {btxt}; rule: {rule})", flush=True)
+    assert e <= tol, f"{name}: max|err|/RMS(ref) = {e:.3e} > {tol:.2e} ({rule})"
     if dtype == torch.bfloat16 and np.asarray(ref).size >= 64:
-        assert l2 <= 1e-2 * scale, f"{name}: relative L2 error {l2:.3e} > 1e-2"
+        assert l2 <= l2_tol, f"{name}: relative L2 error {l2:.3e} > {l2_tol:.2e}"
         assert abs(slope - 1) <= 3e-3 * scale, f"{name}: slope {slope:.5f} is off 1"
     return e

@@ -9,6 +9,7 @@ import numpy as np
 import pytest
 import torch
 
+import bf16_model as M
 import synth_inputs as si
 from oracle import lowrank_oracle as orc
 from parity import check
@@ -17,9 +18,12 @@ from paper_2512_12131_amd import binding as B
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 EPS = 1e-5
-FL = 3.0   # storage-floor units allowed on top of 2e-2 for block-level activations (see parity.py)
-FLW = 5.0  # ... and for the block's weight gradients: heavy-tailed tensors behind the longest chains
-           # (forward, re-forward and backward roundings); their sharp check is the 1e-2 L2 bound
+
+
+def _budget(X, P, DY, Bn, S, H, y_ref, c, dx_ref, g_ref, **kw):
+    """Per-tensor error of the ideal bf16 pipeline (tests/bf16_model.py) against the oracle: what a tensor
+    may reach beyond the flat tolerance (parity.py, rule 3)."""
+    return M.block_budget(X, P, DY, Bn, S, H, 128, EPS, y_ref, c, dx_ref, g_ref, **kw)
 
 
 def _oracle_params(p):
@@ -73,17 +77,18 @@ def test_block_small_full_parity(Bn, S, H, f, r, norm):
     y_ref, c = orc.block_fwd(X, P, Bn, S, H, 128, EPS)
     dx_ref, g_ref = orc.block_bwd(X, P, DY, Bn, S, H, 128, EPS)
     dt = torch.bfloat16
-    check("y", y, y_ref, dt, floor=FL)
-    check("z_qkv", ck["z_qkv"], np.concatenate([c["z_q"], c["z_k"], c["z_v"]], 1), dt, floor=FL)
-    check("z_o", ck["z_o"], c["z_o"], dt, floor=FL)
-    check("z_gu", ck["z_gu"], np.concatenate([c["z_g"], c["z_u"]], 1), dt, floor=FL)
-    check("z_d", ck["z_d"], c["z_d"], dt, floor=FL)
+    bud = _budget(X, P, DY, Bn, S, H, y_ref, c, dx_ref, g_ref, two_pass=(norm == B.LR_NORM_TWO_PASS))
+    check("y", y, y_ref, dt, bud["y"])
+    check("z_qkv", ck["z_qkv"], np.concatenate([c["z_q"], c["z_k"], c["z_v"]], 1), dt, bud["z_qkv"])
+    check("z_o", ck["z_o"], c["z_o"], dt, bud["z_o"])
+    check("z_gu", ck["z_gu"], np.concatenate([c["z_g"], c["z_u"]], 1), dt, bud["z_gu"])
+    check("z_d", ck["z_d"], c["z_d"], dt, bud["z_d"])
     check("s1", ck["s1"], orc.rms_stat(X), torch.float32, scale=10)
-    check("s2", ck["s2"], orc.rms_stat(c["h1"]), torch.bfloat16, floor=0.0)
-    check("dx", dx, dx_ref, dt, floor=FL)
+    check("s2", ck["s2"], orc.rms_stat(c["h1"]), torch.bfloat16)
+    check("dx", dx, dx_ref, dt, bud["dx"])
     got = _unpack_grads(grads, f, r)
     for name, ref in g_ref.items():
-        check("d" + name, got[name], ref, dt, floor=FLW)
+        check("d" + name, got[name], ref, dt, bud["d" + name])
     # pad region of the ffn-sized gradients stays zero
     if f_ld > f:
         assert float(grads["w_dn_d"][:, f:].abs().max()) == 0.0
@@ -100,13 +105,14 @@ def test_block_odd_ffn_padding():
     assert f_ld == 344
     P = _oracle_params(case["params"])
     X, DY = si.f64(case["x"]), si.f64(case["dy"])
-    y_ref, _ = orc.block_fwd(X, P, Bn, S, H, 128, EPS)
+    y_ref, c = orc.block_fwd(X, P, Bn, S, H, 128, EPS)
     dx_ref, g_ref = orc.block_bwd(X, P, DY, Bn, S, H, 128, EPS)
-    check("y", y, y_ref, torch.bfloat16, floor=FL)
-    check("dx", dx, dx_ref, torch.bfloat16, floor=FL)
+    bud = _budget(X, P, DY, Bn, S, H, y_ref, c, dx_ref, g_ref)
+    check("y", y, y_ref, torch.bfloat16, bud["y"])
+    check("dx", dx, dx_ref, torch.bfloat16, bud["dx"])
     got = _unpack_grads(grads, f, r)
     for name in ("wd_d", "wu_g", "wu_u"):
-        check("d" + name, got[name], g_ref[name], torch.bfloat16, floor=FLW)
+        check("d" + name, got[name], g_ref[name], torch.bfloat16, bud["d" + name])
     assert float(grads["w_dn_d"][:, f:].abs().max()) == 0.0
 
 
@@ -126,13 +132,14 @@ def test_block_identity_sigma():
     y_silu, _ = orc.block_fwd(X, P, Bn, S, H, 128, EPS)
     assert np.abs(y_silu - y_ref).max() > 0.1 * np.sqrt(np.mean(y_ref ** 2))
     dt = torch.bfloat16
-    check("y", y, y_ref, dt, floor=FL)
-    check("z_gu", ck["z_gu"], np.concatenate([c["z_g"], c["z_u"]], 1), dt, floor=FL)
-    check("z_d", ck["z_d"], c["z_d"], dt, floor=FL)
-    check("dx", dx, dx_ref, dt, floor=FL)
+    bud = _budget(X, P, DY, Bn, S, H, y_ref, c, dx_ref, g_ref, act="identity")
+    check("y", y, y_ref, dt, bud["y"])
+    check("z_gu", ck["z_gu"], np.concatenate([c["z_g"], c["z_u"]], 1), dt, bud["z_gu"])
+    check("z_d", ck["z_d"], c["z_d"], dt, bud["z_d"])
+    check("dx", dx, dx_ref, dt, bud["dx"])
     got = _unpack_grads(grads, f, r)
     for name, ref in g_ref.items():
-        check("d" + name, got[name], ref, dt, floor=FLW)
+        check("d" + name, got[name], ref, dt, bud["d" + name])
 
 
 def test_block_statistic_chained_between_blocks():
@@ -155,16 +162,17 @@ def test_block_statistic_chained_between_blocks():
     dx2, g2 = B.lr_block_bwd(desc2, p2, y1, dy, ck2)
     torch.cuda.synchronize()
     X2 = si.f64(y1)                                   # block 2's input as stored
-    check("s1 of block 2", ck2["s1"], orc.rms_stat(X2), torch.bfloat16, floor=0.0)
+    check("s1 of block 2", ck2["s1"], orc.rms_stat(X2), torch.bfloat16)
     P2 = _oracle_params(case2["params"])
     DY = si.f64(case1["dy"])
-    y_ref, _ = orc.block_fwd(X2, P2, Bn, S, H, 128, EPS)
+    y_ref, c = orc.block_fwd(X2, P2, Bn, S, H, 128, EPS)
     dx_ref, g_ref = orc.block_bwd(X2, P2, DY, Bn, S, H, 128, EPS)
-    check("y2", y2, y_ref, torch.bfloat16, floor=FL)
-    check("dx2", dx2, dx_ref, torch.bfloat16, floor=FL)
+    bud = _budget(X2, P2, DY, Bn, S, H, y_ref, c, dx_ref, g_ref)
+    check("y2", y2, y_ref, torch.bfloat16, bud["y"])
+    check("dx2", dx2, dx_ref, torch.bfloat16, bud["dx"])
     got = _unpack_grads(g2, f, r)
     for name in ("wd_q", "wu_k", "wd_g", "gamma1"):
-        check("d" + name, got[name], g_ref[name], torch.bfloat16, floor=FLW)
+        check("d" + name, got[name], g_ref[name], torch.bfloat16, bud["d" + name])
 
 
 def test_block_accumulate_and_determinism():
@@ -208,12 +216,14 @@ def test_block_full_shape_batch0(name):
     dx_ref, g_ref = orc.block_bwd(X0, P, DY0, 1, S, H, 128, EPS)
     print("  oracle bwd done", flush=True)
     dt = torch.bfloat16
-    check("y[b0]", y[:S], y_ref, dt, floor=FL)
-    check("z_qkv[b0]", ck["z_qkv"][:S], np.concatenate([c["z_q"], c["z_k"], c["z_v"]], 1), dt, floor=FL)
-    check("z_o[b0]", ck["z_o"][:S], c["z_o"], dt, floor=FL)
-    check("z_gu[b0]", ck["z_gu"][:S], np.concatenate([c["z_g"], c["z_u"]], 1), dt, floor=FL)
-    check("z_d[b0]", ck["z_d"][:S], c["z_d"], dt, floor=FL)
-    check("dx[b0]", dx[:S], dx_ref, dt, floor=FL)
+    bud = _budget(X0, P, DY0, 1, S, H, y_ref, c, dx_ref, g_ref, realisations=2)
+    print("  bf16 model done", flush=True)
+    check("y[b0]", y[:S], y_ref, dt, bud["y"])
+    check("z_qkv[b0]", ck["z_qkv"][:S], np.concatenate([c["z_q"], c["z_k"], c["z_v"]], 1), dt, bud["z_qkv"])
+    check("z_o[b0]", ck["z_o"][:S], c["z_o"], dt, bud["z_o"])
+    check("z_gu[b0]", ck["z_gu"][:S], np.concatenate([c["z_g"], c["z_u"]], 1), dt, bud["z_gu"])
+    check("z_d[b0]", ck["z_d"][:S], c["z_d"], dt, bud["z_d"])
+    check("dx[b0]", dx[:S], dx_ref, dt, bud["dx"])
     # weight gradients: batch element 0 alone against the oracle ...
     desc1 = B.make_block_desc(1, S, d, H, 128, f, f_ld, r, eps=EPS)
     x, dy = case["x"].to(DEV), case["dy"].to(DEV)
@@ -226,7 +236,7 @@ def test_block_full_shape_batch0(name):
             torch.cuda.synchronize()
             got0 = _unpack_grads(gb, f, r)
             for nm, ref in g_ref.items():
-                check("d" + nm + "[b0]", got0[nm], ref, dt, floor=FLW)
+                check("d" + nm + "[b0]", got0[nm], ref, dt, bud["d" + nm])
             acc = gb
         else:
             B.lr_block_bwd(desc1, packed, xb, dyb, ckb, grads=acc, accumulate=True)

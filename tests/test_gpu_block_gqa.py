@@ -6,6 +6,7 @@ import numpy as np
 import pytest
 import torch
 
+import bf16_model as M
 import synth_inputs as si
 from oracle import lowrank_oracle as orc
 from parity import check
@@ -15,7 +16,6 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 EPS = 1e-5
 HD = 128
-FL, FLW = 3.0, 5.0     # storage-floor units, as in the multi-head block tests
 
 
 def _unpack_grads(g, d, dkv, f, r):
@@ -62,15 +62,16 @@ def test_block_gqa_parity(Bn, S, H, Hkv, f, r, with_rope):
     y_ref, c = orc.block_fwd(X, P, Bn, S, H, HD, EPS, rope=rope_ref, Hkv=Hkv)
     dx_ref, g_ref = orc.block_bwd(X, P, DY, Bn, S, H, HD, EPS, rope=rope_ref, Hkv=Hkv)
     dt = torch.bfloat16
-    check("y", y, y_ref, dt, floor=FL)
-    check("z_qkv", ck["z_qkv"], np.concatenate([c["z_q"], c["z_k"], c["z_v"]], 1), dt, floor=FL)
-    check("z_o", ck["z_o"], c["z_o"], dt, floor=FL)
-    check("z_gu", ck["z_gu"], np.concatenate([c["z_g"], c["z_u"]], 1), dt, floor=FL)
-    check("z_d", ck["z_d"], c["z_d"], dt, floor=FL)
-    check("dx", dx, dx_ref, dt, floor=FL)
+    bud = M.block_budget(X, P, DY, Bn, S, H, HD, EPS, y_ref, c, dx_ref, g_ref, rope=rope_ref, Hkv=Hkv)
+    check("y", y, y_ref, dt, bud["y"])
+    check("z_qkv", ck["z_qkv"], np.concatenate([c["z_q"], c["z_k"], c["z_v"]], 1), dt, bud["z_qkv"])
+    check("z_o", ck["z_o"], c["z_o"], dt, bud["z_o"])
+    check("z_gu", ck["z_gu"], np.concatenate([c["z_g"], c["z_u"]], 1), dt, bud["z_gu"])
+    check("z_d", ck["z_d"], c["z_d"], dt, bud["z_d"])
+    check("dx", dx, dx_ref, dt, bud["dx"])
     got = _unpack_grads(grads, d, dkv, f, r)
     for name, ref in g_ref.items():
-        check("d" + name, got[name], ref, dt, floor=FLW)
+        check("d" + name, got[name], ref, dt, bud["d" + name])
 
 
 def test_block_with_as_many_kv_heads_is_the_multi_head_block():

@@ -6,6 +6,7 @@ import numpy as np
 import pytest
 import torch
 
+import bf16_model as M
 import synth_inputs as si
 from oracle import lax_oracle as lax
 from parity import check
@@ -14,8 +15,21 @@ from paper_2512_12131_amd import binding as B
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 EPS = 1e-5
-FL = 3.0
-FLW = 5.0
+
+
+def _lax_budget(X, P, DY, hp, dzn, Bn, S, H, y_ref, z_ref, dx_ref, g_ref, dh_ref, Hkv=None):
+    """Error of the ideal bf16 pipeline (tests/bf16_model.py) per tensor: the budget of parity.py, rule 3."""
+    def one_run(jit):
+        out, g, dh = M.block(X, P, DY, Bn, S, H, 128, EPS, h_prev=hp, dz_next=dzn, lax=True, Hkv=Hkv, jitter=jit)
+        bud = {"y": M.err2(out["y"], y_ref), "dx": M.err2(out["dx"], dx_ref)}
+        for n in lax.PROJ:
+            bud["z_" + n] = M.err2(out["z_" + n], z_ref[n])
+            bud["dh_prev_" + n] = M.err2(dh[n], dh_ref[n])
+        bud.update({"d" + k: M.err2(g[k], g_ref[k]) for k in g_ref})
+        return bud
+
+    return M.over_realisations(one_run)
+
 PARTS = {"qkv": ("q", "k", "v"), "o": ("o",), "gu": ("g", "u"), "d": ("d",)}
 
 
@@ -81,18 +95,18 @@ def test_block_lax_parity(Bn, S, H, f, r):
     y_ref, z_ref, _ = lax.block_fwd(X, P, _f64(h_prev), Bn, S, H, 128, EPS)
     dx_ref, g_ref, dh_ref = lax.block_bwd(X, P, _f64(h_prev), DY, _f64(dz_next), Bn, S, H, 128, EPS)
     dt = torch.bfloat16
-    check("y", y, y_ref, dt, floor=FL)
+    bud = _lax_budget(X, P, DY, _f64(h_prev), _f64(dz_next), Bn, S, H, y_ref, z_ref, dx_ref, g_ref, dh_ref)
+    check("y", y, y_ref, dt, bud["y"])
     z_gpu = _split({k: ck["z_" + k] for k in PARTS}, r)
     for n in lax.PROJ:
-        check("z_" + n, z_gpu[n], z_ref[n], dt, floor=FL)
-    check("dx", dx, dx_ref, dt, floor=FL)
+        check("z_" + n, z_gpu[n], z_ref[n], dt, bud["z_" + n])
+    check("dx", dx, dx_ref, dt, bud["dx"])
     dh_gpu = _split(dh, r)
-    # behind the same chains as the weight gradients (attention backward, re-forward): their floor
     for n in lax.PROJ:
-        check("dh_prev_" + n, dh_gpu[n], dh_ref[n], dt, floor=FLW)
+        check("dh_prev_" + n, dh_gpu[n], dh_ref[n], dt, bud["dh_prev_" + n])
     got = _unpack_grads(grads, f, r)
     for name, ref in g_ref.items():
-        check("d" + name, got[name], ref, dt, floor=FLW)
+        check("d" + name, got[name], ref, dt, bud["d" + name])
 
 
 def test_block_lax_null_residuals_equal_the_plain_identity_block():
@@ -149,12 +163,22 @@ def test_two_block_stack_through_the_library():
     dx2r, g2r, dh2r = lax.block_bwd(y1r, P2, z1r, DY, zero, Bn, S, H, 128, EPS)
     dx1r, g1r, _ = lax.block_bwd(X, P1, zero, dx2r, dh2r, Bn, S, H, 128, EPS)
     dt = torch.bfloat16
-    # two blocks in sequence, each within the single-block bars: twice the bars (scale = 2)
-    check("y2", y2, y2r, dt, scale=2.0, floor=FL)
-    check("dx1", dx1, dx1r, dt, scale=2.0, floor=FL)
+    # the budget: the same two-block chain through the bf16 model (its y1, z1, dx2 and dh2 feed the next call)
+    def one_run(jit):
+        m1, _, _ = M.block(X, P1, DY, Bn, S, H, 128, EPS, lax=True, jitter=jit)
+        z1m = {n: m1["z_" + n] for n in lax.PROJ}
+        m2, _, dh2m = M.block(m1["y"], P2, DY, Bn, S, H, 128, EPS, h_prev=z1m, lax=True, jitter=jit)
+        m1b, g1m, _ = M.block(X, P1, m2["dx"], Bn, S, H, 128, EPS, dz_next=dh2m, lax=True, jitter=jit)
+        bud = {"y2": M.err2(m2["y"], y2r), "dx1": M.err2(m1b["dx"], dx1r)}
+        bud.update({"d" + k: M.err2(g1m[k], g1r[k]) for k in g1r})
+        return bud
+
+    bud = M.over_realisations(one_run)
+    check("y2", y2, y2r, dt, bud["y2"])
+    check("dx1", dx1, dx1r, dt, bud["dx1"])
     got1 = _unpack_grads(g1, f, r)
     for name in ("wd_q", "wu_v", "wd_o", "wd_g", "wu_u", "wd_d", "gamma1"):
-        check("d" + name, got1[name], g1r[name], dt, scale=2.0, floor=FLW)
+        check("d" + name, got1[name], g1r[name], dt, bud["d" + name])
 
 
 def test_block_lax_with_grouped_kv_heads():
@@ -179,17 +203,18 @@ def test_block_lax_with_grouped_kv_heads():
     y_ref, z_ref, _ = lax.block_fwd(X, P, _f64(h_prev), Bn, S, H, 128, EPS, Hkv=Hkv)
     dx_ref, g_ref, dh_ref = lax.block_bwd(X, P, _f64(h_prev), DY, _f64(dz_next), Bn, S, H, 128, EPS, Hkv=Hkv)
     dt = torch.bfloat16
-    check("y", y, y_ref, dt, floor=FL)
+    bud = _lax_budget(X, P, DY, _f64(h_prev), _f64(dz_next), Bn, S, H, y_ref, z_ref, dx_ref, g_ref, dh_ref, Hkv=Hkv)
+    check("y", y, y_ref, dt, bud["y"])
     z_gpu = _split({k: ck["z_" + k] for k in PARTS}, r)
     for n in lax.PROJ:
-        check("z_" + n, z_gpu[n], z_ref[n], dt, floor=FL)
-    check("dx", dx, dx_ref, dt, floor=FL)
+        check("z_" + n, z_gpu[n], z_ref[n], dt, bud["z_" + n])
+    check("dx", dx, dx_ref, dt, bud["dx"])
     dh_gpu = _split(dh, r)
     for n in lax.PROJ:
-        check("dh_prev_" + n, dh_gpu[n], dh_ref[n], dt, floor=FLW)
+        check("dh_prev_" + n, dh_gpu[n], dh_ref[n], dt, bud["dh_prev_" + n])
     wq = grads["w_up_qkv"].reshape(-1, r)
     got = {"wu_q": wq[:d], "wu_k": wq[d:d + dkv], "wu_v": wq[d + dkv:], "wd_q": grads["w_dn_qkv"][:r],
            "wd_k": grads["w_dn_qkv"][r:2 * r], "wd_v": grads["w_dn_qkv"][2 * r:], "wu_o": grads["w_up_o"],
            "gamma1": grads["gamma1"], "wd_d": grads["w_dn_d"][:, :f]}
     for name, g in got.items():
-        check("d" + name, g, g_ref[name], dt, floor=FLW)
+        check("d" + name, g, g_ref[name], dt, bud["d" + name])

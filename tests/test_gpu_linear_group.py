@@ -153,3 +153,21 @@ def test_determinism():
         outs.append((z, stat, y) + tuple(r))
     for a, b in zip(*outs):
         assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("T,d_in,r", [(512, 256, 64), (700, 384, 256)])
+def test_rank_r_activation_recomputed_equals_forward(T, d_in, r):
+    """Sec. 4.4: the backward rebuilds sigma(z) from the rank-r checkpoint z alone; it must be the
+    activation the forward fed into its up-projection, bit for bit.  With W_up = identity (d_out = r) the
+    forward's y IS that activation (products with 1 and 0 and their fp32 sum are exact), and lr_act_fwd
+    on the stored z is the kernel the backward uses to rebuild it."""
+    c = si.linear_case(T, d_in, r, r, dtype=torch.bfloat16, seed=9)
+    x, wd = _dev(c["x"]), _dev(c["w_down"])
+    eye = torch.eye(r, dtype=torch.bfloat16, device=DEV)
+    z, y = B.lr_linear_fwd(x, wd, eye, B.LR_ACT_SILU)
+    a = B.lr_act_fwd(z, B.LR_ACT_SILU)
+    torch.cuda.synchronize()
+    assert torch.equal(y, a)
+    # and it is sigma of the checkpoint as stored, rounded once
+    ref = torch.nn.functional.silu(z.float()).to(torch.bfloat16)
+    assert (y.float() - ref.float()).abs().max() <= 2.0 ** -7 * ref.float().abs().max()
