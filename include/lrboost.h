@@ -70,6 +70,22 @@ int lr_linear_bwd(const void* x, int64_t ldx, const void* w_down, const void* w_
                   int64_t d_out, int act, int dt, int grad_dt, int accumulate, void* ws,
                   size_t ws_bytes, void* stream);
 
+/* lr_linear_fwd for callers that cannot allocate device memory or hand over a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and
+ * error codes as lr_linear_fwd without (ws, ws_bytes): the rank-r activation between the two GEMMs is
+ * kept in a device array that is part of the library image (LR_LINEAR_STATIC_SCRATCH_BYTES per GPU, held
+ * from the moment the library is loaded on that GPU until the process ends).  The call allocates and
+ * frees nothing.  Limit: T * r * (2 for LR_BF16, 4 for LR_F32) bytes must fit the array, otherwise
+ * LR_EWORKSPACE and nothing is enqueued.  All calls on one GPU share the array: calls that may run
+ * concurrently on one GPU (different streams, different host threads) race on it and must be serialised
+ * by the caller.  Nothing in it needs clearing between calls (every element a call reads, it has
+ * written).  The first call on a device looks up the array's address, which is a set-up step: make it
+ * before a stream capture begins, not inside one.                                                    */
+#define LR_LINEAR_STATIC_SCRATCH_BYTES (32u << 20)
+int lr_linear_fwd_static(const void* x, int64_t ldx, const void* w_down, const void* w_up, void* z,
+                         void* y, int64_t ldy, int64_t T, int64_t d_in, int64_t r, int64_t d_out,
+                         int act, int dt, void* stream);
+
 /* ---- G projections sharing one input (Sec. 4.3 and App. "Linear Grouping Details") ---- */
 /* w_down_cat[G*r, d_in]: the G down-projection weights concatenated along the rank axis (one
  * GEMM); w_up_stack[G, d_out, r]: stacked up-projection weights (one batched GEMM over the

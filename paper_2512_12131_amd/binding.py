@@ -56,6 +56,7 @@ _SIGS = {
     "lr_status_string": (C.c_char_p, [_int]),
     "lr_linear_workspace_bytes": (_sz, [_i64, _i64, _i64, _i64, _int, _int]),
     "lr_linear_fwd": (_int, [_vp, _i64, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _int, _int, _vp, _sz, _vp]),
+    "lr_linear_fwd_static": (_int, [_vp, _i64, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _int, _int, _vp]),
     "lr_linear_bwd": (_int, [_vp, _i64, _vp, _vp, _vp, _vp, _i64, _vp, _i64, _vp, _vp, _i64, _i64, _i64, _i64, _int,
                              _int, _int, _int, _vp, _sz, _vp]),
     "lr_group_workspace_bytes": (_sz, [_int, _i64, _i64, _i64, _i64, _int, _int]),
@@ -157,6 +158,17 @@ def lr_linear_fwd(x, w_down, w_up, act=LR_ACT_SILU):
     ws = _ws(nb, x.device)
     _check(lib().lr_linear_fwd(_p(x), _rowmajor(x), _p(w_down), _p(w_up), _p(z), _p(y), d_out, T, d_in, r, d_out, act,
                                dt, _p(ws), nb, _stream()), "lr_linear_fwd")
+    return z, y
+
+
+def lr_linear_fwd_static(x, w_down, w_up, z, y, act=LR_ACT_SILU):
+    """The forward of one bottleneck layer through the entry point that allocates nothing: the caller
+    passes the outputs z[T, r] and y[T, d_out]; the library's scratch is a device array of its own."""
+    T, d_in = x.shape
+    r, d_out = w_down.shape[0], w_up.shape[0]
+    assert z.shape == (T, r) and y.shape == (T, d_out) and z.is_contiguous() and y.is_contiguous()
+    _check(lib().lr_linear_fwd_static(_p(x), _rowmajor(x), _p(w_down), _p(w_up), _p(z), _p(y), d_out, T, d_in, r, d_out,
+                                      act, _dt(x), _stream()), "lr_linear_fwd_static")
     return z, y
 
 

@@ -4,6 +4,7 @@
 // launches, only workspace carving) to answer *_workspace_bytes(), once for real.  That keeps the
 // size query and the actual use of the workspace from drifting apart.
 #include <cstring>
+#include <mutex>
 
 #include "common.h"
 
@@ -742,6 +743,56 @@ int lr_linear_bwd(const void* x, int64_t ldx, const void* w_down, const void* w_
   a.dw_up = dw_up; a.ldx = ldx; a.lddy = lddy; a.lddx = lddx; a.T = T; a.d_in = d_in; a.r = r; a.d_out = d_out;
   a.act = act; a.accumulate = accumulate;
   linear_bwd_seq(c, a);
+  return status_of(c);
+}
+
+// ---- linear forward for callers that cannot allocate ------------------------------------------------
+// The rank-r activation sigma(z) between the two GEMMs of lr_linear_fwd, which that entry point keeps in
+// the caller's workspace, lives here in a file-scope device array.  Each GPU holds its own copy of the
+// array at its own address: the address is looked up once per device (with that device current) and kept;
+// host code only ever uses that looked-up pointer, never the array's name.
+}  // extern "C"
+namespace {
+static __device__ __align__(256) unsigned char g_linear_scratch[LR_LINEAR_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int linear_scratch_of_current_device(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LR_ELAUNCH;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_linear_scratch)) != hipSuccess || !p) return LR_ELAUNCH;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return LR_OK;
+}
+}  // namespace
+extern "C" {
+
+int lr_linear_fwd_static(const void* x, int64_t ldx, const void* w_down, const void* w_up, void* z, void* y,
+                         int64_t ldy, int64_t T, int64_t d_in, int64_t r, int64_t d_out, int act, int dt,
+                         void* stream) {
+  TRY(check_dt(dt)); TRY(check_act(act));
+  if (T < 0 || T > 0x7fffffffLL) return LR_EINVAL;
+  TRY(check_sizes_fit_int({d_in, r, d_out}));
+  if (ldx < d_in || ldy < d_out) return LR_EINVAL;
+  TRY(check_dims_bf16(dt, {d_in, r, d_out, ldx, ldy}));
+  if (T == 0) return LR_OK;
+  TRY(check_ptrs(dt, {x, w_down, w_up, z, y}));
+  // the same carving as lr_linear_fwd, run dry: what the sequence takes from its scratch
+  Ctx dry; dry.dry = true; dry.dt = dt;
+  LinArgs a{}; a.x = x; a.w_down = w_down; a.w_up = w_up; a.z = z; a.y = y; a.ldx = ldx; a.ldy = ldy;
+  a.T = T; a.d_in = d_in; a.r = r; a.d_out = d_out; a.act = act;
+  linear_fwd_seq(dry, a);
+  if (dry.peak > (size_t)LR_LINEAR_STATIC_SCRATCH_BYTES) return LR_EWORKSPACE;
+  void* scratch = nullptr;
+  TRY(linear_scratch_of_current_device(&scratch));
+  Ctx c; c.base = (char*)scratch; c.cap = LR_LINEAR_STATIC_SCRATCH_BYTES; c.dt = dt; c.st = (hipStream_t)stream;
+  linear_fwd_seq(c, a);
   return status_of(c);
 }
 
