@@ -2,9 +2,11 @@
 
 One "step" = lr_block_fwd + lr_block_bwd (all forward and backward rows of the hot path, with the
 backward re-forwarding from the rank-r checkpoints) on one synthetic batch that is already resident
-in HBM.  Prints ONE JSON line with the whole-job throughput in TFLOP/s of executed GEMM + attention
-work, a roofline object for the dominant kernel class (the bf16 MFMA GEMMs, timed live with HIP
-events on the stream they run on) and the fp64 CPU oracle timed on a bounded sample.
+in HBM.  Prints ONE JSON line with the whole-job throughput in TFLOP/s (model FLOPs of the block's
+forward + backward over wall time; the executed rate, which also counts the re-forward, beside it), a
+roofline object for the dominant kernel class (the bf16 MFMA GEMMs, timed live with HIP events on the
+stream they run on, in total and per launch class), the attention calls timed the same way, and the fp64
+CPU oracle timed on a bounded sample.
 """
 from __future__ import annotations
 
@@ -71,40 +73,132 @@ def block_flops(B, S, d, H, f, r, dkv=None):
             "lin_fwd": lin_fwd, "attn_fwd": attn_fwd}
 
 
-def gemm_classes(B, S, d, H, f, r, dkv=None):
-    """Every GEMM launch class of one block step as (FLOPs, ideal bytes): 2MNK and one read of each
-    operand plus one write of the result (bf16; weight gradients leave as fp32)."""
+TAG_NAMES = {0: "store", 1: "down: row scale + sigma", 2: "up + residual", 3: "sigma' (+ row statistic)", 4: "RMSNorm backward",
+             5: "weight gradient (k-major, split-K partials)", 6: "SwiGLU backward", 7: "SwiGLU forward", 8: "down (LaX)",
+             9: "sigma' (LaX)", 10: "up + residual, fp32 copy out", 11: "up + fp32 residual", 12: "RMSNorm backward, fp32 copy out",
+             13: "RMSNorm backward, fp32 residual", 32: "attention forward", 33: "attention backward"}
+
+
+def gemm_launches(B, S, d, H, f, r, dkv=None, f_ld=None):
+    """Every projection-GEMM launch of one block step (forward + backward with re-forward), as dicts:
+    what, tag (epilogue class), M, N, K, batch as launched (ffn axis padded to f_ld), flops = 2MNK over the
+    logical sizes, bytes = the traffic an ideal kernel has (each operand read once, every output written
+    once, the auxiliary tiles an epilogue reads counted too; bf16 unless noted)."""
     T = B * S
     dkv = d if dkv is None else dkv
+    f_ld = f if f_ld is None else f_ld
     out = []
 
-    def g(M, N, K, count=1, out_bytes=2):
-        out.append((count * 2.0 * M * N * K, count * (2.0 * (M * K + N * K) + out_bytes * M * N)))
+    def g(what, tag, M, N, K, batch=1, aux=0.0, outs=None, n_log=None, k_log=None, m_log=None):
+        n_l, k_l, m_l = n_log or N, k_log or K, m_log or M
+        fl = batch * 2.0 * m_l * n_l * k_l
+        by = batch * (2.0 * (m_l * k_l + n_l * k_l) + (2.0 * m_l * n_l if outs is None else outs)) + aux
+        out.append({"what": what, "tag": tag, "M": M, "N": N, "K": K, "batch": batch, "flops": fl, "bytes": by})
 
-    # (input width, output width, group size) of the four grouped low-rank layers: qkv, o, gate/up, down
-    # members as (output width, how many)
-    qkv = ((d, 3),) if dkv == d else ((d, 1), (dkv, 2))
-    for d_in, members in ((d, qkv), (d, ((d, 1),)), (d, ((f, 2),)), (f, ((d, 1),))):
-        G = sum(n for _, n in members)
-        g(T, G * r, d_in)                 # forward: grouped down-projection
-        for d_out, n in members:
-            g(T, d_out, r, n)             # forward: batched up-projections
-            g(T, r, d_out, n)             # backward: data gradient through the up-projections
-            g(d_out, r, T, n, 4)          # backward: weight gradient of the up-projections
-        g(T, d_in, G * r)                 # backward: data gradient through the down-projection
-        g(G * r, d_in, T, 1, 4)           # backward: weight gradient of the down-projection
-    for d_out, n in qkv + ((d, 1), (f, 2)):
-        g(T, d_out, r, n)                 # re-forward from the rank-r checkpoints (all but the last layer)
+    def up_qkv(what):                       # one batched launch, or q alone and {k, v} when k / v are narrower
+        if dkv == d:
+            g(what, 0, T, d, r, 3)
+        else:
+            g(what + " (q)", 0, T, d, r, 1)
+            g(what + " (k, v)", 0, T, dkv, r, 2)
+
+    def wg(what, M, N, m_log=None, n_log=None):      # weight gradient: reduces over the T tokens, fp32 result
+        g(what, 5, M, N, T, 1, outs=4.0 * (m_log or M) * (n_log or N), m_log=m_log, n_log=n_log)
+
+    Td = T * d
+    # ---- forward ----
+    g("fwd down q,k,v (grouped)", 1, T, 3 * r, d, outs=2 * 2.0 * T * 3 * r)          # z and sigma(z)
+    up_qkv("fwd up q,k,v (batched)")
+    g("fwd down o", 1, T, r, d, outs=2 * 2.0 * T * r)
+    g("fwd up o + x, sum h1^2", 10, T, d, r, aux=2.0 * Td, outs=2.0 * Td + 4.0 * Td)
+    g("fwd down gate,up (grouped)", 1, T, 2 * r, d, outs=2 * 2.0 * T * 2 * r)
+    g("up gate", 0, T, f_ld, r, n_log=f)
+    g("fwd up up-branch + SwiGLU", 7, T, f_ld, r, aux=2.0 * T * f, n_log=f)           # reads g, writes m only
+    g("fwd down d", 1, T, r, f_ld, outs=2 * 2.0 * T * r, k_log=f)
+    g("fwd up d + h1", 11, T, d, r, aux=4.0 * Td)
+    # ---- backward ----
+    wg("dW up d", d, r)
+    g("dz d", 3, T, r, d, aux=2.0 * T * r)
+    g("re-fwd up o + x", 2, T, d, r, aux=2.0 * Td)
+    g("up gate", 0, T, f_ld, r, n_log=f)
+    g("re-fwd up up-branch + SwiGLU", 7, T, f_ld, r, aux=2.0 * T * f, outs=2 * 2.0 * T * f, n_log=f)   # u and m
+    wg("dW down d", r, f_ld, n_log=f)
+    g("dm + SwiGLU backward", 6, T, f_ld, r, aux=2 * 2.0 * T * f, outs=2 * 2.0 * T * f, n_log=f)
+    wg("dW up gate", f_ld, r, m_log=f)
+    wg("dW up up-branch", f_ld, r, m_log=f)
+    g("dz gate,up (batched)", 3, T, r, f_ld, 2, aux=2 * 2.0 * T * r, k_log=f)
+    wg("dW down gate,up", 2 * r, d)
+    g("dh1 (RMSNorm-2 backward + dy)", 12, T, d, 2 * r, aux=2 * 2.0 * Td, outs=2.0 * Td + 4.0 * Td)
+    wg("dW up o", d, r)
+    g("dz o", 3, T, r, d, aux=2.0 * T * r)
+    up_qkv("re-fwd up q,k,v (batched)")
+    wg("dW down o", r, d)
+    g("dO", 0, T, d, r)
+    wg("dW up q", d, r)
+    wg("dW up k", dkv, r)
+    wg("dW up v", dkv, r)
+    if dkv == d:
+        g("dz q,k,v (batched)", 3, T, r, d, 3, aux=3 * 2.0 * T * r)
+    else:
+        g("dz q", 3, T, r, d, 1, aux=2.0 * T * r)
+        g("dz k,v (batched)", 3, T, r, dkv, 2, aux=2 * 2.0 * T * r)
+    wg("dW down q,k,v", 3 * r, d)
+    g("dx (RMSNorm-1 backward + dh1)", 13, T, d, 3 * r, aux=2.0 * Td + 4.0 * Td)
     return out
+
+
+def gemm_classes(B, S, d, H, f, r, dkv=None):
+    """(FLOPs, ideal bytes) of every projection-GEMM launch of a block step."""
+    return [(c["flops"], c["bytes"]) for c in gemm_launches(B, S, d, H, f, r, dkv)]
+
+
+def attainable_of(flops, nbytes):
+    """min(MFMA peak, arithmetic intensity x HBM peak) in TFLOP/s."""
+    return min(MFMA_BF16_PEAK_TFLOPS * 1e12, flops / nbytes * HBM_PEAK_GBS * 1e9) / 1e12
 
 
 def attainable_tflops(classes):
     """FLOP-weighted bound of the GEMM launches: each class at min(MFMA peak, A.I. x HBM peak)."""
-    t = 0.0
-    for fl, by in classes:
-        bound = min(MFMA_BF16_PEAK_TFLOPS * 1e12, fl / by * HBM_PEAK_GBS * 1e9)
-        t += fl / bound
+    t = sum(fl / (attainable_of(fl, by) * 1e12) for fl, by in classes)
     return sum(fl for fl, _ in classes) / t / 1e12
+
+
+def per_class_report(records, launches, steps):
+    """Joins the library's launch records (tag, M, N, K, batch, ms, flops) with the launch table: one line
+    per distinct (tag, M, N, K, batch), with the logical FLOPs of the table (the padded ffn axis does no
+    useful work), the measured average duration and the rate against the MFMA peak and against the class's
+    own bound."""
+    table = {}
+    for c in launches:
+        k = (c["tag"], c["M"], c["N"], c["K"], c["batch"])
+        e = table.setdefault(k, {"what": [], "flops": 0.0, "bytes": 0.0, "n": 0})
+        if c["what"] not in e["what"]:
+            e["what"].append(c["what"])
+        e["flops"] += c["flops"]; e["bytes"] += c["bytes"]; e["n"] += 1
+    meas = {}
+    for tag, M, N, K, batch, ms, fl in records:
+        if tag >= 32:
+            continue
+        m = meas.setdefault((tag, M, N, K, batch), [0, 0.0])
+        m[0] += 1; m[1] += ms
+    rows = []
+    for k, (n, ms) in sorted(meas.items(), key=lambda kv: -kv[1][1]):
+        t = table.get(k)
+        if t is None:      # a launch the table does not know (variant workloads): report it from the record alone
+            fl1, by1, what = 2.0 * k[1] * k[2] * k[3] * k[4], None, ["(not in the launch table)"]
+        else:
+            fl1, by1, what = t["flops"] / t["n"], t["bytes"] / t["n"], t["what"]
+        us = ms / n * 1e3
+        tf = fl1 / (us * 1e-6) / 1e12
+        row = {"class": TAG_NAMES.get(k[0], str(k[0])), "what": "; ".join(what), "tag": k[0], "M": k[1], "N": k[2],
+               "K": k[3], "batch": k[4], "launches_per_step": round(n / steps, 2), "avg_us": round(us, 1),
+               "ms_per_step": round(ms / steps, 3), "tflops": round(tf, 1), "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 3)}
+        if by1:
+            att = attainable_of(fl1, by1)
+            row["attainable"] = round(att, 1)
+            row["ideal_MB"] = round(by1 / 1e6, 1)
+        rows.append(row)
+    return rows
 
 
 def main():
@@ -201,34 +295,55 @@ def main():
     dt = (time.perf_counter() - t0) / max(args.steps, 1)
 
     fl = block_flops(Bn, S, d, H, f, r, dkv)
-    value = fl["exec"] / dt / 1e12
+    # headline: MODEL FLOPs over wall time (forward + backward of the block as defined; the re-forward from
+    # the rank-r checkpoints and the second attention forward are overhead of the method, not useful work);
+    # the executed-FLOPs rate is reported beside it
+    value = fl["model"] / dt / 1e12
+    value_exec = fl["exec"] / dt / 1e12
 
     # ---- roofline of the dominant kernel: gemm_bf16_kernel (all of the block's projection GEMMs,
     # forward, re-forward, data-gradient and weight-gradient launches).  The same K steps are run
     # again with the library's launch timer on: every GEMM launch is bracketed by HIP events on the
     # stream it runs on, and the summed intervals give the average launch duration.
     T = Bn * S
-    B.lr_gemm_timer_begin(64 * max(args.steps, 1) + 64)
+    B.lr_launch_timer_begin(80 * max(args.steps, 1) + 64)
     for _ in range(args.steps):
         step()
-    gemm_ms, gemm_launches = B.lr_gemm_timer_end()
-    launches_per_step = gemm_launches / max(args.steps, 1)
-    avg_launch_ms = gemm_ms / max(gemm_launches, 1)
+    records = B.lr_launch_timer_end()
+    gemm_recs = [r for r in records if r[0] < 32]
+    gemm_ms, gemm_launches_n = sum(r[5] for r in gemm_recs), len(gemm_recs)
+    launches_per_step = gemm_launches_n / max(args.steps, 1)
+    avg_launch_ms = gemm_ms / max(gemm_launches_n, 1)
     flops_per_launch = fl["gemm_exec"] / launches_per_step        # algorithmic FLOPs (2MNK) per launch
     achieved = flops_per_launch / (avg_launch_ms * 1e-3) / 1e12
-    classes = gemm_classes(Bn, S, d, H, f, r, dkv)
+    launches = gemm_launches(Bn, S, d, H, f, r, dkv, f_ld)
+    classes = [(c["flops"], c["bytes"]) for c in launches]
     assert abs(sum(c[0] for c in classes) - fl["gemm_exec"]) < 1e-6 * fl["gemm_exec"]
     attainable = attainable_tflops(classes)
     roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
                 "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(args.workload), "traffic_unit": "bytes per launch (offline counters)",
+                "algorithmic_bytes_per_launch": round(sum(c[1] for c in classes) / len(classes)),
                 # each launch class at min(MFMA peak, arithmetic intensity x HBM peak), FLOP-weighted: what
-                # the shapes of this workload allow (below the MFMA peak when the rank is small)
+                # the shapes of this workload allow (below the MFMA peak where an epilogue moves much data
+                # or the rank is small)
                 "attainable": round(attainable, 1), "frac_of_attainable": round(achieved / attainable, 4),
                 "kernel": "gemm_bf16_kernel (bf16 MFMA GEMM, all instantiations)",
                 "launches_per_step": round(launches_per_step, 1), "avg_launch_us": round(avg_launch_ms * 1e3, 2),
                 "gemm_ms_per_step": round(gemm_ms / max(args.steps, 1), 3),
-                "gflop_per_launch": round(flops_per_launch / 1e9, 2)}
+                "gflop_per_launch": round(flops_per_launch / 1e9, 2),
+                "per_class": per_class_report(records, launches, max(args.steps, 1))}
+    # attention beside it (not part of the GEMM figure): forward (run twice per step: forward and
+    # re-forward) and backward, FLOPs causal-halved, from the same event timer
+    attention = {}
+    for tag, name in ((B.LR_TAG_ATTN_FWD, "fwd"), (B.LR_TAG_ATTN_BWD, "bwd")):
+        rs = [r for r in records if r[0] == tag]
+        if rs:
+            us = sum(r[5] for r in rs) / len(rs) * 1e3
+            tf = rs[0][6] / (us * 1e-6) / 1e12
+            attention[name] = {"calls_per_step": round(len(rs) / max(args.steps, 1), 2), "avg_us": round(us, 1),
+                               "tflops": round(tf, 1), "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 3)}
+    attention["ms_per_step"] = round(sum(r[5] for r in records if r[0] >= 32) / max(args.steps, 1), 3)
     # What the matrix pipes of THIS box sustain from registers alone with pseudo-random operands (no
     # memory traffic at all; the chip lowers its clock under matrix load): the ceiling an ideal GEMM
     # kernel would reach here.  `frac` above stays against the published peak.
@@ -353,11 +468,14 @@ def main():
                                f"{', 8 key / value heads (grouped-query attention)' if variant == 'gqa8' else ''}, "
                                f"rank-r checkpoint recompute",
                    "launch": "hip graph replay" if args.graph else "eager",
-                   "tokens": T, "executed_tflop": round(fl["exec"] / 1e12, 3),
-                   "model_tflop": round(fl["model"] / 1e12, 3),
-                   "frac_mfma_peak_executed": round(value / MFMA_BF16_PEAK_TFLOPS, 4),
-                   "model_tflops": round(fl["model"] / dt / 1e12, 2)},
+                   "tokens": T, "value_counts": "model FLOPs (2MNK of forward + backward, attention causal-halved); "
+                                                "recompute not counted",
+                   "model_tflop": round(fl["model"] / 1e12, 3), "executed_tflop": round(fl["exec"] / 1e12, 3),
+                   "frac_mfma_peak_model": round(value / MFMA_BF16_PEAK_TFLOPS, 4),
+                   "executed_tflops": round(value_exec, 2),
+                   "frac_mfma_peak_executed": round(value_exec / MFMA_BF16_PEAK_TFLOPS, 4)},
         "roofline": roofline,
+        "attention": attention,
         "hbm_bound_kernels": stream,
     }
     if ablation is not None:

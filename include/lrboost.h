@@ -16,9 +16,12 @@
  *    accumulation is always fp32.  Per-token statistics are fp32 in either case.
  *  - LR_BF16 requires d_in, r, d_out and every leading dimension to be multiples of 8 and
  *    every pointer 16-byte aligned (LR_EALIGN otherwise).  T is arbitrary.
- *  - Return value: LR_OK or a negative lr_status.  Argument errors are detected before any
- *    launch, so a failed call has enqueued nothing.  Faults inside kernels surface at the
- *    caller's next synchronisation.  Outputs must not alias inputs.
+ *  - Return value: LR_OK or a negative lr_status.  Argument, alignment, workspace and
+ *    "unsupported" errors (everything but LR_ELAUNCH) are detected on the host before any launch,
+ *    so such a failed call has enqueued nothing.  LR_ELAUNCH reports that the runtime rejected a
+ *    kernel launch midway through a call's sequence: the kernels before it have been enqueued and
+ *    the outputs are then unspecified.  Faults inside kernels surface at the caller's next
+ *    synchronisation.  Outputs must not alias inputs.
  *  - Weight and gamma gradients are written in grad_dt: LR_F32 (fp32 main-gradient buffers, the
  *    usual companion of bf16 weights; always the case when dt == LR_F32) or LR_BF16 (pure bf16,
  *    App. "Low-rank Training Algorithm", costs one more rounding).  accumulate != 0 adds them
@@ -255,14 +258,28 @@ int lr_attention_gqa_bwd(const void* q, const void* k, const void* v, const void
                          int64_t hd, int causal, int dt, void* ws, size_t ws_bytes, void* stream);
 
 /* ---- measurement aid (not on the compute path) ------------------------------------------ */
-/* Between begin and end every bf16 MFMA GEMM launch the library makes is bracketed by two HIP
- * events on its stream; end waits for the last one and returns the summed kernel time (HOST
- * pointers: total_ms, launches).  begin creates max_launches event pairs and end destroys
- * them: the one place where the library creates runtime objects, and only on request.  Used
- * by the benchmark to obtain the average GEMM launch duration (Sec. 5.3 of the paper measures
- * the same quantity per linear layer: kernel time and utilisation).                        */
-int lr_gemm_timer_begin(int max_launches);
-int lr_gemm_timer_end(double* total_ms, int* launches);
+/* Between begin and end every bf16 MFMA GEMM launch the library makes, and each attention forward /
+ * backward call of the block, is bracketed by two HIP events on its stream.  end waits for the last one
+ * and writes one record per bracketed launch, in launch order, into records[0 .. max_records) (HOST
+ * memory; *n_records receives the number of launches seen, which may exceed max_records).  begin creates
+ * max_launches event pairs and end destroys them: the one place where the library creates runtime
+ * objects, and only on request.  Process-global and not thread-safe: one measuring thread, no compute
+ * calls from other threads meanwhile.  Used by the benchmark for the per-class GEMM and attention rates
+ * (Sec. 5.3 of the paper measures the same quantity per linear layer: kernel time and utilisation).
+ * tag: the GEMM's epilogue class (0 store, 1 down-projection: row scale + sigma, 2 / 10 / 11 up-projection
+ * + residual, 3 sigma' (+ row statistic), 4 / 12 / 13 RMSNorm backward, 5 split-K weight-gradient partial,
+ * 6 SwiGLU backward, 7 SwiGLU forward, 8 / 9 the LaX forms), or LR_TAG_ATTN_FWD / LR_TAG_ATTN_BWD.
+ * flops: 2 M N K batch for a GEMM; causal-halved 2 S^2 hd per (batch, head) and product for attention
+ * (2 products forward, 5 backward).                                                               */
+#define LR_TAG_ATTN_FWD 32
+#define LR_TAG_ATTN_BWD 33
+typedef struct {
+  int tag, M, N, K, batch;
+  float ms;
+  double flops;
+} lr_launch_record;
+int lr_launch_timer_begin(int max_launches);
+int lr_launch_timer_end(lr_launch_record* records, int max_records, int* n_records);
 /* Sustained rate of the bf16 matrix pipes fed from registers alone (no LDS, no memory traffic):
  * 2048 wavefronts, 8 independent 32x32x16 accumulator tiles each, iters instructions per tile and
  * launch, `launches` timed launches after up to 4 untimed ones, on `stream`; *tflops (HOST pointer)

@@ -83,8 +83,8 @@ _SIGS = {
     "lr_attention_gqa_bwd_workspace_bytes": (_sz, [_i64, _i64, _i64, _i64, _i64]),
     "lr_attention_gqa_bwd": (_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _i64, _i64,
                                     _int, _int, _vp, _sz, _vp]),
-    "lr_gemm_timer_begin": (_int, [_int]),
-    "lr_gemm_timer_end": (_int, [C.POINTER(C.c_double), C.POINTER(_int)]),
+    "lr_launch_timer_begin": (_int, [_int]),
+    "lr_launch_timer_end": (_int, [_vp, _int, C.POINTER(_int)]),
     "lr_mfma_probe": (_int, [_int, _int, _int, C.POINTER(C.c_double), _vp]),
     "lr_rms_stat": (_int, [_vp, _i64, _vp, _i64, _i64, _int, _vp]),
     "lr_rmsnorm_apply": (_int, [_vp, _i64, _vp, _vp, _f32, _vp, _i64, _i64, _i64, _int, _vp]),
@@ -415,15 +415,27 @@ def lr_attention_gqa_bwd(q, k, v, o, dout, lse, B, S, H, Hkv, hd, causal=True):
 
 
 # ---- measurement aid -----------------------------------------------------------------------
-def lr_gemm_timer_begin(max_launches=4096):
-    _check(lib().lr_gemm_timer_begin(max_launches), "lr_gemm_timer_begin")
+class LaunchRecord(C.Structure):
+    _fields_ = [("tag", _int), ("M", _int), ("N", _int), ("K", _int), ("batch", _int), ("ms", _f32),
+                ("flops", C.c_double)]
 
 
-def lr_gemm_timer_end():
-    """Returns (summed GEMM kernel time in ms, number of GEMM launches) since lr_gemm_timer_begin."""
-    ms, n = C.c_double(0.0), C.c_int(0)
-    _check(lib().lr_gemm_timer_end(C.byref(ms), C.byref(n)), "lr_gemm_timer_end")
-    return ms.value, n.value
+LR_TAG_ATTN_FWD, LR_TAG_ATTN_BWD = 32, 33
+_timer_cap = 0
+
+
+def lr_launch_timer_begin(max_launches=4096):
+    global _timer_cap
+    _check(lib().lr_launch_timer_begin(int(max_launches)), "lr_launch_timer_begin")
+    _timer_cap = int(max_launches)
+
+
+def lr_launch_timer_end():
+    """Returns the list of (tag, M, N, K, batch, ms, flops) of every bracketed launch since begin."""
+    buf = (LaunchRecord * _timer_cap)()
+    n = _int(0)
+    _check(lib().lr_launch_timer_end(C.cast(buf, _vp), _timer_cap, C.byref(n)), "lr_launch_timer_end")
+    return [(r.tag, r.M, r.N, r.K, r.batch, r.ms, r.flops) for r in buf[:min(n.value, _timer_cap)]]
 
 
 def lr_mfma_probe(random_operands=True, iters=20000, launches=20):

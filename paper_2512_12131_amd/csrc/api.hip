@@ -433,6 +433,9 @@ bool block_desc_ok(const lr_block_desc* ds, Blk& b, int* why) {
   return true;
 }
 
+// FLOPs of one S x S x hd product over all (batch, head) pairs, causal half counted
+double attn_unit_flops(const Blk& b) { return 2.0 * (double)b.B * b.H * (double)b.S * b.S * b.hd / 2.0; }
+
 // z = in . w_dn^T (no norm), act = sigma(z)
 // (LaX: act = z + h_prev, identity gate)
 void single_down(Ctx& c, const Blk& b, const void* in, int64_t K, const void* w_dn, void* z, void* act, int lax = 0,
@@ -560,8 +563,12 @@ void block_fwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x
   a.lax = lax; a.h_prev = lax ? lx->h_prev_qkv : nullptr;
   group_fwd_seq(c, a);
   if (b.rope_cos) rope_qk(c, b, qkv, 0);
-  LAUNCH(c, attention_gqa_fwd_bf16(qkv, (char*)qkv + (size_t)T * d * es, (char*)qkv + (size_t)T * (d + dkv) * es, o, lse,
-                                   d, dkv, (int)b.B, (int)b.S, (int)b.H, (int)b.Hkv, (int)b.hd, b.causal, c.st));
+  {
+    const int slot = c.dry ? -1 : launch_timer_open(LR_TAG_ATTN_FWD, (int)T, (int)d, (int)b.S, 1, attn_unit_flops(b) * 2.0, c.st);
+    LAUNCH(c, attention_gqa_fwd_bf16(qkv, (char*)qkv + (size_t)T * d * es, (char*)qkv + (size_t)T * (d + dkv) * es, o, lse,
+                                     d, dkv, (int)b.B, (int)b.S, (int)b.H, (int)b.Hkv, (int)b.hd, b.causal, c.st));
+    launch_timer_close(slot, c.st);
+  }
   single_down(c, b, o, d, p->w_dn_o, ck ? ck->z_o : nullptr, act, lax, lax ? lx->h_prev_o : nullptr);
   single_up(c, b, act, p->w_up_o, d, x, h1, ck ? ck->s2 : nullptr, h1f);   // h1 = x + ..., s2 = sum h1^2 from the epilogue
   // MLP side
@@ -650,8 +657,12 @@ void block_bwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x
   group_up_seq(c, a, act_g);
   if (b.rope_cos) rope_qk(c, b, qkv, 0);
   const void* q_ = qkv; const void* k_ = (char*)qkv + (size_t)T * d * es; const void* v_ = (char*)qkv + (size_t)T * (d + dkv) * es;
-  LAUNCH(c, attention_gqa_fwd_bf16(q_, k_, v_, o, lse, d, dkv, (int)b.B, (int)b.S, (int)b.H, (int)b.Hkv, (int)b.hd,
-                                   b.causal, c.st));
+  {
+    const int slot = c.dry ? -1 : launch_timer_open(LR_TAG_ATTN_FWD, (int)T, (int)d, (int)b.S, 1, attn_unit_flops(b) * 2.0, c.st);
+    LAUNCH(c, attention_gqa_fwd_bf16(q_, k_, v_, o, lse, d, dkv, (int)b.B, (int)b.S, (int)b.H, (int)b.Hkv, (int)b.hd,
+                                     b.causal, c.st));
+    launch_timer_close(slot, c.st);
+  }
   // down-O backward
   wgrad(c, dz1, r, (int)r, o, d, (int)d, T, g->w_dn_o, nullptr, nullptr, nullptr, accumulate);
   {
@@ -664,9 +675,12 @@ void block_bwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x
   {
     const size_t mk = c.mark();
     void* aws = c.take(attention_gqa_bwd_ws_bytes((int)b.B, (int)b.S, (int)b.H, (int)b.Hkv, (int)b.hd));
+    // five GEMM units (S, dP, dV, dK in one kernel, dQ over the stored score gradient) against the forward's two
+    const int slot = c.dry ? -1 : launch_timer_open(LR_TAG_ATTN_BWD, (int)T, (int)d, (int)b.S, 1, attn_unit_flops(b) * 5.0, c.st);
     LAUNCH(c, attention_gqa_bwd_bf16(q_, k_, v_, o, dout, lse, dqkv, (char*)dqkv + (size_t)T * d * es,
                                      (char*)dqkv + (size_t)T * (d + dkv) * es, d, dkv, (int)b.B, (int)b.S, (int)b.H,
                                      (int)b.Hkv, (int)b.hd, b.causal, aws, c.st));
+    launch_timer_close(slot, c.st);
     c.release(mk);
   }
   // back through the rotations of q and k: their transposes, on dq and dk
@@ -1055,9 +1069,9 @@ int lr_rope(void* x, int64_t ldx, const float* cos_tab, const float* sin_tab, in
 }
 
 // ---- measurement aid ---------------------------------------------------------------------------
-int lr_gemm_timer_begin(int max_launches) { return gemm_timer_begin(max_launches) == 0 ? LR_OK : LR_EINVAL; }
-int lr_gemm_timer_end(double* total_ms, int* launches) {
-  return gemm_timer_end(total_ms, launches) == 0 ? LR_OK : LR_EINVAL;
+int lr_launch_timer_begin(int max_launches) { return launch_timer_begin(max_launches) == 0 ? LR_OK : LR_EINVAL; }
+int lr_launch_timer_end(lr_launch_record* records, int max_records, int* n_records) {
+  return launch_timer_end(records, max_records, n_records) == 0 ? LR_OK : LR_EINVAL;
 }
 
 // ---- standalone memory-bound kernels ---------------------------------------------------------

@@ -93,9 +93,12 @@ hipError_t gemm_bf16_untimed(const GemmOp& op, hipStream_t st);
 // true when gemm_bf16 can run `op` with both operands k-major (no transposed copies needed)
 bool gemm_bf16_kmajor_ok(const GemmOp& op);
 hipError_t gemm_f32(const GemmOp& op, hipStream_t st);
-// Benchmark aid: time every bf16 GEMM launch between begin and end with HIP events on its stream.
-int gemm_timer_begin(int max_launches);
-int gemm_timer_end(double* total_ms, int* launches);
+// Benchmark aid: launches bracketed by HIP events on their stream (every gemm_bf16 launch, tagged with
+// its epilogue kind, and whatever the sequencing code opens and closes itself, tags >= LR_TAG_ATTN_FWD).
+int launch_timer_begin(int max_launches);
+int launch_timer_open(int tag, int M, int N, int K, int batch, double flops, hipStream_t st);   // -1: not recording
+void launch_timer_close(int slot, hipStream_t st);
+int launch_timer_end(lr_launch_record* out, int max_records, int* n_records);
 
 // ---- streaming kernels (stream_kernels.hip) ---------------------------------------------------
 hipError_t k_rms_stat(const void* x, int64_t ldx, float* stat, int64_t T, int64_t d, int dt, hipStream_t);

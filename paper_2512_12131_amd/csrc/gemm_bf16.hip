@@ -639,6 +639,10 @@ hipError_t dispatch(const GemmOp& op, hipStream_t st) {
   }
 }
 
+// (A 128x128 tile of four wavefronts needs 80 KB of LDS, so two workgroups share a CU and one's epilogue
+// could run under the other's main loop.  Measured on the 7B block it loses everywhere, 6-30 % per launch
+// class, the classes with tile-reading epilogues included: it moves twice the operand bytes per FLOP
+// through L2 and LDS, and that costs more than the overlap returns.)
 bool use_big_tile(int N) { return N > 128 && (N % 256 == 0 || N > 512); }
 
 }  // namespace
@@ -667,54 +671,80 @@ int gemm_bf16_pick_splitk(int M, int N, int K, int batch) {
   return best;
 }
 
-// ---- optional timing of the GEMM launches (for the benchmark's roofline figure) -----------------
-// When enabled, every gemm_bf16 launch is bracketed by two HIP events on the launch stream; the sum of
-// the bracketed intervals is the time the stream spent in these kernels.  Off by default; the events
-// are created by gemm_timer_begin and released by gemm_timer_end, never on the compute path.
+// ---- optional timing of launches (for the benchmark's roofline figures) --------------------------
+// When enabled, every gemm_bf16 launch (and whatever else the sequencing code brackets with
+// launch_timer_open / close) sits between two HIP events on its stream; the elapsed time between them is
+// the time the stream spent in that launch.  Off by default; the events are created by launch_timer_begin
+// and released when the session is read out, never on the compute path.  Process-global and not
+// thread-safe: a measurement aid for a single-threaded benchmark, not part of the compute contract.
 namespace {
-struct GemmTimer {
+struct LaunchTimer {
   bool on = false;
   std::vector<hipEvent_t> ev;
+  std::vector<lr_launch_record> rec;
   size_t used = 0;
 } g_timer;
+
+void timer_release() {
+  for (auto& e : g_timer.ev)
+    if (e) (void)hipEventDestroy(e);
+  g_timer.ev.clear();
+  g_timer.rec.clear();
+  g_timer.used = 0;
+  g_timer.on = false;
+}
 }  // namespace
 
-int gemm_timer_begin(int max_launches) {
+int launch_timer_begin(int max_launches) {
   if (g_timer.on || max_launches <= 0) return -1;
-  g_timer.ev.resize((size_t)max_launches * 2);
+  g_timer.ev.assign((size_t)max_launches * 2, nullptr);
   for (auto& e : g_timer.ev)
-    if (hipEventCreate(&e) != hipSuccess) return -1;
+    if (hipEventCreate(&e) != hipSuccess) {
+      e = nullptr;
+      timer_release();          // destroys the events created so far
+      return -1;
+    }
+  g_timer.rec.assign((size_t)max_launches, lr_launch_record{});
   g_timer.used = 0;
   g_timer.on = true;
   return 0;
 }
 
-int gemm_timer_end(double* total_ms, int* launches) {
+int launch_timer_open(int tag, int M, int N, int K, int batch, double flops, hipStream_t st) {
+  if (!g_timer.on || g_timer.used >= g_timer.rec.size()) return -1;
+  const int slot = (int)g_timer.used++;
+  lr_launch_record& r = g_timer.rec[slot];
+  r.tag = tag; r.M = M; r.N = N; r.K = K; r.batch = batch; r.flops = flops; r.ms = 0.f;
+  (void)hipEventRecord(g_timer.ev[2 * slot], st);
+  return slot;
+}
+
+void launch_timer_close(int slot, hipStream_t st) {
+  if (slot >= 0 && g_timer.on) (void)hipEventRecord(g_timer.ev[2 * slot + 1], st);
+}
+
+int launch_timer_end(lr_launch_record* out, int max_records, int* n_records) {
   if (!g_timer.on) return -1;
-  g_timer.on = false;
-  double sum = 0.0;
-  const size_t n = g_timer.used / 2;
+  const size_t n = g_timer.used;
   if (n > 0) (void)hipEventSynchronize(g_timer.ev[2 * n - 1]);
+  int w = 0;
   for (size_t i = 0; i < n; i++) {
     float ms = 0.f;
     (void)hipEventElapsedTime(&ms, g_timer.ev[2 * i], g_timer.ev[2 * i + 1]);
-    sum += ms;
+    g_timer.rec[i].ms = ms;
+    if (out && w < max_records) out[w++] = g_timer.rec[i];
   }
-  for (auto& e : g_timer.ev) (void)hipEventDestroy(e);
-  g_timer.ev.clear();
-  if (total_ms) *total_ms = sum;
-  if (launches) *launches = (int)n;
+  if (n_records) *n_records = (int)n;
+  timer_release();
   return 0;
 }
 
-
 hipError_t gemm_bf16(const GemmOp& op, hipStream_t st) {
-  if (!g_timer.on || g_timer.used + 2 > g_timer.ev.size() || op.M <= 0 || op.N <= 0 || op.batch <= 0)
-    return gemm_bf16_untimed(op, st);
-  (void)hipEventRecord(g_timer.ev[g_timer.used], st);
+  if (!g_timer.on || op.M <= 0 || op.N <= 0 || op.batch <= 0) return gemm_bf16_untimed(op, st);
+  const int tag = op.splitk > 1 ? (int)EPI_PARTIAL : op.epi.kind;
+  const int slot = launch_timer_open(tag, op.M, op.N, op.K, op.batch, 2.0 * op.M * op.N * (double)op.K * op.batch, st);
   hipError_t e = gemm_bf16_untimed(op, st);
-  (void)hipEventRecord(g_timer.ev[g_timer.used + 1], st);
-  g_timer.used += 2;
+  launch_timer_close(slot, st);
   return e;
 }
 

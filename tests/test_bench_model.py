@@ -43,5 +43,19 @@ def test_attainable_rate_is_capped_by_the_memory_side_only_for_small_ranks():
     w = bench.WORKLOADS
     full = bench.attainable_tflops(bench.gemm_classes(*w["block-7B"][:6]))
     thin = bench.attainable_tflops(bench.gemm_classes(*w["block-7B-r128"][:6]))
-    assert abs(full - bench.MFMA_BF16_PEAK_TFLOPS) < 1e-6
+    # at the full rank only three launches sit below the machine balance, all K = r products with wide
+    # epilogue traffic: SwiGLU backward (reads g, u, writes dg, du) and the two residual sums that carry the
+    # fp32 copy of the residual stream
+    assert 0.97 * bench.MFMA_BF16_PEAK_TFLOPS < full < bench.MFMA_BF16_PEAK_TFLOPS
+    below = [c for c in bench.gemm_launches(*w["block-7B"][:6]) if bench.attainable_of(c["flops"], c["bytes"]) < 2499.0]
+    assert sorted(c["tag"] for c in below) == [6, 10, 11]
     assert thin < 0.5 * bench.MFMA_BF16_PEAK_TFLOPS
+
+
+def test_launch_table_counts_32_launches_and_pads_only_the_ffn_axis():
+    Bn, S, d, H, f, r = bench.WORKLOADS["block-1B"][:6]
+    la = bench.gemm_launches(Bn, S, d, H, f, r, None, 5464)
+    assert len(la) == 32
+    assert sum(c["batch"] if c["tag"] == 0 and c["K"] == r and c["N"] == d else 0 for c in la) == 3 + 3 + 1
+    assert {c["N"] for c in la if c["what"] == "up gate"} == {5464}
+    assert all(c["flops"] == 2.0 * Bn * S * f * r for c in la if c["what"] == "up gate")
