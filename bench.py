@@ -213,9 +213,10 @@ def main():
                     help="skip the register-only MFMA rate measurement reported beside the roofline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--ablation", action="store_true",
-                    help="add an 'ablation' object: grouped / batched projections and the statistic taken "
-                         "inside the GEMM against their separate forms (Table 3's compute rows, Sec. 5.3), "
-                         "and the cost of the rank-r checkpoint recompute (Table 5), at 4096 and 16384 tokens")
+                    help="add an 'ablation' object: grouped / batched projections, fused SwiGLU and the norm "
+                         "statistic against their separate forms (Table 3's compute rows, Sec. 5.3) at 4096 and "
+                         "16384 tokens, and rank-r checkpointing against a backward that keeps every wide "
+                         "activation (Table 5: memory saved, time added)")
     ap.add_argument("--chain-stat", action="store_true",
                     help="time the block as a middle block of a stack: the sum of squares of x arrives from the block "
                          "below (ckpt s1 pre-filled) and the one of y is emitted from the epilogue of the last GEMM")
@@ -398,52 +399,121 @@ def main():
         def rnd(*shape, scale=1.0):
             return (torch.randn(shape, device=dev, generator=gen) * scale).to(torch.bfloat16)
 
-        for Ta in (4096, 16384):
+        def group_vs_separate(Ta, G, d_out):
+            """One concatenated down GEMM + one batched up launch (norm statistic inside) against G separate
+            low-rank layers behind standalone norm kernels, forward and backward."""
             xa = rnd(Ta, d)
             gam = torch.ones((d,), device=dev, dtype=torch.bfloat16)
-            wd_cat = rnd(3 * r, d, scale=d ** -0.5)
-            wu_st = rnd(3, d, r, scale=r ** -0.5)
-            dys = rnd(3, Ta, d)
-            # grouped down-projection + batched up-projections, statistic from the GEMM's A tiles
+            wd_cat = rnd(G * r, d, scale=d ** -0.5)
+            wu_st = rnd(G, d_out, r, scale=r ** -0.5)
+            dys = rnd(G, Ta, d_out)
             zc, st_, ys = B.lr_group_fwd(xa, gam, eps, B.LR_NORM_ONLINE, wd_cat, wu_st)
             t_gf = time_ms(lambda: B.lr_group_fwd(xa, gam, eps, B.LR_NORM_ONLINE, wd_cat, wu_st))
             t_gb = time_ms(lambda: B.lr_group_bwd(xa, gam, eps, B.LR_NORM_ONLINE, wd_cat, wu_st, zc, st_, dys))
-            # the same with the statistic from a separate pass over x
+            # the same with the statistic and the normalisation as passes of their own
             t_2f = time_ms(lambda: B.lr_group_fwd(xa, gam, eps, B.LR_NORM_TWO_PASS, wd_cat, wu_st))
-            # three separate low-rank layers on a pre-normalised input (norm kernels timed with them)
             stx = B.lr_rms_stat(xa)
             xh = B.lr_rmsnorm_apply(xa, gam, stx, eps)
-            zs = [B.lr_linear_fwd(xh, wd_cat[i * r:(i + 1) * r], wu_st[i])[0] for i in range(3)]
+            zs = [B.lr_linear_fwd(xh, wd_cat[i * r:(i + 1) * r], wu_st[i])[0] for i in range(G)]
 
             def sep_fwd():
                 s_ = B.lr_rms_stat(xa)
                 h_ = B.lr_rmsnorm_apply(xa, gam, s_, eps)
-                for i in range(3):
+                for i in range(G):
                     B.lr_linear_fwd(h_, wd_cat[i * r:(i + 1) * r], wu_st[i])
 
             def sep_bwd():
                 acc = None
-                for i in range(3):
+                for i in range(G):
                     dxi = B.lr_linear_bwd(xh, wd_cat[i * r:(i + 1) * r], wu_st[i], zs[i], dys[i])[0]
                     acc = dxi if acc is None else acc.add_(dxi)
                 B.lr_rmsnorm_bwd(xa, gam, stx, eps, acc)
 
             t_sf, t_sb = time_ms(sep_fwd), time_ms(sep_bwd)
-            out_abl[f"T={Ta}"] = {"grouped_fwd_ms": round(t_gf, 4), "grouped_bwd_ms": round(t_gb, 4),
-                                  "grouped_two_pass_stat_fwd_ms": round(t_2f, 4),
-                                  "separate_fwd_ms": round(t_sf, 4), "separate_bwd_ms": round(t_sb, 4),
-                                  "fwd_speedup": round(t_sf / t_gf, 3), "bwd_speedup": round(t_sb / t_gb, 3)}
-            del xa, wd_cat, wu_st, dys, zc, ys, xh, zs
-        # rank-r checkpointing: memory kept per block against every d- and d_ff-wide activation, and the
-        # time of the re-forward it costs (forward minus the four down-projections that are not redone:
-        # their outputs are the checkpoints)
-        t_fwd = time_ms(lambda: B.lr_block_fwd(desc, params, x, ckpt=ck, ws=ws, y=y))
-        t_bwd = time_ms(lambda: B.lr_block_bwd(desc, params, x, dy, ck, grads=grads, accumulate=False, ws=ws, dx=dx))
-        kept = 7 * T * r * 2 + 2 * T * 4
-        full = (T * d * 2) * 8 + (T * f * 2) * 3 + 7 * T * r * 2 * 2   # xhat1,q,k,v,o,h1,xhat2,(y) + g,u,m + z and sigma(z)
-        out_abl["checkpoint"] = {"block_fwd_ms": round(t_fwd, 4), "block_bwd_ms": round(t_bwd, 4),
-                                 "kept_MB": round(kept / 1e6, 1), "store_everything_MB": round(full / 1e6, 1),
-                                 "delta_mem_MB": round((full - kept) / 1e6, 1)}
+            return {"grouped_fwd_ms": round(t_gf, 4), "grouped_bwd_ms": round(t_gb, 4),
+                    "grouped_two_pass_norm_fwd_ms": round(t_2f, 4),
+                    "separate_fwd_ms": round(t_sf, 4), "separate_bwd_ms": round(t_sb, 4),
+                    "fwd_speedup": round(t_sf / t_gf, 3), "bwd_speedup": round(t_sb / t_gb, 3)}
+
+        def launch_rows(Ta, recs, nsteps):
+            """Table 3's compute rows taken launch by launch from the event timer of a block step at Ta tokens:
+            each fused / grouped / batched launch against the separate launches it replaces (all of them
+            launches this block really makes, at the same shapes)."""
+            acc = {}
+            for tag, M_, N_, K_, b_, ms, _ in recs:
+                a = acc.setdefault((tag, M_, N_, K_, b_), [0, 0.0])
+                a[0] += 1; a[1] += ms
+
+            def us(tag, N_, K_, b_=1):
+                n, ms = acc.get((tag, Ta, N_, K_, b_), (0, 0.0))
+                return ms / n * 1e3 if n else None
+
+            g = torch.randn((Ta, f_ld), device=dev, dtype=torch.bfloat16)
+            u = torch.randn((Ta, f_ld), device=dev, dtype=torch.bfloat16)
+            t_sf = time_ms(lambda: B.lr_swiglu_fwd(g, u)) * 1e3
+            t_sb = time_ms(lambda: B.lr_swiglu_bwd(g, u, g)) * 1e3
+            xs = torch.randn((Ta, d), device=dev, dtype=torch.bfloat16)
+            t_stat = time_ms(lambda: B.lr_rms_stat(xs)) * 1e3
+            rows = {}
+
+            def row(name, fused, parts):
+                if fused is None or any(p is None for p in parts):
+                    return
+                rows[name] = {"fused_us": round(fused, 1), "separate_us": round(sum(parts), 1),
+                              "speedup": round(sum(parts) / fused, 3)}
+
+            one_dn, one_up = us(1, r, d), us(0, d, r)           # a single down / up projection of the same shapes
+            row("down q,k,v: one concatenated GEMM vs 3", us(1, 3 * r, d), [one_dn] * 3)
+            row("down gate,up: one concatenated GEMM vs 2", us(1, 2 * r, d), [one_dn] * 2)
+            row("up q,k,v: one batched launch vs 3", us(0, d, r, 3), [one_up] * 3)
+            row("SwiGLU forward in the up-projection epilogue vs GEMM + streaming kernel", us(7, f_ld, r),
+                [us(0, f_ld, r), t_sf])
+            row("SwiGLU backward in the data-gradient epilogue vs GEMM + streaming kernel", us(6, f_ld, r),
+                [us(0, f_ld, r), t_sb])
+            up_plain, up_stat = us(2, d, r), us(10, d, r)
+            if up_plain and up_stat:
+                rows["sum of squares of h1: in the up-projection epilogue (with the fp32 copy of h1) vs a pass of its own"] = {
+                    "epilogue_extra_us": round(up_stat - up_plain, 1), "separate_pass_us": round(t_stat, 1)}
+            return rows
+
+        out_abl["launches T=%d" % T] = launch_rows(T, records, max(args.steps, 1))
+        for Ta in (4096, 16384):
+            out_abl[f"qkv group T={Ta}"] = group_vs_separate(Ta, 3, d)
+            out_abl[f"gate/up group T={Ta}"] = group_vs_separate(Ta, 2, f_ld)
+        if Bn > 1 and variant == "silu":
+            # the same block at one sequence (batch 1): the launch-by-launch rows where the GEMMs are smaller
+            desc1 = B.make_block_desc(1, S, d, H, 128, f, f_ld, r, eps=eps, act=act)
+            ck1 = B.alloc_block_ckpt(desc1, dev)
+            x1, dy1, y1, dx1 = x[:S].contiguous(), dy[:S].contiguous(), torch.empty_like(x[:S]), torch.empty_like(x[:S])
+            for _ in range(2):
+                B.lr_block_fwd(desc1, params, x1, ckpt=ck1, ws=ws, y=y1)
+                B.lr_block_bwd(desc1, params, x1, dy1, ck1, grads=grads, accumulate=False, ws=ws, dx=dx1)
+            B.lr_launch_timer_begin(80 * 4 + 64)
+            for _ in range(4):
+                B.lr_block_fwd(desc1, params, x1, ckpt=ck1, ws=ws, y=y1)
+                B.lr_block_bwd(desc1, params, x1, dy1, ck1, grads=grads, accumulate=False, ws=ws, dx=dx1)
+            out_abl["launches T=%d" % S] = launch_rows(S, B.lr_launch_timer_end(), 4)
+        # rank-r checkpointing against a backward that keeps every wide activation (Sec. 4.4, Table 5):
+        # memory saved, time added, and their ratio
+        if variant == "silu" or variant == "identity":
+            sv = B.alloc_block_saved(desc, dev)
+            ws2 = torch.empty(max(B.lib().lr_block_saved_workspace_bytes(desc, 0), B.lib().lr_block_saved_workspace_bytes(desc, 1)),
+                              dtype=torch.uint8, device=dev)
+            t_fwd = time_ms(lambda: B.lr_block_fwd(desc, params, x, ckpt=ck, ws=ws, y=y))
+            t_bwd = time_ms(lambda: B.lr_block_bwd(desc, params, x, dy, ck, grads=grads, accumulate=False, ws=ws, dx=dx))
+            t_fwd_s = time_ms(lambda: B.lr_block_fwd_save(desc, params, x, ckpt=ck, saved=sv, ws=ws2, y=y))
+            t_bwd_s = time_ms(lambda: B.lr_block_bwd_saved(desc, params, x, dy, ck, sv, grads=grads, accumulate=False,
+                                                           ws=ws2, dx=dx))
+            kept = sum(v.numel() * v.element_size() for v in ck.values())
+            wide = sum(v.numel() * v.element_size() for v in sv.values())
+            plus = (t_fwd + t_bwd) - (t_fwd_s + t_bwd_s)
+            out_abl["checkpoint"] = {"rank_r_fwd_ms": round(t_fwd, 4), "rank_r_bwd_ms": round(t_bwd, 4),
+                                     "store_all_fwd_ms": round(t_fwd_s, 4), "store_all_bwd_ms": round(t_bwd_s, 4),
+                                     "plus_time_ms": round(plus, 4), "plus_time_frac": round(plus / (t_fwd_s + t_bwd_s), 4),
+                                     "rank_r_checkpoints_MB": round(kept / 1e6, 1),
+                                     "wide_activations_MB": round(wide / 1e6, 1), "delta_mem_MB": round(wide / 1e6, 1),
+                                     "eff_ckpt_MB_per_ms": round(wide / 1e6 / plus, 1) if plus > 0 else None}
+            del sv, ws2
         ablation = out_abl
     else:
         ablation = None

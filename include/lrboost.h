@@ -189,6 +189,31 @@ int lr_block_bwd(const lr_block_desc* desc, const lr_block_params* params, const
                  const lr_block_params* grads, int accumulate, void* ws, size_t ws_bytes,
                  void* stream);
 
+/* ---- the block with every wide activation kept ---------------------------------------------
+ * The reference point of the checkpointing comparison (Sec. 4.4, Table 5: memory saved against time
+ * added by keeping only rank-r activations): lr_block_fwd_save also leaves every d-wide and ffn-wide
+ * activation of the forward in caller-owned buffers, and lr_block_bwd_saved reads them instead of
+ * re-forwarding from the rank-r checkpoints (which it still takes: sigma and sigma' are rebuilt from z at
+ * rank r).  Results equal those of lr_block_fwd / lr_block_bwd bit for bit (recomputed = stored).  Dense
+ * bf16 unless noted; the backward only reads them:
+ *   qkv  q [T, d], then k [T, d_kv], then v [T, d_kv], back to back (after the rotary embedding, if any)
+ *   o    [T, d]        lse  [batch, n_heads, seq] fp32        h1  [T, d]
+ *   gu   g [T, ffn_ld], then u [T, ffn_ld]                    m   [T, ffn_ld]
+ * 2.4 GB at the 7B shape (batch 4 x seq 4096) against 0.24 GB of rank-r checkpoints.                 */
+typedef struct {
+  void *qkv, *o;
+  float* lse;
+  void *h1, *gu, *m;
+} lr_block_saved;
+size_t lr_block_saved_workspace_bytes(const lr_block_desc* desc, int backward);
+int lr_block_fwd_save(const lr_block_desc* desc, const lr_block_params* params, const void* x,
+                      void* y, const lr_block_ckpt* ckpt, const lr_block_saved* saved, void* ws,
+                      size_t ws_bytes, void* stream);
+int lr_block_bwd_saved(const lr_block_desc* desc, const lr_block_params* params, const void* x,
+                       const void* dy, const lr_block_ckpt* ckpt, const lr_block_saved* saved,
+                       void* dx, const lr_block_params* grads, int accumulate, void* ws,
+                       size_t ws_bytes, void* stream);
+
 /* ---- the LaX variant of the block (App. "LaX variant (residual low-rank)") ----------------
  * Identity gate at rank r, and every bottleneck layer adds the rank-r activation h_{i-1} of the
  * same projection in the decoder layer below before its up-projection: y_i = B_i (h_i + h_{i-1}),

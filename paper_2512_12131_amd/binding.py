@@ -44,6 +44,10 @@ class BlockCkpt(C.Structure):
     _fields_ = [(n, _vp) for n in ("z_qkv", "z_o", "z_gu", "z_d", "s1", "s2")]
 
 
+class BlockSaved(C.Structure):
+    _fields_ = [(n, _vp) for n in ("qkv", "o", "lse", "h1", "gu", "m")]
+
+
 class BlockLax(C.Structure):
     _fields_ = [(k + "_" + n, _vp) for k in ("h_prev", "dz_next", "dh_prev") for n in ("qkv", "o", "gu", "d")]
 
@@ -70,6 +74,11 @@ _SIGS = {
                             _vp]),
     "lr_block_bwd": (_int, [C.POINTER(BlockDesc), C.POINTER(BlockParams), _vp, _vp, C.POINTER(BlockCkpt), _vp,
                             C.POINTER(BlockParams), _int, _vp, _sz, _vp]),
+    "lr_block_saved_workspace_bytes": (_sz, [C.POINTER(BlockDesc), _int]),
+    "lr_block_fwd_save": (_int, [C.POINTER(BlockDesc), C.POINTER(BlockParams), _vp, _vp, C.POINTER(BlockCkpt),
+                                 C.POINTER(BlockSaved), _vp, _sz, _vp]),
+    "lr_block_bwd_saved": (_int, [C.POINTER(BlockDesc), C.POINTER(BlockParams), _vp, _vp, C.POINTER(BlockCkpt),
+                                  C.POINTER(BlockSaved), _vp, C.POINTER(BlockParams), _int, _vp, _sz, _vp]),
     "lr_block_lax_fwd": (_int, [C.POINTER(BlockDesc), C.POINTER(BlockParams), _vp, _vp, C.POINTER(BlockCkpt),
                                 C.POINTER(BlockLax), _vp, _sz, _vp]),
     "lr_block_lax_bwd": (_int, [C.POINTER(BlockDesc), C.POINTER(BlockParams), _vp, _vp, C.POINTER(BlockCkpt), _vp,
@@ -314,6 +323,54 @@ def lr_block_bwd(desc, params: dict, x, dy, ckpt: dict, grads: dict = None, accu
     ps, cs, gs = _params_struct(params), _ckpt_struct(ckpt), _params_struct(grads)
     _check(lib().lr_block_bwd(C.byref(desc), C.byref(ps), _p(x), _p(dy), C.byref(cs), _p(dx), C.byref(gs),
                               int(accumulate), _p(ws), ws.numel(), _stream()), "lr_block_bwd")
+    return dx, grads
+
+
+# ---- block with every wide activation kept ---------------------------------------------------
+def alloc_block_saved(desc, device):
+    T, d, f = desc.batch * desc.seq, desc.d_model, desc.ffn_ld
+    dkv = (desc.n_kv_heads or desc.n_heads) * desc.head_dim
+    bf = torch.bfloat16
+    return {"qkv": torch.empty((T * (d + 2 * dkv),), dtype=bf, device=device),
+            "o": torch.empty((T, d), dtype=bf, device=device),
+            "lse": torch.empty((desc.batch, desc.n_heads, desc.seq), dtype=torch.float32, device=device),
+            "h1": torch.empty((T, d), dtype=bf, device=device),
+            "gu": torch.empty((2, T, f), dtype=bf, device=device),
+            "m": torch.empty((T, f), dtype=bf, device=device)}
+
+
+def _saved_struct(sv: dict):
+    return BlockSaved(*[C.c_void_p(sv[n].data_ptr()) for n, _ in BlockSaved._fields_])
+
+
+def lr_block_fwd_save(desc, params: dict, x, ckpt: dict = None, saved: dict = None, ws=None, y=None):
+    """Returns (y, ckpt, saved): the forward that also keeps every wide activation."""
+    ckpt = alloc_block_ckpt(desc, x.device) if ckpt is None else ckpt
+    saved = alloc_block_saved(desc, x.device) if saved is None else saved
+    y = torch.empty_like(x) if y is None else y
+    nb = lib().lr_block_saved_workspace_bytes(C.byref(desc), 0)
+    if nb == 0:
+        raise LrError("lr_block_saved_workspace_bytes: invalid or unsupported block descriptor")
+    ws = _ws(nb, x.device) if ws is None else ws
+    ps, cs, ss = _params_struct(params), _ckpt_struct(ckpt), _saved_struct(saved)
+    _check(lib().lr_block_fwd_save(C.byref(desc), C.byref(ps), _p(x), _p(y), C.byref(cs), C.byref(ss), _p(ws),
+                                   ws.numel(), _stream()), "lr_block_fwd_save")
+    return y, ckpt, saved
+
+
+def lr_block_bwd_saved(desc, params: dict, x, dy, ckpt: dict, saved: dict, grads: dict = None, accumulate=False,
+                       ws=None, dx=None):
+    """Returns (dx, grads): the backward that reads the kept activations instead of re-forwarding."""
+    if grads is None:
+        grads = {n: torch.empty_like(params[n], dtype=_tdt(desc.grad_dt)) for n in PARAM_NAMES}
+    dx = torch.empty_like(x) if dx is None else dx
+    nb = lib().lr_block_saved_workspace_bytes(C.byref(desc), 1)
+    if nb == 0:
+        raise LrError("lr_block_saved_workspace_bytes: invalid or unsupported block descriptor")
+    ws = _ws(nb, x.device) if ws is None else ws
+    ps, cs, gs, ss = _params_struct(params), _ckpt_struct(ckpt), _params_struct(grads), _saved_struct(saved)
+    _check(lib().lr_block_bwd_saved(C.byref(desc), C.byref(ps), _p(x), _p(dy), C.byref(cs), C.byref(ss), _p(dx),
+                                    C.byref(gs), int(accumulate), _p(ws), ws.numel(), _stream()), "lr_block_bwd_saved")
     return dx, grads
 
 

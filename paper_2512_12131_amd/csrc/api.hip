@@ -541,20 +541,23 @@ void rope_qk(Ctx& c, const Blk& b, void* qkv, int inverse) {
                            inverse, c.st));
 }
 
+// sv: optional; the wide activations then land in the caller's buffers (to be kept for a backward that
+// does not re-forward) instead of the workspace
 void block_fwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x, void* y, const lr_block_ckpt* ck,
-                   const lr_block_lax* lx = nullptr) {
+                   const lr_block_lax* lx = nullptr, const lr_block_saved* sv = nullptr) {
   const int lax = lx != nullptr;
   const size_t es = 2;
   const int64_t T = b.T, d = b.d, r = b.r, f = b.f;
   const int64_t dkv = b.dkv;
-  void* qkv = c.take((size_t)T * (d + 2 * dkv) * es);     // q [T, d], k [T, dkv], v [T, dkv]
-  void* o = c.take((size_t)T * d * es);
-  void* h1 = c.take((size_t)T * d * es);
+  void* qkv = sv ? sv->qkv : c.take((size_t)T * (d + 2 * dkv) * es);     // q [T, d], k [T, dkv], v [T, dkv]
+  void* o = sv ? sv->o : c.take((size_t)T * d * es);
+  void* h1 = sv ? sv->h1 : c.take((size_t)T * d * es);
   float* h1f = (float*)c.take((size_t)T * d * sizeof(float));   // h1 before rounding: the residual of y
-  float* lse = (float*)c.take((size_t)b.B * b.H * b.S * sizeof(float));
+  float* lse = sv ? sv->lse : (float*)c.take((size_t)b.B * b.H * b.S * sizeof(float));
   void* act = c.take((size_t)T * 3 * r * es);     // sigma(z) of whichever projection group is live
-  void* gg = c.take((size_t)T * f * es);
-  void* mm = c.take((size_t)T * f * es);
+  void* gg = sv ? sv->gu : c.take((size_t)T * f * es);
+  void* uu = sv ? (void*)((char*)sv->gu + (size_t)T * f * es) : nullptr;   // u itself is kept only when saving
+  void* mm = sv ? sv->m : c.take((size_t)T * f * es);
   // attention side
   GrpArgs a = qkv_group_args(b);
   a.x = x; a.gamma = p->gamma1; a.w_down_cat = p->w_dn_qkv; a.w_up_stack = p->w_up_qkv;
@@ -577,14 +580,16 @@ void block_fwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x
   m.z_cat = ck ? ck->z_gu : nullptr; m.stat = ck ? ck->s2 : nullptr; m.stat_ready = 1; m.act_out = act;
   m.lax = lax; m.h_prev = lax ? lx->h_prev_gu : nullptr;
   group_down_seq(c, m, act);
-  mlp_up_swiglu(c, b, p->w_up_gu, act, gg, nullptr, mm);
+  mlp_up_swiglu(c, b, p->w_up_gu, act, gg, uu, mm);
   single_down(c, b, mm, f, p->w_dn_d, ck ? ck->z_d : nullptr, act, lax, lax ? lx->h_prev_d : nullptr);
   single_up(c, b, act, p->w_up_d, d, nullptr, y, b.stat_y_out, nullptr, h1f);   // optionally sum y^2 for the block above
 }
 
+// sv: optional; the forward's wide activations as kept by the caller (read only): the re-forward of h1,
+// g, u, m, q, k, v, o and lse from the rank-r checkpoints is then skipped
 void block_bwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x, const void* dy,
                    const lr_block_ckpt* ck, void* dx, const lr_block_params* g, int accumulate,
-                   const lr_block_lax* lx = nullptr) {
+                   const lr_block_lax* lx = nullptr, const lr_block_saved* sv = nullptr) {
   const int lax = lx != nullptr;
   const lr_block_lax nlx{};
   if (!lx) lx = &nlx;
@@ -599,23 +604,27 @@ void block_bwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x
   void* act_o = c.take((size_t)T * r * es);
   void* act_g = c.take((size_t)T * 3 * r * es);   // sigma(z_gu), later sigma(z_qkv)
   void* dz1 = c.take((size_t)T * r * es);         // dz_d, later dz_o
-  void* h1 = c.take((size_t)T * d * es);
+  void* h1 = sv ? sv->h1 : c.take((size_t)T * d * es);
   void* dh1 = c.take((size_t)T * d * es);
   float* dh1f = (float*)c.take((size_t)T * d * sizeof(float));   // dh1 before rounding: the residual of dx
-  void* big = c.take((size_t)2 * T * f * es);     // g,u  (later q,k,v: needs 3*T*d <= 2*T*f checked below)
+  void* big = sv ? sv->gu : c.take((size_t)2 * T * f * es);     // g,u  (later q,k,v: needs 3*T*d <= 2*T*f checked below)
   void* big2 = c.take((size_t)2 * T * f * es);    // dg,du (later dq,dk,dv)
-  void* mm = c.take((size_t)T * f * es);          // m, later o and do
-  float* lse = (float*)c.take((size_t)b.B * b.H * b.S * sizeof(float));
+  void* mm = sv ? sv->m : c.take((size_t)T * f * es);          // m, later o and do
+  float* lse = sv ? sv->lse : (float*)c.take((size_t)b.B * b.H * b.S * sizeof(float));
   const int64_t dkv = b.dkv;
   void* qkv = big;
   void* dqkv = big2;
+  if (sv) qkv = sv->qkv;
   if (d + 2 * dkv > 2 * f) {  // unusual shapes: separate buffers
-    qkv = c.take((size_t)T * (d + 2 * dkv) * es);
+    if (!sv) qkv = c.take((size_t)T * (d + 2 * dkv) * es);
     dqkv = c.take((size_t)T * (d + 2 * dkv) * es);
   }
   void* o = mm;
   void* dout = nullptr;
-  if (2 * d > f) {
+  if (sv) {                   // the kept tensors are read only: dO gets a buffer of its own
+    o = sv->o;
+    dout = c.take((size_t)T * d * es);
+  } else if (2 * d > f) {
     o = c.take((size_t)T * d * es);
     dout = c.take((size_t)T * d * es);
   } else {
@@ -627,11 +636,11 @@ void block_bwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x
   single_up_bwd(c, b, dy, d, act_d, ck->z_d, p->w_up_d, g->w_up_d, dz1, accumulate, lax, lx->dz_next_d, lx->dh_prev_d);
   // re-forward from the rank-r checkpoints: h1, then g, u, m
   rebuild_act(c, b, ck->z_o, lx->h_prev_o, act_o, r, lax);
-  single_up(c, b, act_o, p->w_up_o, d, x, h1, nullptr);
+  if (!sv) single_up(c, b, act_o, p->w_up_o, d, x, h1, nullptr);
   rebuild_act(c, b, ck->z_gu, lx->h_prev_gu, act_g, 2 * r, lax);
   GrpArgs m = group_args(b, 2, f);
   m.x = h1; m.gamma = p->gamma2; m.w_down_cat = p->w_dn_gu; m.w_up_stack = p->w_up_gu; m.y_stack = big;
-  mlp_up_swiglu(c, b, p->w_up_gu, act_g, big, (char*)big + (size_t)T * f * es, mm);
+  if (!sv) mlp_up_swiglu(c, b, p->w_up_gu, act_g, big, (char*)big + (size_t)T * f * es, mm);
   // down-D backward: dW_dn_d = dz_d^T . m ; dm = dz_d . W_dn_d with the SwiGLU reverse fused in
   wgrad(c, dz1, r, (int)r, mm, f, (int)f, T, g->w_dn_d, nullptr, nullptr, nullptr, accumulate);
   {
@@ -654,10 +663,10 @@ void block_bwd_seq(Ctx& c, const Blk& b, const lr_block_params* p, const void* x
   rebuild_act(c, b, ck->z_qkv, lx->h_prev_qkv, act_g, 3 * r, lax);
   GrpArgs a = qkv_group_args(b);
   a.x = x; a.gamma = p->gamma1; a.w_down_cat = p->w_dn_qkv; a.w_up_stack = p->w_up_qkv; a.y_stack = qkv;
-  group_up_seq(c, a, act_g);
-  if (b.rope_cos) rope_qk(c, b, qkv, 0);
+  if (!sv) group_up_seq(c, a, act_g);
+  if (!sv && b.rope_cos) rope_qk(c, b, qkv, 0);
   const void* q_ = qkv; const void* k_ = (char*)qkv + (size_t)T * d * es; const void* v_ = (char*)qkv + (size_t)T * (d + dkv) * es;
-  {
+  if (!sv) {
     const int slot = c.dry ? -1 : launch_timer_open(LR_TAG_ATTN_FWD, (int)T, (int)d, (int)b.S, 1, attn_unit_flops(b) * 2.0, c.st);
     LAUNCH(c, attention_gqa_fwd_bf16(q_, k_, v_, o, lse, d, dkv, (int)b.B, (int)b.S, (int)b.H, (int)b.Hkv, (int)b.hd,
                                      b.causal, c.st));
@@ -940,6 +949,50 @@ int lr_block_bwd(const lr_block_desc* desc, const lr_block_params* params, const
   Ctx c; c.base = (char*)ws; c.cap = ws_bytes; c.dt = LR_BF16; c.gdt = b.gdt; c.st = (hipStream_t)stream;
   block_bwd_seq(c, b, params, x, dy, ckpt, dx, grads, accumulate);
   return c.err == hipErrorNotSupported ? LR_EUNSUPPORTED : status_of(c);
+}
+
+// ---- block with every wide activation kept (the store-everything reference of Sec. 4.4 / Table 5) ----
+size_t lr_block_saved_workspace_bytes(const lr_block_desc* desc, int backward) {
+  Blk b; int why;
+  if (!block_desc_ok(desc, b, &why)) return 0;
+  Ctx c; c.dry = true; c.dt = LR_BF16;
+  lr_block_params np{};
+  lr_block_saved nsv{};
+  if (backward) block_bwd_seq(c, b, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0, nullptr, &nsv);
+  else block_fwd_seq(c, b, &np, nullptr, nullptr, nullptr, nullptr, &nsv);
+  return c.peak + 256;
+}
+
+static int check_saved(const lr_block_saved* sv) {
+  if (!sv) return LR_EINVAL;
+  TRY(check_ptrs(LR_BF16, {sv->qkv, sv->o, sv->h1, sv->gu, sv->m}));
+  if (!sv->lse) return LR_EINVAL;
+  return LR_OK;
+}
+
+int lr_block_fwd_save(const lr_block_desc* desc, const lr_block_params* params, const void* x, void* y,
+                      const lr_block_ckpt* ckpt, const lr_block_saved* saved, void* ws, size_t ws_bytes, void* stream) {
+  Blk b; int why;
+  if (!block_desc_ok(desc, b, &why)) return why;
+  TRY(check_params(params)); TRY(check_ckpt(ckpt)); TRY(check_saved(saved));
+  TRY(check_ptrs(LR_BF16, {x, y}));
+  TRY(check_ws(ws, ws_bytes, lr_block_saved_workspace_bytes(desc, 0)));
+  Ctx c; c.base = (char*)ws; c.cap = ws_bytes; c.dt = LR_BF16; c.st = (hipStream_t)stream;
+  block_fwd_seq(c, b, params, x, y, ckpt, nullptr, saved);
+  return status_of(c);
+}
+
+int lr_block_bwd_saved(const lr_block_desc* desc, const lr_block_params* params, const void* x, const void* dy,
+                       const lr_block_ckpt* ckpt, const lr_block_saved* saved, void* dx, const lr_block_params* grads,
+                       int accumulate, void* ws, size_t ws_bytes, void* stream) {
+  Blk b; int why;
+  if (!block_desc_ok(desc, b, &why)) return why;
+  TRY(check_params(params)); TRY(check_params(grads)); TRY(check_ckpt(ckpt)); TRY(check_saved(saved));
+  TRY(check_ptrs(LR_BF16, {x, dy, dx}));
+  TRY(check_ws(ws, ws_bytes, lr_block_saved_workspace_bytes(desc, 1)));
+  Ctx c; c.base = (char*)ws; c.cap = ws_bytes; c.dt = LR_BF16; c.gdt = b.gdt; c.st = (hipStream_t)stream;
+  block_bwd_seq(c, b, params, x, dy, ckpt, dx, grads, accumulate, nullptr, saved);
+  return status_of(c);
 }
 
 // ---- block, LaX variant -------------------------------------------------------------------------
