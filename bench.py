@@ -29,6 +29,8 @@ WORKLOADS = {
     # one rank's share of the 7B block under bottleneck-aware tensor parallelism at TP = 8 (Sec. 4.1):
     # d, heads and d_ff divided by 8, the rank-r tensors whole; the all-reduces between chunks are not run
     "block-7B-btp8-shard": (4, 4096, 512, 4, 1376, 1024),
+    # the same at TP = 4, the degree the paper measures with (Sec. 5.1)
+    "block-7B-btp4-shard": (4, 4096, 1024, 8, 2752, 1024),
     # the other model sizes of the paper's configuration table (App. "Model configuration"; heads of
     # 128 here, the head counts follow from d_model), batch 4 x seq 4096 as in Sec. 5.1
     "block-3B": (4, 4096, 3072, 24, 8192, 768),

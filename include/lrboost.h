@@ -52,7 +52,16 @@ typedef enum { LR_ACT_IDENTITY = 0, LR_ACT_SILU = 1 } lr_act;
  * inside a GEMM, 1/rms applied as a per-row scale in the epilogue; single-GPU form of the
  * paper's Alg. 1).  LR_NORM_TWO_PASS: the unfused twin (statistic pass, normalise pass,
  * plain GEMM), i.e. what Alg. 1 falls back to (Sec. 4.5 "Configuration").               */
-typedef enum { LR_NORM_NONE = 0, LR_NORM_TWO_PASS = 1, LR_NORM_ONLINE = 2 } lr_norm;
+/* LR_NORM_SHARD_LOCAL (lr_group_fwd only): one tensor-parallel rank's part of Alg. 1, the steps
+ * before the exchange.  x[T, d_in] is the rank's slice of the features (d_in = d / TP), gamma its
+ * slice of the scale, w_down_cat[G*r, d_in] the matching columns of the weights.  The rank takes its
+ * local sum of squares, normalises its slice by its LOCAL rms, multiplies by its weight slice and
+ * undoes the local scale on the product: z_cat[T, G*r] receives that un-normalised partial product
+ * (to be summed over the ranks), stat[T] the local sum of squares (summed with it).  sigma, the
+ * up-projections and y come after the exchange: act, w_up_stack, y_stack, ldy, y_batch_stride and
+ * d_out are ignored (pass NULL / 0 / any positive d_out).  lr_online_rmsnorm_finish applies the
+ * global rescale to the summed product.  No backward form.                                  */
+typedef enum { LR_NORM_NONE = 0, LR_NORM_TWO_PASS = 1, LR_NORM_ONLINE = 2, LR_NORM_SHARD_LOCAL = 3 } lr_norm;
 
 int lr_version(void);
 /* Human-readable name of a status code; static storage, never freed. */
@@ -323,6 +332,13 @@ int lr_rms_stat(const void* x, int64_t ldx, float* stat, int64_t T, int64_t d, i
 int lr_rmsnorm_apply(const void* x, int64_t ldx, const void* gamma, const float* stat,
                      float eps, void* xhat, int64_t ldo, int64_t T, int64_t d, int dt,
                      void* stream);
+/* The steps of Alg. 1 after the exchange: z[t, j] = h_sum[t, j] / sqrt(stat_sum[t] / d_total + eps) for
+ * j < n, where h_sum[T, n] is the sum over the ranks of the partial products of LR_NORM_SHARD_LOCAL calls,
+ * stat_sum[T] (fp32) the sum of their local statistics and d_total the full feature width (Eq. 5: the
+ * result equals RMSNorm over the full width followed by the full projection).                  */
+int lr_online_rmsnorm_finish(const void* h_sum, int64_t ldh, const float* stat_sum, int64_t d_total,
+                             float eps, void* z, int64_t ldz, int64_t T, int64_t n, int dt,
+                             void* stream);
 /* Reverse mode of Eq. 4: dx = (dn - n*c)/rms [+ dres], dn = dxhat*gamma, n = x/rms,
  * c = mean_j(dn*n); dgamma_part[nparts, d] fp32 partial column sums of dxhat*n, where
  * nparts = lr_rmsnorm_bwd_parts(T) (the caller, or lr_colsum, adds them up).  dres may be

@@ -15,7 +15,7 @@ import torch
 
 LR_F32, LR_BF16 = 0, 1
 LR_ACT_IDENTITY, LR_ACT_SILU = 0, 1
-LR_NORM_NONE, LR_NORM_TWO_PASS, LR_NORM_ONLINE = 0, 1, 2
+LR_NORM_NONE, LR_NORM_TWO_PASS, LR_NORM_ONLINE, LR_NORM_SHARD_LOCAL = 0, 1, 2, 3
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liblrboost.so")
@@ -97,6 +97,7 @@ _SIGS = {
     "lr_mfma_probe": (_int, [_int, _int, _int, C.POINTER(C.c_double), _vp]),
     "lr_rms_stat": (_int, [_vp, _i64, _vp, _i64, _i64, _int, _vp]),
     "lr_rmsnorm_apply": (_int, [_vp, _i64, _vp, _vp, _f32, _vp, _i64, _i64, _i64, _int, _vp]),
+    "lr_online_rmsnorm_finish": (_int, [_vp, _i64, _vp, _i64, _f32, _vp, _i64, _i64, _i64, _int, _vp]),
     "lr_rmsnorm_bwd_parts": (_i64, [_i64]),
     "lr_rmsnorm_bwd": (_int, [_vp, _i64, _vp, _vp, _f32, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _i64, _int, _vp]),
     "lr_act_fwd": (_int, [_vp, _i64, _vp, _i64, _i64, _i64, _int, _int, _vp]),
@@ -516,6 +517,30 @@ def lr_rmsnorm_apply(x, gamma, stat, eps):
     _check(lib().lr_rmsnorm_apply(_p(x), _rowmajor(x), _p(gamma), _p(stat), eps, _p(out), d, T, d, _dt(x), _stream()),
            "lr_rmsnorm_apply")
     return out
+
+
+def lr_shard_down_fwd(x_shard, gamma_shard, eps, w_down_cat_shard):
+    """One rank's part of the feature-sharded grouped down-projection (lr_group_fwd with
+    LR_NORM_SHARD_LOCAL).  Returns (partial product [T, G*r], local sum of squares [T])."""
+    T, d_in = x_shard.shape
+    GR = w_down_cat_shard.shape[0]
+    dt = _dt(x_shard)
+    h = torch.empty((T, GR), dtype=x_shard.dtype, device=x_shard.device)
+    stat = torch.empty((T,), dtype=torch.float32, device=x_shard.device)
+    nb = lr_group_workspace_bytes(1, T, d_in, GR, 8, dt, 0)
+    ws = _ws(nb, x_shard.device)
+    _check(lib().lr_group_fwd(_p(x_shard), _rowmajor(x_shard), _p(gamma_shard), eps, LR_NORM_SHARD_LOCAL,
+                              _p(w_down_cat_shard), None, _p(h), _p(stat), None, 0, 0, 1, T, d_in, GR, 8, LR_ACT_IDENTITY,
+                              dt, _p(ws), nb, _stream()), "lr_group_fwd (shard-local)")
+    return h, stat
+
+
+def lr_online_rmsnorm_finish(h_sum, stat_sum, d_total, eps):
+    T, n = h_sum.shape
+    z = torch.empty_like(h_sum)
+    _check(lib().lr_online_rmsnorm_finish(_p(h_sum), _rowmajor(h_sum), _p(stat_sum), d_total, eps, _p(z), n, T, n,
+                                          _dt(h_sum), _stream()), "lr_online_rmsnorm_finish")
+    return z
 
 
 def lr_rmsnorm_bwd(x, gamma, stat, eps, dxhat, dres=None):

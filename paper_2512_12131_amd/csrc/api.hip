@@ -231,6 +231,19 @@ void group_down_seq(Ctx& c, const GrpArgs& a, void* act) {
     if (!a.stat_ready) LAUNCH(c, k_rms_stat(a.x, a.ldx, a.stat, a.T, a.d_in, c.dt, c.st));
     LAUNCH(c, k_rmsnorm_apply(a.x, a.ldx, a.gamma, a.stat, a.eps, xh, a.d_in, a.T, a.d_in, c.dt, c.st));
     dn.A = xh; dn.lda = a.d_in;
+  } else if (a.norm == LR_NORM_SHARD_LOCAL) {
+    // One rank's part of the feature-sharded form (Sec. 4.2, Alg. 1, the steps before the exchange): x is a
+    // [T, d_in] slice of the full input.  Local statistic, normalisation by the LOCAL rms (rounded to the
+    // storage type, as a rank would feed it to its GEMM), product with the rank's weight rows, and the local
+    // scale undone per row in the epilogue: z_cat receives the un-normalised partial product that the ranks
+    // add up, stat the local sum of squares that travels with it.  No activation, no up-projection: both
+    // come after the exchange and the global rescale.
+    void* xh = c.take((size_t)a.T * a.d_in * es);
+    LAUNCH(c, k_rms_stat(a.x, a.ldx, a.stat, a.T, a.d_in, c.dt, c.st));
+    LAUNCH(c, k_rmsnorm_apply(a.x, a.ldx, a.gamma, a.stat, a.eps, xh, a.d_in, a.T, a.d_in, c.dt, c.st));
+    dn.A = xh; dn.lda = a.d_in;
+    dn.epi.kind = EPI_DOWN; dn.epi.C2 = nullptr; dn.epi.R = nullptr;
+    dn.epi.use_rho = 1; dn.epi.rho_sqrt = 1; dn.epi.rowa = a.stat; dn.epi.inv_d = 1.f / (float)a.d_in; dn.epi.eps = a.eps;
   }
   gemm(c, dn);
 }
@@ -256,7 +269,7 @@ void group_fwd_seq(Ctx& c, const GrpArgs& a) {
   const size_t es = esize(c.dt);
   void* act = a.act_out ? a.act_out : c.take((size_t)a.T * a.G * a.r * es);
   group_down_seq(c, a, act);
-  group_up_seq(c, a, act);
+  if (a.norm != LR_NORM_SHARD_LOCAL) group_up_seq(c, a, act);
 }
 
 // Backward of the group.  `act` = sigma(z_cat) must already be in place.
@@ -828,7 +841,8 @@ size_t lr_group_workspace_bytes(int G, int64_t T, int64_t d_in, int64_t r, int64
   a.y_bs = T * d_out; a.lddy = d_out; a.dy_bs = T * d_out; a.lddx = d_in;
   size_t peak = 0;
   // take the larger of the norm variants so one query serves all of them
-  for (int norm : {LR_NORM_NONE, LR_NORM_TWO_PASS, LR_NORM_ONLINE}) {
+  for (int norm : {LR_NORM_NONE, LR_NORM_TWO_PASS, LR_NORM_ONLINE, LR_NORM_SHARD_LOCAL}) {
+    if (backward && norm == LR_NORM_SHARD_LOCAL) continue;
     c.off = 0; a.norm = norm;
     if (backward) group_bwd_full_seq(c, a); else group_fwd_seq(c, a);
     if (c.peak > peak) peak = c.peak;
@@ -841,15 +855,18 @@ int lr_group_fwd(const void* x, int64_t ldx, const void* gamma, float eps, int n
                  int G, int64_t T, int64_t d_in, int64_t r, int64_t d_out, int act, int dt, void* ws, size_t ws_bytes,
                  void* stream) {
   TRY(check_dt(dt)); TRY(check_act(act));
-  if (norm != LR_NORM_NONE && norm != LR_NORM_TWO_PASS && norm != LR_NORM_ONLINE) return LR_EINVAL;
+  const bool shard = norm == LR_NORM_SHARD_LOCAL;   // stops before the exchange: no up-projections, no y
+  if (norm != LR_NORM_NONE && norm != LR_NORM_TWO_PASS && norm != LR_NORM_ONLINE && !shard) return LR_EINVAL;
   if (G <= 0 || G > 64 || T < 0 || T > 0x7fffffffLL) return LR_EINVAL;
   TRY(check_sizes_fit_int({d_in, r, d_out}));
   if ((int64_t)G * r > 0x7fffffffLL) return LR_EINVAL;
-  if (ldx < d_in || ldy < d_out) return LR_EINVAL;
-  if (G > 1 && y_batch_stride < d_out) return LR_EINVAL;
-  TRY(check_dims_bf16(dt, {d_in, r, d_out, ldx, ldy, y_batch_stride}));
+  if (ldx < d_in || (!shard && ldy < d_out)) return LR_EINVAL;
+  if (!shard && G > 1 && y_batch_stride < d_out) return LR_EINVAL;
+  TRY(check_dims_bf16(dt, {d_in, r, ldx}));
+  if (!shard) TRY(check_dims_bf16(dt, {d_out, ldy, y_batch_stride}));
   if (T == 0) return LR_OK;
-  TRY(check_ptrs(dt, {x, w_down_cat, w_up_stack, z_cat, y_stack}));
+  TRY(check_ptrs(dt, {x, w_down_cat, z_cat}));
+  if (!shard) TRY(check_ptrs(dt, {w_up_stack, y_stack}));
   if (norm != LR_NORM_NONE) {
     TRY(check_ptrs(dt, {gamma}));
     if (!stat) return LR_EINVAL;
@@ -1144,6 +1161,17 @@ int lr_rmsnorm_apply(const void* x, int64_t ldx, const void* gamma, const float*
   TRY(check_ptrs(dt, {x, gamma, xhat}));
   return k_rmsnorm_apply(x, ldx, gamma, stat, eps, xhat, ldo, T, d, dt, (hipStream_t)stream) == hipSuccess ? LR_OK
                                                                                                         : LR_ELAUNCH;
+}
+
+int lr_online_rmsnorm_finish(const void* h_sum, int64_t ldh, const float* stat_sum, int64_t d_total, float eps,
+                             void* z, int64_t ldz, int64_t T, int64_t n, int dt, void* stream) {
+  TRY(check_dt(dt));
+  if (T < 0 || n <= 0 || d_total <= 0 || ldh < n || ldz < n || !stat_sum) return LR_EINVAL;
+  TRY(check_dims_bf16(dt, {n, ldh, ldz}));
+  if (T == 0) return LR_OK;
+  TRY(check_ptrs(dt, {h_sum, z}));
+  return k_row_rms_scale(h_sum, ldh, stat_sum, d_total, eps, z, ldz, T, n, dt, (hipStream_t)stream) == hipSuccess
+             ? LR_OK : LR_ELAUNCH;
 }
 
 int64_t lr_rmsnorm_bwd_parts(int64_t T) { return T > 0 ? k_rmsnorm_bwd_parts(T) : 0; }

@@ -842,12 +842,9 @@ hipError_t attention_gqa_fwd_bf16(const void* q, const void* k, const void* v, v
   if ((int64_t)S * ld * 2 >= (int64_t)0x7fffffff || (int64_t)S * ldkv * 2 >= (int64_t)0x7fffffff) return hipErrorNotSupported;
   constexpr int MB = 1;
   constexpr int BQ = 4 * MB * 32;
-  static bool once = false;
-  if (!once) {
-    hipError_t e = set_lds(attn_fwd_kernel<MB>, FWD_LDS);
-    if (e != hipSuccess) return e;
-    once = true;
-  }
+  // one-time opt-in to more than 64 KB of dynamic LDS (thread-safe static initialisation)
+  static const hipError_t attr_err = set_lds(attn_fwd_kernel<MB>, FWD_LDS);
+  if (attr_err != hipSuccess) return attr_err;
   const int nqb = (S + BQ - 1) / BQ;
   dim3 grid((nqb + 1) / 2, H, B);                        // each workgroup: one query block and its mirror
   hipLaunchKernelGGL(attn_fwd_kernel<MB>, grid, dim3(256), FWD_LDS, st, (const uint16_t*)q, (const uint16_t*)k,
@@ -890,16 +887,13 @@ hipError_t attention_gqa_bwd_bf16(const void* q, const void* k, const void* v, c
   const int grp = H / Hkv;
   // 32-bit buffer offsets per (batch, head)
   if ((int64_t)S * ld * 2 >= (int64_t)0x7fffffff || (int64_t)S * ldkv * 2 >= (int64_t)0x7fffffff) return hipErrorNotSupported;
-  static bool once = false;
-  if (!once) {
+  static const hipError_t attr_err = [] {
     hipError_t e = set_lds(attn_bwd_dq_kernel<DQ_MB>, DQ_LDS);
-    if (e != hipSuccess) return e;
-    e = set_lds(attn_bwd_dkv_kernel<DKV_NB, false>, DKV_LDS);
-    if (e != hipSuccess) return e;
-    e = set_lds(attn_bwd_dkv_kernel<DKV_NB, true>, DKV_LDS);
-    if (e != hipSuccess) return e;
-    once = true;
-  }
+    if (e == hipSuccess) e = set_lds(attn_bwd_dkv_kernel<DKV_NB, false>, DKV_LDS);
+    if (e == hipSuccess) e = set_lds(attn_bwd_dkv_kernel<DKV_NB, true>, DKV_LDS);
+    return e;
+  }();
+  if (attr_err != hipSuccess) return attr_err;
   float* D = (float*)ws;
   const int64_t items = (int64_t)B * S * H;
   float* lse2 = D + items;

@@ -46,6 +46,7 @@ struct Epilogue {
   int kind = EPI_STORE;
   int act = LR_ACT_IDENTITY;
   int use_rho = 0;            // multiply rows by rho_m
+  int rho_sqrt = 0;           // rho_m = sqrt(rowa/d + eps) instead of its reciprocal (un-scaling a local norm)
   int stat_from_a = 0;        // rowa is gathered from the A tiles in the main loop (bf16 kernel)
   const float* rowa = nullptr;  // [M] sum of squares
   const float* rowb = nullptr;  // [M]
@@ -104,6 +105,9 @@ int launch_timer_end(lr_launch_record* out, int max_records, int* n_records);
 hipError_t k_rms_stat(const void* x, int64_t ldx, float* stat, int64_t T, int64_t d, int dt, hipStream_t);
 hipError_t k_rmsnorm_apply(const void* x, int64_t ldx, const void* gamma, const float* stat, float eps,
                            void* xhat, int64_t ldo, int64_t T, int64_t d, int dt, hipStream_t);
+// out[t, j] = h[t, j] * rsqrt(stat[t] / d_total + eps), j < n  (the global rescale of a sharded projection)
+hipError_t k_row_rms_scale(const void* h, int64_t ldh, const float* stat, int64_t d_total, float eps, void* out,
+                           int64_t ldo, int64_t T, int64_t n, int dt, hipStream_t);
 int64_t k_rmsnorm_bwd_parts(int64_t T);
 hipError_t k_rmsnorm_bwd(const void* x, int64_t ldx, const void* gamma, const float* stat, float eps,
                          const void* dxhat, int64_t lddxh, const void* dres, int64_t lddres, void* dx,

@@ -164,6 +164,9 @@ __device__ __forceinline__ float epi_apply(const Epilogue& e, void* C, int64_t l
   return epi_compute<ST, NV, KIND>(e, C, ldc, sC, b, m, n, v, rho, rowb, r, r2);
 }
 
-__device__ __forceinline__ float rho_of(const Epilogue& e, float sumsq) { return rsqrtf(sumsq * e.inv_d + e.eps); }
+__device__ __forceinline__ float rho_of(const Epilogue& e, float sumsq) {
+  const float t = sumsq * e.inv_d + e.eps;
+  return e.rho_sqrt ? sqrtf(t) : rsqrtf(t);
+}
 
 }  // namespace lrb

@@ -471,6 +471,7 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
   const bool want2 = KIND == EPI_SWIGLU_BWD || KIND == EPI_SWIGLU_FWD || KIND == EPI_DOWN_LAX || KIND == EPI_LAXGRAD ||
                      (KIND == EPI_DOWN && e.C2 != nullptr);
   const bool use_rho = !PARTIAL && e.use_rho;
+  const bool rho_sqrt = e.rho_sqrt != 0;
   // row partials [M, rowpart_ld] and the statistic [M]: one lane per row writes, the others (and rows
   // past M) are given an out-of-range offset
   constexpr bool ROWPART = BASE == EPI_UP || BASE == EPI_ACTGRAD || BASE == EPI_LAXGRAD;
@@ -554,7 +555,7 @@ __global__ __launch_bounds__(T::NT) void gemm_bf16_kernel(GemmOp op, int kper, i
         float ss;
         if constexpr (STAT_A) ss = sStat[lm];
         else ss = ssv[q];
-        rho = rsqrtf(ss * inv_d + eps);
+        rho = rho_sqrt ? sqrtf(ss * inv_d + eps) : rsqrtf(ss * inv_d + eps);
       }
       if constexpr (BASE == EPI_NORMBWD) rowb = rbv[q];
       float r[8], r2[8], v2[8];

@@ -56,17 +56,21 @@ __global__ __launch_bounds__(256) void rms_stat_kernel(const void* x, int64_t ld
 template <int DT>
 __global__ __launch_bounds__(256) void rmsnorm_apply_kernel(const void* x, int64_t ldx, const void* gamma,
                                                             const float* stat, float eps, void* out, int64_t ldo,
-                                                            int64_t T, int64_t d) {
+                                                            int64_t T, int64_t d, int64_t d_div) {
+  // d: row width; d_div: the width the statistic was taken over (differs from d when the rows are the
+  // summed partial products of a feature-sharded projection); gamma may be null (no scale)
   using S = St<DT>;
   using IO = VecIO<typename S::T, S::NV>;
   const int lane = threadIdx.x & 63;
   const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= T) return;
-  const float rho = rsqrtf(stat[row] / (float)d + eps);
+  const float rho = rsqrtf(stat[row] / (float)d_div + eps);
   for (int64_t c = lane * S::NV; c < d; c += 64 * S::NV) {
     float v[S::NV], g[S::NV];
     IO::load(x, row * ldx + c, v);
-    IO::load(gamma, c, g);
+#pragma unroll
+    for (int i = 0; i < S::NV; i++) g[i] = 1.f;
+    if (gamma) IO::load(gamma, c, g);
 #pragma unroll
     for (int i = 0; i < S::NV; i++) v[i] = v[i] * g[i] * rho;
     IO::store(out, row * ldo + c, v);
@@ -729,7 +733,13 @@ hipError_t k_rms_stat(const void* x, int64_t ldx, float* stat, int64_t T, int64_
 hipError_t k_rmsnorm_apply(const void* x, int64_t ldx, const void* gamma, const float* stat, float eps, void* xhat,
                            int64_t ldo, int64_t T, int64_t d, int dt, hipStream_t st) {
   if (T <= 0) return hipSuccess;
-  DISPATCH_DT(dt, rmsnorm_apply_kernel, dim3((T + 3) / 4), dim3(256), st, x, ldx, gamma, stat, eps, xhat, ldo, T, d);
+  DISPATCH_DT(dt, rmsnorm_apply_kernel, dim3((T + 3) / 4), dim3(256), st, x, ldx, gamma, stat, eps, xhat, ldo, T, d, d);
+}
+hipError_t k_row_rms_scale(const void* h, int64_t ldh, const float* stat, int64_t d_total, float eps, void* out,
+                           int64_t ldo, int64_t T, int64_t n, int dt, hipStream_t st) {
+  if (T <= 0) return hipSuccess;
+  DISPATCH_DT(dt, rmsnorm_apply_kernel, dim3((T + 3) / 4), dim3(256), st, h, ldh, (const void*)nullptr, stat, eps, out, ldo,
+              T, n, d_total);
 }
 int64_t k_rmsnorm_bwd_parts(int64_t T) { return (T + NB_RB - 1) / NB_RB; }
 hipError_t k_rmsnorm_bwd(const void* x, int64_t ldx, const void* gamma, const float* stat, float eps,
@@ -737,13 +747,10 @@ hipError_t k_rmsnorm_bwd(const void* x, int64_t ldx, const void* gamma, const fl
                          float* dgamma_part, int64_t T, int64_t d, int dt, hipStream_t st) {
   if (T <= 0) return hipSuccess;
   if (dt == LR_BF16 && d <= 4096) {   // a row fits a wavefront's registers: single pass over every tensor
-    static bool attr_set = false;   // one-time opt-in to more than 64 KB of dynamic LDS
-    if (!attr_set) {
-      hipError_t err = hipFuncSetAttribute((const void*)rmsnorm_bwd_row_kernel<8>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, RN_ROW_LDS);
-      if (err != hipSuccess) return err;
-      attr_set = true;
-    }
+    // one-time opt-in to more than 64 KB of dynamic LDS (thread-safe static initialisation)
+    static const hipError_t attr_err = hipFuncSetAttribute((const void*)rmsnorm_bwd_row_kernel<8>,
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, RN_ROW_LDS);
+    if (attr_err != hipSuccess) return attr_err;
     hipLaunchKernelGGL(rmsnorm_bwd_row_kernel<8>, dim3(k_rmsnorm_bwd_parts(T)), dim3(256), RN_ROW_LDS, st,
                        (const uint16_t*)x, ldx, (const uint16_t*)gamma, stat, eps, (const uint16_t*)dxhat, lddxh,
                        (const uint16_t*)dres, lddres, (uint16_t*)dx, lddx, dgamma_part, T, d);

@@ -199,6 +199,11 @@ FULL = {
     "1B": (8, 2048, 2048, 16, 5461, 512),
     "7B": (4, 4096, 4096, 32, 11008, 1024),
     "7B-r128": (4, 4096, 4096, 32, 11008, 128),
+    # one rank's share of the 7B block under bottleneck-aware tensor parallelism (Sec. 4.1: d, heads and
+    # d_ff divided by TP, every rank-r tensor whole), all 16384 tokens, at TP = 8 and at the TP = 4 the
+    # paper measures with (Sec. 5.1)
+    "7B-btp8-shard": (4, 4096, 512, 4, 1376, 1024),
+    "7B-btp4-shard": (4, 4096, 1024, 8, 2752, 1024),
 }
 
 
