@@ -55,7 +55,7 @@ HBM_PEAK_GBS = 8000.0
 # FETCH_SIZE and WRITE_SIZE runs of this benchmark, each scaled by what the same counter reads for a
 # plain 1 GiB copy (x2.000 and x1.000): profiles/gemm_bf16_block-7B_hbm_traffic.txt.  Counters cannot
 # be read from inside this process, so workloads without such a measurement report null.
-MEASURED_GEMM_TRAFFIC_BYTES = {"block-7B": 708.7e6}
+MEASURED_GEMM_TRAFFIC_BYTES = {"block-7B": 733.0e6}
 
 
 def block_flops(B, S, d, H, f, r, dkv=None):
@@ -222,6 +222,9 @@ def main():
     ap.add_argument("--chain-stat", action="store_true",
                     help="time the block as a middle block of a stack: the sum of squares of x arrives from the block "
                          "below (ckpt s1 pre-filled) and the one of y is emitted from the epilogue of the last GEMM")
+    ap.add_argument("--vendor-gemm", action="store_true",
+                    help="context only: also time the vendor library's bf16 GEMM (torch.matmul -> hipBLASLt) on the "
+                         "block's projection shapes and report it beside the per-class rates; never on the product path")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run a plain device copy of this many MiB (3 times), so that a hardware-counter "
                          "run of this command can scale FETCH_SIZE / WRITE_SIZE by a kernel of known traffic")
@@ -519,6 +522,32 @@ def main():
         ablation = out_abl
     else:
         ablation = None
+
+    if args.vendor_gemm:
+        # What the vendor's tuned GEMM reaches on this machine for the same products with a plain store (no fused
+        # epilogue): context for the per-class figures, not a target the paper sets and not a path of this library.
+        vend = []
+        seen = set()
+        for c in launches:
+            key = (c["M"], c["N"], c["K"], c["tag"] == 5)
+            if key in seen:
+                continue
+            seen.add(key)
+            M_, N_, K_, tA = key
+            if tA:     # weight gradient: both operands token-major, reduced over tokens
+                a_ = torch.randn((K_, M_), device=dev, dtype=torch.bfloat16)
+                b_ = torch.randn((K_, N_), device=dev, dtype=torch.bfloat16)
+                fn = lambda: torch.matmul(a_.t(), b_)
+            else:
+                a_ = torch.randn((M_, K_), device=dev, dtype=torch.bfloat16)
+                b_ = torch.randn((N_, K_), device=dev, dtype=torch.bfloat16)
+                fn = lambda: torch.matmul(a_, b_.t())
+            t = time_ms(fn, reps=10)
+            tf = 2.0 * M_ * N_ * K_ / (t * 1e-3) / 1e12
+            vend.append({"M": M_, "N": N_, "K": K_, "reduce_over_tokens": tA, "us": round(t * 1e3, 1),
+                         "tflops": round(tf, 1), "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 3)})
+            del a_, b_
+        roofline["vendor_gemm_context"] = vend
 
     if args.calib_copy_mib > 0:
         src = torch.empty(args.calib_copy_mib << 20, dtype=torch.uint8, device=dev)

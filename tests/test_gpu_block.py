@@ -249,14 +249,14 @@ def test_block_full_shape_batch0(name):
     # ... and the full-batch gradients against the sum of the per-element ones (linearity)
     # The two sides are not bit-comparable: a sequence's tiles get a different k-walk start in the two
     # launches, the fp32 sum of squares then differs in the last bit, and a few bf16 roundings of z flip
-    # by one ulp and propagate.  So linearity is asserted in the L2 norm (rounding-flip noise is far
-    # below the 1e-2 bound of the oracle comparison); the max-norm difference is printed.
+    # by one ulp and propagate.  Both norms are asserted: such flips stay four orders below the parity bar
+    # (measured: max-norm <= 9e-6, L2 <= 7e-7 at the 1B and 7B shapes).
     bad = []
     for k in grads:
         a, s = grads[k].double(), acc[k].double()
         e = float((a - s).abs().max() / (s.pow(2).mean().sqrt() + 1e-300))
         l2 = float((a - s).norm() / (s.norm() + 1e-300))
         print(f"    linearity d{k}: l2 {l2:.3e}  max/rms {e:.3e}", flush=True)
-        if l2 >= 3e-3:
-            bad.append((k, l2))
+        if l2 >= 1e-5 or e >= 1e-4:
+            bad.append((k, l2, e))
     assert not bad, bad
