@@ -219,9 +219,11 @@ def main():
                          "statistic against their separate forms (Table 3's compute rows, Sec. 5.3) at 4096 and "
                          "16384 tokens, and rank-r checkpointing against a backward that keeps every wide "
                          "activation (Table 5: memory saved, time added)")
-    ap.add_argument("--chain-stat", action="store_true",
-                    help="time the block as a middle block of a stack: the sum of squares of x arrives from the block "
-                         "below (ckpt s1 pre-filled) and the one of y is emitted from the epilogue of the last GEMM")
+    ap.add_argument("--stat-pass", action="store_true",
+                    help="time the block as the bottom block of a stack: the sum of squares of x is taken by a pass "
+                         "over x (Alg. 1's first step on its own) and none is emitted for y.  Default: a middle "
+                         "block, whose statistic of x arrives from the epilogue of the block below (ckpt s1 "
+                         "pre-filled) and which emits the one of y from the epilogue of its last GEMM")
     ap.add_argument("--vendor-gemm", action="store_true",
                     help="context only: also time the vendor library's bf16 GEMM (torch.matmul -> hipBLASLt) on the "
                          "block's projection shapes and report it beside the per-class rates; never on the product path")
@@ -252,7 +254,7 @@ def main():
     if variant == "rope":
         ang = torch.arange(S, dtype=torch.float64)[:, None] * 10000.0 ** (-2.0 * torch.arange(64, dtype=torch.float64) / 128)
         rope = (torch.cos(ang).float().to(dev), torch.sin(ang).float().to(dev))
-    chain = args.chain_stat
+    chain = not args.stat_pass
     sy = torch.empty((Bn * S,), dtype=torch.float32, device=dev) if chain else None
     desc = B.make_block_desc(Bn, S, d, H, 128, f, f_ld, r, eps=eps, act=act, rope=rope, stat_x_ready=chain, stat_y_out=sy,
                              n_kv_heads=Hkv or 0)
@@ -299,6 +301,14 @@ def main():
         run()
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / max(args.steps, 1)
+    # the same steps once more with an event between consecutive steps: the fastest single step beside the mean
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    marks[0].record()
+    for i in range(args.steps):
+        run()
+        marks[i + 1].record()
+    torch.cuda.synchronize()
+    step_ms = [marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps)]
 
     fl = block_flops(Bn, S, d, H, f, r, dkv)
     # headline: MODEL FLOPs over wall time (forward + backward of the block as defined; the re-forward from
@@ -417,6 +427,10 @@ def main():
             t_gb = time_ms(lambda: B.lr_group_bwd(xa, gam, eps, B.LR_NORM_ONLINE, wd_cat, wu_st, zc, st_, dys))
             # the same with the statistic and the normalisation as passes of their own
             t_2f = time_ms(lambda: B.lr_group_fwd(xa, gam, eps, B.LR_NORM_TWO_PASS, wd_cat, wu_st))
+            # the statistic gathered from the A tiles inside the down-projection at this width (LR_NORM_ONLINE
+            # takes the pass over x once the output is wider than 512 columns), and that pass alone
+            t_ga = time_ms(lambda: B.lr_group_fwd(xa, gam, eps, B.LR_NORM_ONLINE_GATHER, wd_cat, wu_st))
+            t_st = time_ms(lambda: B.lr_rms_stat(xa))
             stx = B.lr_rms_stat(xa)
             xh = B.lr_rmsnorm_apply(xa, gam, stx, eps)
             zs = [B.lr_linear_fwd(xh, wd_cat[i * r:(i + 1) * r], wu_st[i])[0] for i in range(G)]
@@ -437,6 +451,7 @@ def main():
             t_sf, t_sb = time_ms(sep_fwd), time_ms(sep_bwd)
             return {"grouped_fwd_ms": round(t_gf, 4), "grouped_bwd_ms": round(t_gb, 4),
                     "grouped_two_pass_norm_fwd_ms": round(t_2f, 4),
+                    "grouped_fwd_statistic_gathered_in_gemm_ms": round(t_ga, 4), "statistic_pass_alone_ms": round(t_st, 4),
                     "separate_fwd_ms": round(t_sf, 4), "separate_bwd_ms": round(t_sb, 4),
                     "fwd_speedup": round(t_sf / t_gf, 3), "bwd_speedup": round(t_sb / t_gb, 3)}
 
@@ -560,7 +575,8 @@ def main():
     out = {
         "metric": "TFLOP/s + % MFMA bf16 peak, low-rank decoder block fwd+bwd (1 MI355X)",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(dt * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": round(dt * 1e3, 4), "ms_per_step_min": round(min(step_ms), 4) if step_ms else None,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: low-rank decoder block fwd+bwd, batch {Bn}, seq {S}, d_model {d}, "
                                f"{H} heads of 128, ffn {f}, rank {r}, sigma {'identity' if act == B.LR_ACT_IDENTITY else 'SiLU'}"
@@ -569,6 +585,10 @@ def main():
                                f"{', 8 key / value heads (grouped-query attention)' if variant == 'gqa8' else ''}, "
                                f"rank-r checkpoint recompute",
                    "launch": "hip graph replay" if args.graph else "eager",
+                   "norm1_statistic": ("handed over by the block below (stat_x_ready); this block emits the one of y from "
+                                       "the epilogue of its last GEMM" if chain else
+                                       "one pass over x (no GEMM of the block produces x); the one of h1 comes from the "
+                                       "epilogue of the GEMM that produces h1"),
                    "tokens": T, "value_counts": "model FLOPs (2MNK of forward + backward, attention causal-halved); "
                                                 "recompute not counted",
                    "model_tflop": round(fl["model"] / 1e12, 3), "executed_tflop": round(fl["exec"] / 1e12, 3),

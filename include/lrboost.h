@@ -52,6 +52,11 @@ typedef enum { LR_ACT_IDENTITY = 0, LR_ACT_SILU = 1 } lr_act;
  * inside a GEMM, 1/rms applied as a per-row scale in the epilogue; single-GPU form of the
  * paper's Alg. 1).  LR_NORM_TWO_PASS: the unfused twin (statistic pass, normalise pass,
  * plain GEMM), i.e. what Alg. 1 falls back to (Sec. 4.5 "Configuration").               */
+/* LR_NORM_ONLINE takes the sum of squares from the A tiles inside the down-projection while the
+ * output is at most 512 columns wide and from one pass over x (Alg. 1, its first step) beyond
+ * that, where the pass is the faster of the two.  LR_NORM_ONLINE_GATHER is the same computation
+ * with the in-GEMM gather at every width (bf16; fp32 storage takes the pass): no pass over x at
+ * all, at the price of every column tile repeating the gather.  Same outputs, same backward.  */
 /* LR_NORM_SHARD_LOCAL (lr_group_fwd only): one tensor-parallel rank's part of Alg. 1, the steps
  * before the exchange.  x[T, d_in] is the rank's slice of the features (d_in = d / TP), gamma its
  * slice of the scale, w_down_cat[G*r, d_in] the matching columns of the weights.  The rank takes its
@@ -61,7 +66,8 @@ typedef enum { LR_ACT_IDENTITY = 0, LR_ACT_SILU = 1 } lr_act;
  * up-projections and y come after the exchange: act, w_up_stack, y_stack, ldy, y_batch_stride and
  * d_out are ignored (pass NULL / 0 / any positive d_out).  lr_online_rmsnorm_finish applies the
  * global rescale to the summed product.  No backward form.                                  */
-typedef enum { LR_NORM_NONE = 0, LR_NORM_TWO_PASS = 1, LR_NORM_ONLINE = 2, LR_NORM_SHARD_LOCAL = 3 } lr_norm;
+typedef enum { LR_NORM_NONE = 0, LR_NORM_TWO_PASS = 1, LR_NORM_ONLINE = 2, LR_NORM_SHARD_LOCAL = 3,
+               LR_NORM_ONLINE_GATHER = 4 } lr_norm;
 
 int lr_version(void);
 /* Human-readable name of a status code; static storage, never freed. */
@@ -137,7 +143,7 @@ typedef struct {
   int64_t rank;
   float eps;
   int act;         /* lr_act at rank r                                                     */
-  int norm;        /* LR_NORM_ONLINE or LR_NORM_TWO_PASS                                   */
+  int norm;        /* LR_NORM_ONLINE, LR_NORM_ONLINE_GATHER or LR_NORM_TWO_PASS            */
   int dt;          /* LR_BF16                                                              */
   int grad_dt;     /* dtype of the weight / gamma gradient buffers: LR_F32 or LR_BF16      */
   int causal;      /* 1                                                                    */

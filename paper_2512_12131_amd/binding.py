@@ -15,7 +15,7 @@ import torch
 
 LR_F32, LR_BF16 = 0, 1
 LR_ACT_IDENTITY, LR_ACT_SILU = 0, 1
-LR_NORM_NONE, LR_NORM_TWO_PASS, LR_NORM_ONLINE, LR_NORM_SHARD_LOCAL = 0, 1, 2, 3
+LR_NORM_NONE, LR_NORM_TWO_PASS, LR_NORM_ONLINE, LR_NORM_SHARD_LOCAL, LR_NORM_ONLINE_GATHER = 0, 1, 2, 3, 4
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liblrboost.so")

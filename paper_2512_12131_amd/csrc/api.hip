@@ -209,18 +209,19 @@ void group_down_seq(Ctx& c, const GrpArgs& a, void* act) {
   dn.M = (int)a.T; dn.N = (int)GR; dn.K = (int)a.d_in;
   dn.epi.kind = EPI_DOWN; dn.epi.act = a.act; dn.epi.C2 = act; dn.epi.ldc2 = GR;
   if (a.lax) { dn.epi.kind = EPI_DOWN_LAX; dn.epi.R = a.h_prev; dn.epi.ldr = GR; }
-  if (a.norm == LR_NORM_ONLINE) {
+  if (a.norm == LR_NORM_ONLINE || a.norm == LR_NORM_ONLINE_GATHER) {
     void* wg = c.take((size_t)GR * a.d_in * es);   // w_down_cat with gamma folded into its columns
     LAUNCH(c, k_scale_cols(a.w_down_cat, a.gamma, wg, GR, a.d_in, c.dt, c.st));
     dn.B = wg;
     dn.epi.use_rho = 1; dn.epi.inv_d = 1.f / (float)a.d_in; dn.epi.eps = a.eps;
     if (a.stat_ready) {
       dn.epi.rowa = a.stat;
-    } else if (c.dt == LR_BF16 && GR <= 512) {
+    } else if (c.dt == LR_BF16 && (GR <= 512 || a.norm == LR_NORM_ONLINE_GATHER)) {
       // sum of squares gathered from the A tiles inside the GEMM.  Every column tile of a row panel
       // repeats the gather, so this pays only while the output is one or two tiles wide; beyond that a
       // separate pass over x (Alg. 1 line 1 as its own step) is faster (0.80 against 0.89 ms for the
-      // Q/K/V group of the 7B shape).
+      // Q/K/V group of the 7B shape), and LR_NORM_ONLINE takes it.  LR_NORM_ONLINE_GATHER asks for the
+      // gather at any width.
       dn.epi.stat_from_a = 1; dn.epi.stat_out = a.stat;
     } else {
       LAUNCH(c, k_rms_stat(a.x, a.ldx, a.stat, a.T, a.d_in, c.dt, c.st));
@@ -423,7 +424,7 @@ bool block_desc_ok(const lr_block_desc* ds, Blk& b, int* why) {
     return false;
   if (ds->n_heads * ds->head_dim != ds->d_model) return false;
   if (check_act(ds->act) != LR_OK) return false;
-  if (ds->norm != LR_NORM_ONLINE && ds->norm != LR_NORM_TWO_PASS) return false;
+  if (ds->norm != LR_NORM_ONLINE && ds->norm != LR_NORM_TWO_PASS && ds->norm != LR_NORM_ONLINE_GATHER) return false;
   if (ds->grad_dt != LR_F32 && ds->grad_dt != LR_BF16) return false;
   if (ds->batch * ds->seq > 0x7fffffffLL || ds->ffn_ld > 0x7fffffffLL || 3 * ds->rank > 0x7fffffffLL) return false;
   *why = LR_EUNSUPPORTED;
@@ -856,7 +857,8 @@ int lr_group_fwd(const void* x, int64_t ldx, const void* gamma, float eps, int n
                  void* stream) {
   TRY(check_dt(dt)); TRY(check_act(act));
   const bool shard = norm == LR_NORM_SHARD_LOCAL;   // stops before the exchange: no up-projections, no y
-  if (norm != LR_NORM_NONE && norm != LR_NORM_TWO_PASS && norm != LR_NORM_ONLINE && !shard) return LR_EINVAL;
+  if (norm != LR_NORM_NONE && norm != LR_NORM_TWO_PASS && norm != LR_NORM_ONLINE && norm != LR_NORM_ONLINE_GATHER && !shard)
+    return LR_EINVAL;
   if (G <= 0 || G > 64 || T < 0 || T > 0x7fffffffLL) return LR_EINVAL;
   TRY(check_sizes_fit_int({d_in, r, d_out}));
   if ((int64_t)G * r > 0x7fffffffLL) return LR_EINVAL;
@@ -887,7 +889,8 @@ int lr_group_bwd(const void* x, int64_t ldx, const void* gamma, float eps, int n
                  int G, int64_t T, int64_t d_in, int64_t r, int64_t d_out, int act, int dt, int grad_dt, int accumulate,
                  void* ws, size_t ws_bytes, void* stream) {
   TRY(check_dt(dt)); TRY(check_act(act)); TRY(check_gdt(dt, grad_dt));
-  if (norm != LR_NORM_NONE && norm != LR_NORM_TWO_PASS && norm != LR_NORM_ONLINE) return LR_EINVAL;
+  if (norm != LR_NORM_NONE && norm != LR_NORM_TWO_PASS && norm != LR_NORM_ONLINE && norm != LR_NORM_ONLINE_GATHER)
+    return LR_EINVAL;
   if (G <= 0 || G > 64 || T < 0 || T > 0x7fffffffLL) return LR_EINVAL;
   TRY(check_sizes_fit_int({d_in, r, d_out}));
   if ((int64_t)G * r > 0x7fffffffLL) return LR_EINVAL;

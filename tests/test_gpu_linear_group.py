@@ -73,7 +73,7 @@ GRP_CASES = [
 
 
 @pytest.mark.parametrize("T,d_in,r,d_out,G,dtype", GRP_CASES)
-@pytest.mark.parametrize("norm", [B.LR_NORM_ONLINE, B.LR_NORM_TWO_PASS, B.LR_NORM_NONE])
+@pytest.mark.parametrize("norm", [B.LR_NORM_ONLINE, B.LR_NORM_TWO_PASS, B.LR_NORM_NONE, B.LR_NORM_ONLINE_GATHER])
 def test_group_fwd_bwd(T, d_in, r, d_out, G, dtype, norm):
     print(f"group T={T} d_in={d_in} r={r} d_out={d_out} G={G} {dtype} norm={norm}", flush=True)
     eps = 1e-5
