@@ -11,7 +11,9 @@ from paper_2512_12131_amd import binding as B
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
-SHAPES = [(1, 8), (37, 72), (300, 1032), (1025, 4096)]
+# the last two: enough rows for the backward's row kernel to give a workgroup 128 and 192 rows (its partial
+# buffer then has rows that no workgroup owns), the second with a ragged last workgroup
+SHAPES = [(1, 8), (37, 72), (300, 1032), (1025, 4096), (32768, 128), (49160, 64)]
 
 
 @pytest.mark.parametrize("T,d", SHAPES)
