@@ -27,6 +27,31 @@ def test_library_exports_every_declared_symbol():
     assert lib.lr_version() >= 100
 
 
+def test_binding_constants_equal_the_headers():
+    """Every enumerator and numeric #define of the header that the binding also names has the header's value."""
+    text = open(os.path.join(ROOT, "include", "lrboost.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    header = {}
+    for body in re.findall(r"typedef\s+enum\s*\{(.*?)\}", text, flags=re.S):
+        nxt = 0
+        for item in body.split(","):
+            item = item.strip()
+            if not item:
+                continue
+            m = re.match(r"(LR_[A-Z0-9_]+)\s*(?:=\s*(-?\d+))?$", item)
+            assert m, item
+            nxt = int(m.group(2)) if m.group(2) is not None else nxt
+            header[m.group(1)] = nxt
+            nxt += 1
+    for name, val in re.findall(r"#define\s+(LR_[A-Z0-9_]+)\s+\(?(\d+)u?\)?\s*$", text, flags=re.M):
+        header[name] = int(val)
+    shared = [n for n in header if hasattr(B, n)]
+    assert {"LR_BF16", "LR_ACT_SILU", "LR_NORM_ONLINE", "LR_NORM_SHARD_LOCAL", "LR_NORM_ONLINE_GATHER",
+            "LR_TAG_ATTN_FWD", "LR_TAG_ATTN_BWD"} <= set(shared), sorted(shared)
+    for n in shared:
+        assert getattr(B, n) == header[n], (n, getattr(B, n), header[n])
+
+
 def test_status_strings():
     lib = B.lib()
     for code in (0, -1, -2, -3, -4, -5):
